@@ -1,0 +1,83 @@
+/*
+ * stage2bw_kernels.h -- C ABI of the single kernels the 2BW stage is made of, for parity tests
+ * and stand-alone roofline measurements.  Every pointer is a DEVICE pointer owned by the caller
+ * unless its name ends in _host; `stream` is a hipStream_t (NULL = null stream).  Calls only
+ * enqueue.  Return value: 0, or a negative STAGE_ERR_* code from stage2bw.h (INVALID_ARG when a
+ * shape or alignment the kernel assumes does not hold; nothing is launched then).
+ *
+ * dtype: 0 = fp32, 1 = bf16 (2-byte elements, fp32 accumulation and statistics).
+ * All row strides and contiguous extents must be multiples of 8 elements; base pointers 16-byte
+ * aligned.
+ *
+ * The operations are the steps of one transformer block's forward and reverse-mode gradient
+ * (the stage of Section 3.1 is a stack of such blocks; Section 5 names the models):
+ * projections with fused bias / residual / GELU, masked softmax attention, LayerNorm, the
+ * in-place coalescing of weight gradients (Section 3.1) and the Adam form of the delayed
+ * update W(t+1) = W(t) - nu * step(grad f(W(t-1))) (Section 3.1, Semantics).
+ */
+#ifndef STAGE2BW_KERNELS_H
+#define STAGE2BW_KERNELS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * C[M,N] = epilogue(sum_k A(m,k) B(k,n)),  A(m,k) = trans_a ? A[k*lda+m] : A[m*lda+k],
+ * B(k,n) = trans_b ? B[n*ldb+k] : B[k*ldb+n].
+ * epilogue 0: C = acc (+ bias[n]) (+ aux[m,n])            (forward projection, residual)
+ *          1: u = acc + bias[n]; C = u; aux_out = GELU(u)  (FC1)
+ *          2: C = acc * GELU'(aux[m,n])                     (data gradient through GELU)
+ *          3: C fp32: C = (accumulate ? C : 0) + acc        (weight gradient, coalesced in place)
+ * bf16 supports the pairs the stage issues: (trans_a,trans_b,epilogue) in
+ * {(0,0,0),(0,0,1),(0,1,0),(0,1,2),(1,0,3)}; fp32 supports all.
+ */
+int k2bw_gemm(int dtype, int trans_a, int trans_b, int epilogue, int M, int N, int K, const void* A,
+              int lda, const void* B, int ldb, void* C, int ldc, const void* bias, const void* aux,
+              void* aux_out, int accumulate, void* stream);
+
+/* y = gain*(x-mean)*rstd + shift per row of length h (biased variance, eps under the root);
+ * mean, rstd: fp32 [rows]. */
+int k2bw_layernorm_fwd(int dtype, int rows, int h, float eps, const void* x, const void* gain,
+                       const void* shift, void* y, float* mean, float* rstd, void* stream);
+
+/* Floats of workspace k2bw_layernorm_bwd needs for row length h. */
+int64_t k2bw_layernorm_bwd_workspace(int h);
+/* dx = (dres ? dres : 0) + LN'(dy); dgain_dshift: fp32 [2h] = (sum_r dy*xhat | sum_r dy),
+ * overwritten or added to according to accumulate. */
+int k2bw_layernorm_bwd(int dtype, int rows, int h, const void* dy, const void* x, const float* mean,
+                       const float* rstd, const void* gain, const void* dres, void* dx,
+                       float* dgain_dshift, int accumulate, float* workspace, void* stream);
+
+/* Floats of workspace k2bw_bias_grad needs for n columns. */
+int64_t k2bw_bias_grad_workspace(int n);
+/* out[n] (fp32) = (accumulate ? out : 0) + sum over rows of y[rows, n]. */
+int k2bw_bias_grad(int dtype, int rows, int n, const void* y, float* out, int accumulate,
+                   float* workspace, void* stream);
+
+/* qkv: [b*s, 3h] with columns Q|K|V, each head-major, h = a*dh; o: [b*s, h]; lse: fp32 [b,a,s].
+ * mask_mode 0 none, 1 causal (key j <= query i), 2 key padding (key j < seqlens[n]). */
+int k2bw_attention_fwd(int dtype, int b, int s, int a, int dh, int mask_mode, const int32_t* seqlens,
+                       const void* qkv, void* o, float* lse, void* stream);
+/* dqkv: [b*s, 3h]; delta: fp32 scratch [b,a,s]. */
+int k2bw_attention_bwd(int dtype, int b, int s, int a, int dh, int mask_mode, const int32_t* seqlens,
+                       const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
+                       float* delta, void* stream);
+
+/* One Adam step over n parameters (n multiple of 4) from the coalesced sum G, g = G/m_micro:
+ * moments updated in place; w_next = w_cur - lr*mhat/(sqrt(vhat)+eps) with bias correction for
+ * step `step` (>= 1).  w_next may equal w_cur.  w_next_bf16 (may be NULL) also receives the new
+ * weights rounded to bf16. */
+int k2bw_adam(int64_t n, const float* w_cur, float* w_next, void* w_next_bf16, float* m, float* v,
+              const float* G, float lr, float beta1, float beta2, float eps, int m_micro, int64_t step,
+              void* stream);
+
+/* Plain 16-byte copy (bytes multiple of 16): the reference kernel for scaling HBM counters. */
+int k2bw_copy(const void* in, void* out, int64_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STAGE2BW_KERNELS_H */

@@ -1,0 +1,102 @@
+// C ABI over the single kernels (see include/stage2bw_kernels.h): argument marshalling only.
+#include <cmath>
+
+#include "../../include/stage2bw.h"
+#include "../../include/stage2bw_kernels.h"
+#include "kernels.hpp"
+
+using namespace k2bw;
+
+namespace {
+int rc_of(hipError_t e) {
+  if (e == hipSuccess) return STAGE_OK;
+  if (e == hipErrorInvalidValue) return STAGE_ERR_INVALID_ARG;
+  if (e == hipErrorOutOfMemory) return STAGE_ERR_OOM;
+  return STAGE_ERR_HIP;
+}
+bool dtype_ok(int d) { return d == kF32 || d == kBF16; }
+}  // namespace
+
+extern "C" {
+
+int k2bw_gemm(int dtype, int trans_a, int trans_b, int epilogue, int M, int N, int K, const void* A, int lda,
+              const void* B, int ldb, void* C, int ldc, const void* bias, const void* aux, void* aux_out,
+              int accumulate, void* stream) {
+  if (!dtype_ok(dtype)) return STAGE_ERR_INVALID_ARG;
+  GemmDesc d;
+  d.dtype = dtype; d.trans_a = trans_a != 0; d.trans_b = trans_b != 0; d.epilogue = epilogue;
+  d.M = M; d.N = N; d.K = K; d.A = A; d.lda = lda; d.B = B; d.ldb = ldb; d.C = C; d.ldc = ldc;
+  d.bias = bias; d.aux = aux; d.aux_out = aux_out; d.accumulate = accumulate != 0;
+  return rc_of(gemm(d, static_cast<hipStream_t>(stream)));
+}
+
+int k2bw_layernorm_fwd(int dtype, int rows, int h, float eps, const void* x, const void* gain, const void* shift,
+                       void* y, float* mean, float* rstd, void* stream) {
+  if (!dtype_ok(dtype)) return STAGE_ERR_INVALID_ARG;
+  return rc_of(layernorm_fwd(x, gain, shift, y, mean, rstd, rows, h, eps, dtype, static_cast<hipStream_t>(stream)));
+}
+
+int64_t k2bw_layernorm_bwd_workspace(int h) {
+  if (h <= 0) return STAGE_ERR_INVALID_ARG;
+  return (int64_t)ln_bwd_max_parts() * 2 * h;
+}
+
+int k2bw_layernorm_bwd(int dtype, int rows, int h, const void* dy, const void* x, const float* mean,
+                       const float* rstd, const void* gain, const void* dres, void* dx, float* dgain_dshift,
+                       int accumulate, float* workspace, void* stream) {
+  if (!dtype_ok(dtype) || !dgain_dshift || !workspace) return STAGE_ERR_INVALID_ARG;
+  int parts = 0;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = layernorm_bwd(dy, x, mean, rstd, gain, dres, dx, workspace, &parts, rows, h, dtype, s);
+  if (e != hipSuccess) return rc_of(e);
+  return rc_of(colsum_finalize(workspace, parts, 2 * h, dgain_dshift, accumulate != 0, s));
+}
+
+int64_t k2bw_bias_grad_workspace(int n) {
+  if (n <= 0) return STAGE_ERR_INVALID_ARG;
+  return (int64_t)colsum_max_parts() * n;
+}
+
+int k2bw_bias_grad(int dtype, int rows, int n, const void* y, float* out, int accumulate, float* workspace,
+                   void* stream) {
+  if (!dtype_ok(dtype) || !out || !workspace) return STAGE_ERR_INVALID_ARG;
+  int parts = 0;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = colsum_partial(y, rows, n, n, workspace, &parts, dtype, s);
+  if (e != hipSuccess) return rc_of(e);
+  return rc_of(colsum_finalize(workspace, parts, n, out, accumulate != 0, s));
+}
+
+int k2bw_attention_fwd(int dtype, int b, int s, int a, int dh, int mask_mode, const int32_t* seqlens,
+                       const void* qkv, void* o, float* lse, void* stream) {
+  AttnDesc d;
+  d.b = b; d.s = s; d.a = a; d.dh = dh; d.mask_mode = mask_mode; d.seqlens = seqlens; d.dtype = dtype;
+  return rc_of(attention_fwd(d, qkv, o, lse, static_cast<hipStream_t>(stream)));
+}
+
+int k2bw_attention_bwd(int dtype, int b, int s, int a, int dh, int mask_mode, const int32_t* seqlens,
+                       const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta,
+                       void* stream) {
+  AttnDesc d;
+  d.b = b; d.s = s; d.a = a; d.dh = dh; d.mask_mode = mask_mode; d.seqlens = seqlens; d.dtype = dtype;
+  return rc_of(attention_bwd(d, qkv, o, lse, d_o, dqkv, delta, static_cast<hipStream_t>(stream)));
+}
+
+int k2bw_adam(int64_t n, const float* w_cur, float* w_next, void* w_next_bf16, float* m, float* v, const float* G,
+              float lr, float beta1, float beta2, float eps, int m_micro, int64_t step, void* stream) {
+  if (m_micro < 1 || step < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f))
+    return STAGE_ERR_INVALID_ARG;
+  AdamDesc d;
+  d.n = n; d.w_cur = w_cur; d.w_next = w_next; d.w_next_lp = static_cast<bf16_t*>(w_next_bf16);
+  d.m = m; d.v = v; d.G = G; d.lr = lr; d.beta1 = beta1; d.beta2 = beta2; d.eps = eps;
+  d.inv_m = 1.0f / (float)m_micro;
+  d.c1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)step)));
+  d.c2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)step)));
+  return rc_of(adam_step(d, static_cast<hipStream_t>(stream)));
+}
+
+int k2bw_copy(const void* in, void* out, int64_t bytes, void* stream) {
+  return rc_of(copy_bytes(in, out, bytes, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,343 @@
+// LayerNorm forward / backward and column-sum kernels (HBM-bound).
+//
+// A row of length h is handled by R threads (R = 64: one wavefront, 128 or 256: two or four
+// wavefronts of the 256-thread workgroup), each owning CPT chunks of 8 consecutive elements,
+// chunk index = sub + c*R, so that the R threads' 16-byte accesses are contiguous.  The row
+// stays in registers between the statistics and the normalisation: one read, one write.
+// Statistics are fp32: mean first, then the centred sum of squares (biased variance).
+#include "kernels.hpp"
+
+namespace k2bw {
+namespace {
+
+constexpr int kWg = 256;
+
+// sum over the R threads that share a row; R == 64 needs no LDS
+template <int R>
+__device__ __forceinline__ float group_sum(float v, float* red, int tid) {
+  v = wave_sum(v);
+  if (R == 64) return v;
+  constexpr int W = R / 64;           // waves per row
+  const int wave = tid >> 6;
+  __syncthreads();                    // red may still be read from the previous call
+  if ((tid & 63) == 0) red[wave] = v;
+  __syncthreads();
+  float s = 0.f;
+  const int first = (wave / W) * W;
+#pragma unroll
+  for (int i = 0; i < W; ++i) s += red[first + i];
+  return s;
+}
+
+template <typename T, int R, int CPT>
+__global__ __launch_bounds__(kWg) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gain,
+                                                      const T* __restrict__ shift, T* __restrict__ y,
+                                                      float* __restrict__ mean_out, float* __restrict__ rstd_out,
+                                                      int rows, int h, float eps) {
+  constexpr int ROWS = kWg / R;
+  __shared__ float red[4];
+  const int tid = threadIdx.x;
+  const int sub = tid % R;
+  const int row = blockIdx.x * ROWS + tid / R;
+  const bool row_ok = row < rows;
+  float v[CPT][8];
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) {
+    const int col = (sub + c * R) * 8;
+    if (row_ok && col < h) {
+      load8(x + (int64_t)row * h + col, v[c]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s += v[c][i];
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[c][i] = 0.f;
+    }
+  }
+  const float mean = group_sum<R>(s, red, tid) / (float)h;
+  float q = 0.f;
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) {
+    const int col = (sub + c * R) * 8;
+    if (col < h) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { const float d = v[c][i] - mean; q += d * d; }
+    }
+  }
+  const float var = group_sum<R>(q, red, tid) / (float)h;
+  const float rstd = 1.0f / sqrtf(var + eps);
+  if (!row_ok) return;
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) {
+    const int col = (sub + c * R) * 8;
+    if (col < h) {
+      float g[8], b[8], o[8];
+      load8(gain + col, g);
+      load8(shift + col, b);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = g[i] * ((v[c][i] - mean) * rstd) + b[i];
+      store8(y + (int64_t)row * h + col, o);
+    }
+  }
+  if (sub == 0) { mean_out[row] = mean; rstd_out[row] = rstd; }
+}
+
+// Backward.  Workgroups stride over row groups and keep per-column sums of dy*xhat and dy in
+// registers; each workgroup writes one row of partial[parts][2h] (first h: dy*xhat, then dy).
+template <typename T, int R, int CPT>
+__global__ __launch_bounds__(kWg) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                      const float* __restrict__ mean_in, const float* __restrict__ rstd_in,
+                                                      const T* __restrict__ gain, const T* __restrict__ dres,
+                                                      T* __restrict__ dx, float* __restrict__ partial, int rows, int h) {
+  constexpr int ROWS = kWg / R;
+  __shared__ float red[4];
+  __shared__ float comb[(ROWS > 1) ? (ROWS - 1) * R * CPT * 8 : 1];
+  const int tid = threadIdx.x;
+  const int sub = tid % R, rsub = tid / R;
+  float gsum[CPT][8], bsum[CPT][8], gn[CPT][8];
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) {
+    const int col = (sub + c * R) * 8;
+    if (col < h) load8(gain + col, gn[c]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { gsum[c][i] = 0.f; bsum[c][i] = 0.f; if (col >= h) gn[c][i] = 0.f; }
+  }
+  const int n_groups = (rows + ROWS - 1) / ROWS;
+  for (int grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
+    const int row = grp * ROWS + rsub;
+    const bool row_ok = row < rows;
+    const float mean = row_ok ? mean_in[row] : 0.f;
+    const float rstd = row_ok ? rstd_in[row] : 0.f;
+    float xh[CPT][8], dxh[CPT][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int col = (sub + c * R) * 8;
+      if (row_ok && col < h) {
+        float xv[8], dv[8];
+        load8(x + (int64_t)row * h + col, xv);
+        load8(dy + (int64_t)row * h + col, dv);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          xh[c][i] = (xv[i] - mean) * rstd;
+          dxh[c][i] = dv[i] * gn[c][i];
+          s1 += dxh[c][i];
+          s2 += dxh[c][i] * xh[c][i];
+          gsum[c][i] += dv[i] * xh[c][i];
+          bsum[c][i] += dv[i];
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { xh[c][i] = 0.f; dxh[c][i] = 0.f; }
+      }
+    }
+    const float c1 = group_sum<R>(s1, red, tid) / (float)h;
+    const float c2 = group_sum<R>(s2, red, tid) / (float)h;
+    if (row_ok) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int col = (sub + c * R) * 8;
+        if (col < h) {
+          float o[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) o[i] = rstd * (dxh[c][i] - c1 - xh[c][i] * c2);
+          if (dres) {
+            float r[8];
+            load8(dres + (int64_t)row * h + col, r);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] += r[i];
+          }
+          store8(dx + (int64_t)row * h + col, o);
+        }
+      }
+    }
+  }
+  // combine the ROWS sub-rows of this workgroup, then one partial row per workgroup
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    if (ROWS > 1) {
+      __syncthreads();
+      if (rsub > 0) {
+#pragma unroll
+        for (int c = 0; c < CPT; ++c)
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            comb[(((rsub - 1) * CPT + c) * 8 + i) * R + sub] = which ? bsum[c][i] : gsum[c][i];
+      }
+      __syncthreads();
+    }
+    if (rsub == 0) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int col = (sub + c * R) * 8;
+        if (col < h) {
+          float o[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            o[i] = which ? bsum[c][i] : gsum[c][i];
+            for (int rr = 1; rr < ROWS; ++rr) o[i] += comb[(((rr - 1) * CPT + c) * 8 + i) * R + sub];
+          }
+          store8(partial + (int64_t)blockIdx.x * 2 * h + which * h + col, o);
+        }
+      }
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kWg) void colsum_partial_kernel(const T* __restrict__ y, int rows, int n, int ld,
+                                                              float* __restrict__ partial, int rows_per_part) {
+  __shared__ float comb[7][8][32];
+  const int tid = threadIdx.x;
+  const int cc = tid % 32, rl = tid / 32;      // column chunk, row lane
+  const int col = (blockIdx.x * 32 + cc) * 8;
+  const int r0 = blockIdx.y * rows_per_part;
+  const int r1 = min(rows, r0 + rows_per_part);
+  float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (col < n) {
+    for (int r = r0 + rl; r < r1; r += 8) {
+      float v[8];
+      load8(y + (int64_t)r * ld + col, v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s[i] += v[i];
+    }
+  }
+  if (rl > 0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) comb[rl - 1][i][cc] = s[i];
+  }
+  __syncthreads();
+  if (rl == 0 && col < n) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int rr = 0; rr < 7; ++rr) s[i] += comb[rr][i][cc];
+    store8(partial + (int64_t)blockIdx.y * n + col, s);
+  }
+}
+
+__global__ __launch_bounds__(kWg) void colsum_finalize_kernel(const float* __restrict__ partial, int parts, int n,
+                                                               float* __restrict__ out, int accumulate) {
+  const int col = blockIdx.x * kWg + threadIdx.x;
+  if (col >= n) return;
+  float s = 0.f;
+  for (int p = 0; p < parts; ++p) s += partial[(int64_t)p * n + col];
+  out[col] = accumulate ? out[col] + s : s;
+}
+
+// R, CPT for a row length: the fewest threads per row that keep CPT <= 4, else up to 8.
+struct RowShape { int R, CPT; };
+RowShape row_shape(int h) {
+  const int chunks = h / 8;
+  for (int R : {64, 128, 256}) {
+    const int cpt = (chunks + R - 1) / R;
+    if (cpt <= 4) return {R, cpt};
+  }
+  return {256, (chunks + 255) / 256};
+}
+
+#define LN_DISPATCH(KERNEL_CALL)                                             \
+  switch (rs.R * 16 + rs.CPT) {                                              \
+    case 64 * 16 + 1: KERNEL_CALL(64, 1); break;                             \
+    case 64 * 16 + 2: KERNEL_CALL(64, 2); break;                             \
+    case 64 * 16 + 3: KERNEL_CALL(64, 3); break;                             \
+    case 64 * 16 + 4: KERNEL_CALL(64, 4); break;                             \
+    case 128 * 16 + 3: KERNEL_CALL(128, 3); break;                           \
+    case 128 * 16 + 4: KERNEL_CALL(128, 4); break;                           \
+    case 256 * 16 + 3: KERNEL_CALL(256, 3); break;                           \
+    case 256 * 16 + 4: KERNEL_CALL(256, 4); break;                           \
+    case 256 * 16 + 5: KERNEL_CALL(256, 5); break;                           \
+    case 256 * 16 + 6: KERNEL_CALL(256, 6); break;                           \
+    case 256 * 16 + 7: KERNEL_CALL(256, 7); break;                           \
+    case 256 * 16 + 8: KERNEL_CALL(256, 8); break;                           \
+    default: return hipErrorInvalidValue;                                    \
+  }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+
+hipError_t layernorm_fwd(const void* x, const void* gain, const void* shift, void* y, float* mean,
+                         float* rstd, int rows, int h, float eps, int dtype, hipStream_t stream) {
+  if (rows <= 0 || h <= 0 || h % 8 || h > 16384 || !x || !y || !gain || !shift || !mean || !rstd)
+    return hipErrorInvalidValue;
+  if (!aligned16(x) || !aligned16(y) || !aligned16(gain) || !aligned16(shift)) return hipErrorInvalidValue;
+  const RowShape rs = row_shape(h);
+  const int grid = ceil_div(rows, kWg / rs.R);
+#define CALL_FWD(R_, C_)                                                                                  \
+  if (dtype == kBF16)                                                                                     \
+    hipLaunchKernelGGL((ln_fwd_kernel<bf16_t, R_, C_>), dim3(grid), dim3(kWg), 0, stream,                 \
+                       static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(gain),                   \
+                       static_cast<const bf16_t*>(shift), static_cast<bf16_t*>(y), mean, rstd,            \
+                       rows, h, eps);                                                                     \
+  else                                                                                                    \
+    hipLaunchKernelGGL((ln_fwd_kernel<float, R_, C_>), dim3(grid), dim3(kWg), 0, stream,                  \
+                       static_cast<const float*>(x), static_cast<const float*>(gain),                     \
+                       static_cast<const float*>(shift), static_cast<float*>(y), mean, rstd,              \
+                       rows, h, eps)
+  LN_DISPATCH(CALL_FWD)
+#undef CALL_FWD
+  return hipGetLastError();
+}
+
+int ln_bwd_max_parts() { return 512; }
+
+hipError_t layernorm_bwd(const void* dy, const void* x, const float* mean, const float* rstd,
+                         const void* gain, const void* dres, void* dx, float* partial, int* parts_out,
+                         int rows, int h, int dtype, hipStream_t stream) {
+  if (rows <= 0 || h <= 0 || h % 8 || h > 16384 || !dy || !x || !mean || !rstd || !gain || !dx || !partial ||
+      !parts_out)
+    return hipErrorInvalidValue;
+  if (!aligned16(dy) || !aligned16(x) || !aligned16(dx) || !aligned16(gain) || !aligned16(partial) ||
+      (dres && !aligned16(dres)))
+    return hipErrorInvalidValue;
+  const RowShape rs = row_shape(h);
+  const int groups = ceil_div(rows, kWg / rs.R);
+  const int grid = groups < ln_bwd_max_parts() ? groups : ln_bwd_max_parts();
+#define CALL_BWD(R_, C_)                                                                                    \
+  if (dtype == kBF16)                                                                                       \
+    hipLaunchKernelGGL((ln_bwd_kernel<bf16_t, R_, C_>), dim3(grid), dim3(kWg), 0, stream,                   \
+                       static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(x), mean, rstd,           \
+                       static_cast<const bf16_t*>(gain),                                                    \
+                       static_cast<const bf16_t*>(dres), static_cast<bf16_t*>(dx), partial, rows, h);       \
+  else                                                                                                      \
+    hipLaunchKernelGGL((ln_bwd_kernel<float, R_, C_>), dim3(grid), dim3(kWg), 0, stream,                    \
+                       static_cast<const float*>(dy), static_cast<const float*>(x), mean, rstd,             \
+                       static_cast<const float*>(gain),                                                     \
+                       static_cast<const float*>(dres), static_cast<float*>(dx), partial, rows, h)
+  LN_DISPATCH(CALL_BWD)
+#undef CALL_BWD
+  *parts_out = grid;
+  return hipGetLastError();
+}
+
+int colsum_max_parts() { return 64; }
+
+hipError_t colsum_partial(const void* y, int rows, int n, int ldy, float* partial, int* parts_out, int dtype,
+                          hipStream_t stream) {
+  if (rows <= 0 || n <= 0 || n % 8 || ldy % 8 || ldy < n || !y || !partial || !parts_out) return hipErrorInvalidValue;
+  if (!aligned16(y) || !aligned16(partial)) return hipErrorInvalidValue;
+  int parts = ceil_div(rows, 64);
+  if (parts > colsum_max_parts()) parts = colsum_max_parts();
+  const int rows_per_part = ceil_div(rows, parts);
+  parts = ceil_div(rows, rows_per_part);
+  dim3 grid(ceil_div(n, 256), parts);
+  if (dtype == kBF16)
+    hipLaunchKernelGGL((colsum_partial_kernel<bf16_t>), grid, dim3(kWg), 0, stream, static_cast<const bf16_t*>(y),
+                       rows, n, ldy, partial, rows_per_part);
+  else
+    hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, dim3(kWg), 0, stream, static_cast<const float*>(y),
+                       rows, n, ldy, partial, rows_per_part);
+  *parts_out = parts;
+  return hipGetLastError();
+}
+
+hipError_t colsum_finalize(const float* partial, int parts, int n, float* out, bool accumulate,
+                           hipStream_t stream) {
+  if (parts <= 0 || n <= 0 || !partial || !out) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(colsum_finalize_kernel, dim3(ceil_div(n, kWg)), dim3(kWg), 0, stream, partial, parts, n, out,
+                     accumulate ? 1 : 0);
+  return hipGetLastError();
+}
+
+}  // namespace k2bw

@@ -1,0 +1,106 @@
+// Fused coalesce + Adam update writing the other weight buffer, and dtype conversions.
+// HBM-bound: 16-byte accesses, grid-stride, every byte touched once.
+//   fp32 mode: read W(t), m, v, G (16 B/param); write W(t+1), m, v (12 B/param).
+//   bf16 mode: read master, m, v, G (16 B); write master, m, v, bf16 W(t+1) (14 B).
+#include "kernels.hpp"
+
+namespace k2bw {
+namespace {
+
+template <bool LP>
+__global__ __launch_bounds__(256) void adam_kernel(AdamDesc d) {
+  const int64_t n4 = d.n / 4;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const float omb1 = 1.0f - d.beta1, omb2 = 1.0f - d.beta2;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    const float4 w = reinterpret_cast<const float4*>(d.w_cur)[i];
+    float4 m = reinterpret_cast<const float4*>(d.m)[i];
+    float4 v = reinterpret_cast<const float4*>(d.v)[i];
+    const float4 gs = reinterpret_cast<const float4*>(d.G)[i];
+    float wv[4] = {w.x, w.y, w.z, w.w}, mv[4] = {m.x, m.y, m.z, m.w}, vv[4] = {v.x, v.y, v.z, v.w};
+    const float gv[4] = {gs.x, gs.y, gs.z, gs.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float g = gv[k] * d.inv_m;
+      mv[k] = d.beta1 * mv[k] + omb1 * g;
+      vv[k] = d.beta2 * vv[k] + omb2 * g * g;
+      wv[k] = wv[k] - d.lr * (mv[k] * d.c1) / (sqrtf(vv[k] * d.c2) + d.eps);
+    }
+    reinterpret_cast<float4*>(d.m)[i] = make_float4(mv[0], mv[1], mv[2], mv[3]);
+    reinterpret_cast<float4*>(d.v)[i] = make_float4(vv[0], vv[1], vv[2], vv[3]);
+    reinterpret_cast<float4*>(d.w_next)[i] = make_float4(wv[0], wv[1], wv[2], wv[3]);
+    if (LP) reinterpret_cast<uint2*>(d.w_next_lp)[i] = make_uint2(pack_bf16x2(wv[0], wv[1]), pack_bf16x2(wv[2], wv[3]));
+  }
+}
+
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ in, bf16_t* __restrict__ out,
+                                                           int64_t n4) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    const float4 a = reinterpret_cast<const float4*>(in)[i];
+    reinterpret_cast<uint2*>(out)[i] = make_uint2(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w));
+  }
+}
+
+__global__ __launch_bounds__(256) void bf16_to_f32_kernel(const bf16_t* __restrict__ in, float* __restrict__ out,
+                                                           int64_t n4) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    const uint2 a = reinterpret_cast<const uint2*>(in)[i];
+    reinterpret_cast<float4*>(out)[i] =
+        make_float4(__uint_as_float(a.x << 16), __uint_as_float(a.x & 0xffff0000u), __uint_as_float(a.y << 16),
+                    __uint_as_float(a.y & 0xffff0000u));
+  }
+}
+
+__global__ __launch_bounds__(256) void copy16_kernel(const uint4* __restrict__ in, uint4* __restrict__ out, int64_t n16) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) out[i] = in[i];
+}
+
+int stream_grid(int64_t items) {
+  // enough workgroups to cover 256 CUs several times over, capped so the grid-stride loop does the rest
+  int64_t g = (items + 255) / 256;
+  if (g > 256 * 16) g = 256 * 16;
+  if (g < 1) g = 1;
+  return static_cast<int>(g);
+}
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+
+hipError_t adam_step(const AdamDesc& d, hipStream_t stream) {
+  if (d.n <= 0 || d.n % 4 || !d.w_cur || !d.w_next || !d.m || !d.v || !d.G) return hipErrorInvalidValue;
+  if (!aligned16(d.w_cur) || !aligned16(d.w_next) || !aligned16(d.m) || !aligned16(d.v) || !aligned16(d.G) ||
+      (reinterpret_cast<uintptr_t>(d.w_next_lp) & 7))
+    return hipErrorInvalidValue;
+  const int grid = stream_grid(d.n / 4);
+  if (d.w_next_lp)
+    hipLaunchKernelGGL(adam_kernel<true>, dim3(grid), dim3(256), 0, stream, d);
+  else
+    hipLaunchKernelGGL(adam_kernel<false>, dim3(grid), dim3(256), 0, stream, d);
+  return hipGetLastError();
+}
+
+hipError_t convert_f32_to_bf16(const float* in, bf16_t* out, int64_t n, hipStream_t stream) {
+  if (n <= 0 || n % 4 || !in || !out || !aligned16(in) || (reinterpret_cast<uintptr_t>(out) & 7))
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(stream_grid(n / 4)), dim3(256), 0, stream, in, out, n / 4);
+  return hipGetLastError();
+}
+
+hipError_t convert_bf16_to_f32(const bf16_t* in, float* out, int64_t n, hipStream_t stream) {
+  if (n <= 0 || n % 4 || !in || !out || !aligned16(out) || (reinterpret_cast<uintptr_t>(in) & 7))
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(bf16_to_f32_kernel, dim3(stream_grid(n / 4)), dim3(256), 0, stream, in, out, n / 4);
+  return hipGetLastError();
+}
+
+hipError_t copy_bytes(const void* in, void* out, int64_t bytes, hipStream_t stream) {
+  if (bytes <= 0 || bytes % 16 || !in || !out || !aligned16(in) || !aligned16(out)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(copy16_kernel, dim3(stream_grid(bytes / 16)), dim3(256), 0, stream,
+                     static_cast<const uint4*>(in), static_cast<uint4*>(out), bytes / 16);
+  return hipGetLastError();
+}
+
+}  // namespace k2bw

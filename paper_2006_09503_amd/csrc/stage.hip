@@ -1,0 +1,742 @@
+// The 2BW stage: device state, the forward/backward/update launch sequences and the C ABI.
+//
+// Device state (P parameters, T = b*s tokens, E = bytes per activation element):
+//   wbuf[2]   two weight versions, flat, same per-layer order as the host vector; fp32 in fp32
+//             mode, bf16 in bf16 mode.  Version v lives in wbuf[v % 2].
+//   master    fp32 copy updated in place (bf16 mode only; it is never read by forward/backward)
+//   G         fp32 coalesced gradient accumulator
+//   adam_m/v  one copy of optimizer state
+//   slots     per in-flight microbatch: every saved activation of every layer, or just the
+//             stage input when activations are recomputed in the backward pass
+//   ws        backward temporaries, reduction partials
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/stage2bw.h"
+#include "kernels.hpp"
+#include "schedule.hpp"
+
+using namespace k2bw;
+using s2bw::Schedule;
+
+namespace {
+
+struct LayerOff {  // element offsets into a flat parameter vector
+  int64_t ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, w1, b1, w2, b2;
+};
+
+struct LayerActs {  // saved activations of one layer for one microbatch
+  char *x, *a, *qkv, *o, *x1, *c, *u, *g;  // activation dtype
+  float *mean1, *rstd1, *mean2, *rstd2, *lse;
+};
+
+struct ActSet {
+  std::vector<LayerActs> layer;
+};
+
+int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+struct EventPair {
+  hipEvent_t start, stop;
+  int cls;
+  double flops, bytes;
+};
+
+}  // namespace
+
+struct stage2bw {
+  stage_config_t cfg;
+  hipStream_t stream = nullptr;
+  Schedule sched;
+  int64_t P = 0;
+  int T = 0;
+  int esize = 4;  // bytes per activation / version-buffer element
+  int dtype = kF32;
+  std::vector<LayerOff> off;
+
+  // device memory
+  std::vector<void*> allocations;
+  int64_t bytes_total = 0, bytes_weights = 0, bytes_stash = 0;
+  char* wbuf[2] = {nullptr, nullptr};
+  float* master = nullptr;
+  float* G = nullptr;
+  float* adam_m = nullptr;
+  float* adam_v = nullptr;
+
+  std::vector<ActSet> slot_acts;   // full stash: one per slot; recompute: one shared set
+  std::vector<char*> slot_x0;      // recompute: the stashed stage input per slot
+  std::vector<int32_t*> slot_lens; // per slot: key lengths (padding mask)
+
+  // backward workspace
+  char *tmp_h = nullptr, *dx1 = nullptr, *dchain[2] = {nullptr, nullptr}, *du = nullptr, *dqkv = nullptr;
+  char* y_scratch = nullptr;  // recompute: output of the re-run forward
+  float *delta = nullptr, *ln_partial = nullptr, *cs_partial = nullptr;
+
+  // timing
+  bool timing = false;
+  std::vector<EventPair> events;
+  size_t events_used = 0;
+
+  stage2bw(const stage_config_t& c) : cfg(c), sched(c.m, c.max_inflight) {}
+};
+
+namespace {
+
+int hip_rc(hipError_t e) {
+  if (e == hipSuccess) return STAGE_OK;
+  if (e == hipErrorOutOfMemory) return STAGE_ERR_OOM;
+  return STAGE_ERR_HIP;
+}
+
+#define HIP_TRY(expr)                       \
+  do {                                      \
+    hipError_t e__ = (expr);                \
+    if (e__ != hipSuccess) return hip_rc(e__); \
+  } while (0)
+
+int validate(const stage_config_t* c) {
+  if (!c) return STAGE_ERR_INVALID_ARG;
+  if (c->n_layers < 1 || c->hidden < 8 || c->n_heads < 1 || c->ffn < 8 || c->seq < 1 || c->microbatch < 1)
+    return STAGE_ERR_INVALID_ARG;
+  if (c->hidden % 8 || c->ffn % 8 || c->hidden % c->n_heads) return STAGE_ERR_INVALID_ARG;
+  const int dh = c->hidden / c->n_heads;
+  if (dh % 8 || dh > 128 || c->hidden > 16384) return STAGE_ERR_INVALID_ARG;
+  if (c->m < 1 || c->max_inflight < 1 || c->m < c->max_inflight) return STAGE_ERR_INVALID_ARG;
+  if (c->mask_mode < 0 || c->mask_mode > 2) return STAGE_ERR_INVALID_ARG;
+  if (c->precision != STAGE_PREC_FP32 && c->precision != STAGE_PREC_BF16) return STAGE_ERR_INVALID_ARG;
+  if (c->recompute != 0 && c->recompute != 1) return STAGE_ERR_INVALID_ARG;
+  if (!(c->lr >= 0.f) || !(c->beta1 >= 0.f && c->beta1 < 1.f) || !(c->beta2 >= 0.f && c->beta2 < 1.f) ||
+      !(c->adam_eps >= 0.f) || !(c->ln_eps >= 0.f))
+    return STAGE_ERR_INVALID_ARG;
+  if ((int64_t)c->seq * c->microbatch > (1 << 24)) return STAGE_ERR_INVALID_ARG;
+  return STAGE_OK;
+}
+
+int64_t layer_params(int64_t h, int64_t f) { return 4 * h * h + 2 * h * f + 9 * h + f; }
+
+std::vector<LayerOff> make_offsets(const stage_config_t& c) {
+  std::vector<LayerOff> v(c.n_layers);
+  const int64_t h = c.hidden, f = c.ffn;
+  int64_t o = 0;
+  for (int l = 0; l < c.n_layers; ++l) {
+    LayerOff& L = v[l];
+    L.ln1_g = o; o += h;
+    L.ln1_b = o; o += h;
+    L.wqkv = o; o += h * 3 * h;
+    L.bqkv = o; o += 3 * h;
+    L.wo = o; o += h * h;
+    L.bo = o; o += h;
+    L.ln2_g = o; o += h;
+    L.ln2_b = o; o += h;
+    L.w1 = o; o += h * f;
+    L.b1 = o; o += f;
+    L.w2 = o; o += f * h;
+    L.b2 = o; o += h;
+  }
+  return v;
+}
+
+int dev_alloc(stage2bw* st, void** out, int64_t bytes, int64_t* account) {
+  void* p = nullptr;
+  bytes = align_up(bytes, 256);
+  hipError_t e = hipMalloc(&p, (size_t)bytes);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return STAGE_ERR_OOM;
+  }
+  st->allocations.push_back(p);
+  st->bytes_total += bytes;
+  if (account) *account += bytes;
+  *out = p;
+  return STAGE_OK;
+}
+
+// One allocation holding an ActSet; returns STAGE_OK and fills set.
+int alloc_actset(stage2bw* st, ActSet* set) {
+  const stage_config_t& c = st->cfg;
+  const int64_t T = st->T, h = c.hidden, f = c.ffn, E = st->esize;
+  const int64_t act_h = align_up(T * h * E, 256), act_3h = align_up(T * 3 * h * E, 256), act_f = align_up(T * f * E, 256);
+  const int64_t stat = align_up(T * 4, 256), lse = align_up((int64_t)c.microbatch * c.n_heads * c.seq * 4, 256);
+  const int64_t per_layer = 5 * act_h + act_3h + 2 * act_f + 4 * stat + lse;
+  char* base = nullptr;
+  int rc = dev_alloc(st, reinterpret_cast<void**>(&base), per_layer * c.n_layers, &st->bytes_stash);
+  if (rc != STAGE_OK) return rc;
+  set->layer.resize(c.n_layers);
+  for (int l = 0; l < c.n_layers; ++l) {
+    char* p = base + per_layer * l;
+    LayerActs& A = set->layer[l];
+    A.x = p; p += act_h;
+    A.a = p; p += act_h;
+    A.qkv = p; p += act_3h;
+    A.o = p; p += act_h;
+    A.x1 = p; p += act_h;
+    A.c = p; p += act_h;
+    A.u = p; p += act_f;
+    A.g = p; p += act_f;
+    A.mean1 = reinterpret_cast<float*>(p); p += stat;
+    A.rstd1 = reinterpret_cast<float*>(p); p += stat;
+    A.mean2 = reinterpret_cast<float*>(p); p += stat;
+    A.rstd2 = reinterpret_cast<float*>(p); p += stat;
+    A.lse = reinterpret_cast<float*>(p); p += lse;
+  }
+  return STAGE_OK;
+}
+
+// ---- launch wrapper with optional event timing ------------------------------------------------
+template <typename F>
+hipError_t timed(stage2bw* st, int cls, double flops, double bytes, F&& launch) {
+  EventPair* ev = nullptr;
+  if (st->timing && st->events_used < st->events.size()) {
+    ev = &st->events[st->events_used++];
+    ev->cls = cls; ev->flops = flops; ev->bytes = bytes;
+    hipError_t e = hipEventRecord(ev->start, st->stream);
+    if (e != hipSuccess) return e;
+  }
+  hipError_t e = launch();
+  if (e != hipSuccess) return e;
+  if (ev) return hipEventRecord(ev->stop, st->stream);
+  return hipSuccess;
+}
+
+const char* wptr(const stage2bw* st, int buffer, int64_t elem_off) {
+  return st->wbuf[buffer] + elem_off * st->esize;
+}
+
+hipError_t run_gemm(stage2bw* st, int cls, const GemmDesc& d) {
+  return timed(st, cls, 2.0 * d.M * d.N * d.K, 0.0, [&] { return gemm(d, st->stream); });
+}
+
+hipError_t run_ln_fwd(stage2bw* st, const void* x, const void* gain, const void* shift, void* y, float* mean,
+                      float* rstd) {
+  const double bytes = 2.0 * st->T * st->cfg.hidden * st->esize + 8.0 * st->T;
+  return timed(st, STAGE_K_LN_FWD, 0.0, bytes, [&] {
+    return layernorm_fwd(x, gain, shift, y, mean, rstd, st->T, st->cfg.hidden, st->cfg.ln_eps, st->dtype, st->stream);
+  });
+}
+
+// LayerNorm backward + its two parameter gradients (gain | shift are adjacent in G).
+hipError_t run_ln_bwd(stage2bw* st, const void* dy, const void* x, const float* mean, const float* rstd,
+                      const void* gain, const void* dres, void* dx, float* g_gain, bool accumulate) {
+  const int h = st->cfg.hidden;
+  int parts = 0;
+  const double bytes = 4.0 * st->T * h * st->esize + 8.0 * st->T;
+  hipError_t e = timed(st, STAGE_K_LN_BWD, 0.0, bytes, [&] {
+    return layernorm_bwd(dy, x, mean, rstd, gain, dres, dx, st->ln_partial, &parts, st->T, h, st->dtype, st->stream);
+  });
+  if (e != hipSuccess) return e;
+  return timed(st, STAGE_K_BIAS_GRAD, 0.0, 4.0 * parts * 2 * h, [&] {
+    return colsum_finalize(st->ln_partial, parts, 2 * h, g_gain, accumulate, st->stream);
+  });
+}
+
+hipError_t run_bias_grad(stage2bw* st, const void* dy, int n, float* g_bias, bool accumulate) {
+  int parts = 0;
+  hipError_t e = timed(st, STAGE_K_BIAS_GRAD, 0.0, (double)st->T * n * st->esize, [&] {
+    return colsum_partial(dy, st->T, n, n, st->cs_partial, &parts, st->dtype, st->stream);
+  });
+  if (e != hipSuccess) return e;
+  return timed(st, STAGE_K_BIAS_GRAD, 0.0, 4.0 * parts * n, [&] {
+    return colsum_finalize(st->cs_partial, parts, n, g_bias, accumulate, st->stream);
+  });
+}
+
+AttnDesc attn_desc(const stage2bw* st, const int32_t* lens) {
+  AttnDesc d;
+  d.b = st->cfg.microbatch; d.s = st->cfg.seq; d.a = st->cfg.n_heads; d.dh = st->cfg.hidden / st->cfg.n_heads;
+  d.mask_mode = st->cfg.mask_mode; d.seqlens = lens; d.dtype = st->dtype;
+  return d;
+}
+
+// Forward of all layers on weight buffer `buf`.  acts.layer[0].x already holds the stage input.
+hipError_t run_forward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens, void* y_out) {
+  const stage_config_t& c = st->cfg;
+  const int T = st->T, h = c.hidden, f = c.ffn;
+  const double attn_flops = 4.0 * c.microbatch * (double)c.seq * c.seq * h;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerOff& o = st->off[l];
+    LayerActs& A = acts.layer[l];
+    void* y = (l == c.n_layers - 1) ? y_out : static_cast<void*>(acts.layer[l + 1].x);
+    hipError_t e;
+    e = run_ln_fwd(st, A.x, wptr(st, buf, o.ln1_g), wptr(st, buf, o.ln1_b), A.a, A.mean1, A.rstd1);
+    if (e != hipSuccess) return e;
+    GemmDesc g;
+    g.dtype = st->dtype;
+    g.A = A.a; g.lda = h; g.B = wptr(st, buf, o.wqkv); g.ldb = 3 * h; g.C = A.qkv; g.ldc = 3 * h;
+    g.M = T; g.N = 3 * h; g.K = h; g.bias = wptr(st, buf, o.bqkv);
+    e = run_gemm(st, STAGE_K_GEMM_FWD, g);
+    if (e != hipSuccess) return e;
+    e = timed(st, STAGE_K_ATTN_FWD, attn_flops, 0.0, [&] {
+      return attention_fwd(attn_desc(st, lens), A.qkv, A.o, A.lse, st->stream);
+    });
+    if (e != hipSuccess) return e;
+    g = GemmDesc();
+    g.dtype = st->dtype;
+    g.A = A.o; g.lda = h; g.B = wptr(st, buf, o.wo); g.ldb = h; g.C = A.x1; g.ldc = h;
+    g.M = T; g.N = h; g.K = h; g.bias = wptr(st, buf, o.bo); g.aux = A.x;
+    e = run_gemm(st, STAGE_K_GEMM_FWD, g);
+    if (e != hipSuccess) return e;
+    e = run_ln_fwd(st, A.x1, wptr(st, buf, o.ln2_g), wptr(st, buf, o.ln2_b), A.c, A.mean2, A.rstd2);
+    if (e != hipSuccess) return e;
+    g = GemmDesc();
+    g.dtype = st->dtype;
+    g.A = A.c; g.lda = h; g.B = wptr(st, buf, o.w1); g.ldb = f; g.C = A.u; g.ldc = f;
+    g.M = T; g.N = f; g.K = h; g.bias = wptr(st, buf, o.b1); g.epilogue = kEpiGelu; g.aux_out = A.g;
+    e = run_gemm(st, STAGE_K_GEMM_FWD, g);
+    if (e != hipSuccess) return e;
+    g = GemmDesc();
+    g.dtype = st->dtype;
+    g.A = A.g; g.lda = f; g.B = wptr(st, buf, o.w2); g.ldb = h; g.C = y; g.ldc = h;
+    g.M = T; g.N = h; g.K = f; g.bias = wptr(st, buf, o.b2); g.aux = A.x1;
+    e = run_gemm(st, STAGE_K_GEMM_FWD, g);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+// Backward of all layers on weight buffer `buf`; weight gradients go into G (overwrite when
+// `first`, add otherwise).
+hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens, const void* dy_in, void* dx_out,
+                        bool first) {
+  const stage_config_t& c = st->cfg;
+  const int T = st->T, h = c.hidden, f = c.ffn;
+  const bool acc = !first;
+  const double attn_flops = 10.0 * c.microbatch * (double)c.seq * c.seq * h;
+  const void* dy = dy_in;
+  for (int l = c.n_layers - 1; l >= 0; --l) {
+    const LayerOff& o = st->off[l];
+    LayerActs& A = acts.layer[l];
+    void* dx = (l == 0) ? dx_out : static_cast<void*>(st->dchain[l & 1]);
+    hipError_t e;
+    GemmDesc g;
+    auto wgrad = [&](const void* act, int M, const void* grad, int N, float* out) {
+      GemmDesc w;
+      w.dtype = st->dtype;
+      w.A = act; w.lda = M; w.trans_a = true; w.B = grad; w.ldb = N; w.C = out; w.ldc = N;
+      w.M = M; w.N = N; w.K = T; w.epilogue = kEpiAccum; w.accumulate = acc;
+      return run_gemm(st, STAGE_K_GEMM_WGRAD, w);
+    };
+    auto dgrad = [&](const void* grad, int N, const char* w_, int K, void* out, const void* u) {
+      // out[T,K] = grad[T,N] * W[K,N]^T
+      GemmDesc d;
+      d.dtype = st->dtype;
+      d.A = grad; d.lda = N; d.B = w_; d.ldb = N; d.trans_b = true; d.C = out; d.ldc = K;
+      d.M = T; d.N = K; d.K = N;
+      if (u) { d.epilogue = kEpiGeluGrad; d.aux = u; }
+      return run_gemm(st, STAGE_K_GEMM_DGRAD, d);
+    };
+    // y = x1 + GELU(u) W2 + b2
+    e = wgrad(A.g, f, dy, h, st->G + o.w2);                              if (e != hipSuccess) return e;
+    e = run_bias_grad(st, dy, h, st->G + o.b2, acc);                     if (e != hipSuccess) return e;
+    e = dgrad(dy, h, wptr(st, buf, o.w2), f, st->du, A.u);               if (e != hipSuccess) return e;
+    // u = c W1 + b1
+    e = wgrad(A.c, h, st->du, f, st->G + o.w1);                          if (e != hipSuccess) return e;
+    e = run_bias_grad(st, st->du, f, st->G + o.b1, acc);                 if (e != hipSuccess) return e;
+    e = dgrad(st->du, f, wptr(st, buf, o.w1), h, st->tmp_h, nullptr);    if (e != hipSuccess) return e;
+    // c = LN2(x1); dx1 = dy + LN2'(dc)
+    e = run_ln_bwd(st, st->tmp_h, A.x1, A.mean2, A.rstd2, wptr(st, buf, o.ln2_g), dy, st->dx1, st->G + o.ln2_g, acc);
+    if (e != hipSuccess) return e;
+    // x1 = x + o Wo + bo
+    e = wgrad(A.o, h, st->dx1, h, st->G + o.wo);                         if (e != hipSuccess) return e;
+    e = run_bias_grad(st, st->dx1, h, st->G + o.bo, acc);                if (e != hipSuccess) return e;
+    e = dgrad(st->dx1, h, wptr(st, buf, o.wo), h, st->tmp_h, nullptr);   if (e != hipSuccess) return e;
+    // attention
+    e = timed(st, STAGE_K_ATTN_BWD, attn_flops, 0.0, [&] {
+      return attention_bwd(attn_desc(st, lens), A.qkv, A.o, A.lse, st->tmp_h, st->dqkv, st->delta, st->stream);
+    });
+    if (e != hipSuccess) return e;
+    // qkv = a Wqkv + bqkv
+    e = wgrad(A.a, h, st->dqkv, 3 * h, st->G + o.wqkv);                  if (e != hipSuccess) return e;
+    e = run_bias_grad(st, st->dqkv, 3 * h, st->G + o.bqkv, acc);         if (e != hipSuccess) return e;
+    e = dgrad(st->dqkv, 3 * h, wptr(st, buf, o.wqkv), h, st->tmp_h, nullptr);  if (e != hipSuccess) return e;
+    // a = LN1(x); dx = dx1 + LN1'(da)
+    e = run_ln_bwd(st, st->tmp_h, A.x, A.mean1, A.rstd1, wptr(st, buf, o.ln1_g), st->dx1, dx, st->G + o.ln1_g, acc);
+    if (e != hipSuccess) return e;
+    dy = dx;
+    (void)g;
+  }
+  return hipSuccess;
+}
+
+int free_all(stage2bw* st) {
+  int rc = STAGE_OK;
+  for (void* p : st->allocations)
+    if (hipFree(p) != hipSuccess) rc = STAGE_ERR_HIP;
+  st->allocations.clear();
+  for (EventPair& e : st->events) {
+    (void)hipEventDestroy(e.start);
+    (void)hipEventDestroy(e.stop);
+  }
+  st->events.clear();
+  return rc;
+}
+
+}  // namespace
+
+// =============================================================================== C ABI
+
+extern "C" {
+
+int64_t stage_param_count(const stage_config_t* cfg) {
+  int rc = validate(cfg);
+  if (rc != STAGE_OK) return rc;
+  return cfg->n_layers * layer_params(cfg->hidden, cfg->ffn);
+}
+
+int stage_create(const stage_config_t* cfg, const float* init_weights_host, void* hip_stream, stage_t** out) {
+  if (!out) return STAGE_ERR_INVALID_ARG;
+  *out = nullptr;
+  int rc = validate(cfg);
+  if (rc != STAGE_OK) return rc;
+  if (!init_weights_host) return STAGE_ERR_INVALID_ARG;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
+    (void)hipGetLastError();
+    return STAGE_ERR_HIP;
+  }
+  stage2bw* st = new (std::nothrow) stage2bw(*cfg);
+  if (!st) return STAGE_ERR_OOM;
+  st->stream = static_cast<hipStream_t>(hip_stream);
+  st->P = cfg->n_layers * layer_params(cfg->hidden, cfg->ffn);
+  st->T = cfg->microbatch * cfg->seq;
+  st->dtype = cfg->precision == STAGE_PREC_BF16 ? kBF16 : kF32;
+  st->esize = st->dtype == kBF16 ? 2 : 4;
+  st->off = make_offsets(*cfg);
+
+  const int64_t P = st->P, T = st->T, h = cfg->hidden, f = cfg->ffn, E = st->esize;
+  auto fail = [&](int code) {
+    free_all(st);
+    delete st;
+    return code;
+  };
+#define ALLOC(ptr, bytes, account)                                                      \
+  do {                                                                                  \
+    int rc__ = dev_alloc(st, reinterpret_cast<void**>(&(ptr)), (bytes), (account));     \
+    if (rc__ != STAGE_OK) return fail(rc__);                                            \
+  } while (0)
+
+  ALLOC(st->wbuf[0], P * E, &st->bytes_weights);
+  ALLOC(st->wbuf[1], P * E, &st->bytes_weights);
+  if (st->dtype == kBF16) ALLOC(st->master, P * 4, &st->bytes_weights);
+  ALLOC(st->G, P * 4, nullptr);
+  ALLOC(st->adam_m, P * 4, nullptr);
+  ALLOC(st->adam_v, P * 4, nullptr);
+
+  const int n_sets = cfg->recompute ? 1 : cfg->max_inflight;
+  st->slot_acts.resize(n_sets);
+  for (int i = 0; i < n_sets; ++i) {
+    rc = alloc_actset(st, &st->slot_acts[i]);
+    if (rc != STAGE_OK) return fail(rc);
+  }
+  st->slot_lens.resize(cfg->max_inflight, nullptr);
+  st->slot_x0.resize(cfg->max_inflight, nullptr);
+  for (int i = 0; i < cfg->max_inflight; ++i) {
+    ALLOC(st->slot_lens[i], (int64_t)cfg->microbatch * 4, &st->bytes_stash);
+    if (cfg->recompute) ALLOC(st->slot_x0[i], T * h * E, &st->bytes_stash);
+  }
+  ALLOC(st->tmp_h, T * h * E, nullptr);
+  ALLOC(st->dx1, T * h * E, nullptr);
+  ALLOC(st->dchain[0], T * h * E, nullptr);
+  ALLOC(st->dchain[1], T * h * E, nullptr);
+  ALLOC(st->du, T * f * E, nullptr);
+  ALLOC(st->dqkv, T * 3 * h * E, nullptr);
+  if (cfg->recompute) ALLOC(st->y_scratch, T * h * E, nullptr);
+  ALLOC(st->delta, (int64_t)cfg->microbatch * cfg->n_heads * cfg->seq * 4, nullptr);
+  ALLOC(st->ln_partial, (int64_t)ln_bwd_max_parts() * 2 * h * 4, nullptr);
+  const int64_t widest = (3 * h > f) ? 3 * h : f;
+  ALLOC(st->cs_partial, (int64_t)colsum_max_parts() * widest * 4, nullptr);
+#undef ALLOC
+
+  // upload W(0): fp32 mode -> both buffers; bf16 mode -> master, then both bf16 buffers
+  hipError_t e;
+  float* dst32 = st->dtype == kBF16 ? st->master : reinterpret_cast<float*>(st->wbuf[0]);
+  e = hipMemcpyAsync(dst32, init_weights_host, (size_t)P * 4, hipMemcpyHostToDevice, st->stream);
+  if (e == hipSuccess) {
+    if (st->dtype == kBF16) {
+      e = convert_f32_to_bf16(st->master, reinterpret_cast<bf16_t*>(st->wbuf[0]), P, st->stream);
+      if (e == hipSuccess)
+        e = hipMemcpyAsync(st->wbuf[1], st->wbuf[0], (size_t)P * 2, hipMemcpyDeviceToDevice, st->stream);
+    } else {
+      e = hipMemcpyAsync(st->wbuf[1], st->wbuf[0], (size_t)P * 4, hipMemcpyDeviceToDevice, st->stream);
+    }
+  }
+  if (e == hipSuccess) e = hipMemsetAsync(st->G, 0, (size_t)P * 4, st->stream);
+  if (e == hipSuccess) e = hipMemsetAsync(st->adam_m, 0, (size_t)P * 4, st->stream);
+  if (e == hipSuccess) e = hipMemsetAsync(st->adam_v, 0, (size_t)P * 4, st->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(st->stream);
+  if (e != hipSuccess) return fail(hip_rc(e));
+  *out = st;
+  return STAGE_OK;
+}
+
+int stage_forward(stage_t* st, int64_t mb, const void* x_dev, const int32_t* seqlens_dev, void* y_dev) {
+  if (!st || !x_dev || !y_dev || x_dev == y_dev) return STAGE_ERR_INVALID_ARG;
+  if (st->cfg.mask_mode == STAGE_MASK_PADDING && !seqlens_dev) return STAGE_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(x_dev) & 15) || (reinterpret_cast<uintptr_t>(y_dev) & 15)) return STAGE_ERR_INVALID_ARG;
+  int slot = -1;
+  int rc = st->sched.check_forward(mb, &slot);
+  if (rc != STAGE_OK) return rc;
+  const int buf = Schedule::buffer_of(st->sched.read_version());
+  const int64_t in_bytes = (int64_t)st->T * st->cfg.hidden * st->esize;
+  ActSet& acts = st->cfg.recompute ? st->slot_acts[0] : st->slot_acts[slot];
+  // stash the stage input (with recompute it is the only thing kept)
+  char* x_keep = st->cfg.recompute ? st->slot_x0[slot] : acts.layer[0].x;
+  HIP_TRY(timed(st, STAGE_K_OTHER, 0.0, 2.0 * in_bytes, [&] { return copy_bytes(x_dev, x_keep, in_bytes, st->stream); }));
+  const int32_t* lens = nullptr;
+  if (st->cfg.mask_mode == STAGE_MASK_PADDING) {
+    HIP_TRY(hipMemcpyAsync(st->slot_lens[slot], seqlens_dev, (size_t)st->cfg.microbatch * 4, hipMemcpyDeviceToDevice,
+                           st->stream));
+    lens = st->slot_lens[slot];
+  }
+  if (st->cfg.recompute) {
+    // the shared activation set is scratch here; its layer-0 input is read from the stash
+    char* saved = acts.layer[0].x;
+    acts.layer[0].x = x_keep;
+    hipError_t e = run_forward(st, buf, acts, lens, y_dev);
+    acts.layer[0].x = saved;
+    HIP_TRY(e);
+  } else {
+    HIP_TRY(run_forward(st, buf, acts, lens, y_dev));
+  }
+  int64_t version = 0;
+  int b2 = 0;
+  return st->sched.forward(mb, &slot, &version, &b2);
+}
+
+int stage_backward(stage_t* st, int64_t mb, const void* dy_dev, void* dx_dev) {
+  if (!st || !dy_dev || !dx_dev || dy_dev == dx_dev) return STAGE_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(dy_dev) & 15) || (reinterpret_cast<uintptr_t>(dx_dev) & 15)) return STAGE_ERR_INVALID_ARG;
+  int slot = -1;
+  int rc = st->sched.check_backward(mb, &slot);
+  if (rc != STAGE_OK) return rc;
+  // commit the bookkeeping first to learn tag and accumulate flag (no failure path after the check)
+  int64_t version = 0;
+  int buf = 0, first = 0;
+  rc = st->sched.backward(mb, &slot, &version, &buf, &first);
+  if (rc != STAGE_OK) return rc;
+  const int32_t* lens = st->cfg.mask_mode == STAGE_MASK_PADDING ? st->slot_lens[slot] : nullptr;
+  if (st->cfg.recompute) {
+    // re-run the forward on the version tagged at the forward pass (Section 4.1 with Section 3.1)
+    ActSet& acts = st->slot_acts[0];
+    char* saved = acts.layer[0].x;
+    acts.layer[0].x = st->slot_x0[slot];
+    hipError_t e = run_forward(st, buf, acts, lens, st->y_scratch);
+    if (e == hipSuccess) e = run_backward(st, buf, acts, lens, dy_dev, dx_dev, first != 0);
+    acts.layer[0].x = saved;
+    HIP_TRY(e);
+  } else {
+    HIP_TRY(run_backward(st, buf, st->slot_acts[slot], lens, dy_dev, dx_dev, first != 0));
+  }
+  return STAGE_OK;
+}
+
+int stage_coalesce_update(stage_t* st) {
+  if (!st) return STAGE_ERR_INVALID_ARG;
+  int rc = st->sched.check_update();
+  if (rc != STAGE_OK) return rc;
+  int rb = 0, wb = 0;
+  int64_t step = 0;
+  rc = st->sched.coalesce_update(&rb, &wb, &step);
+  if (rc != STAGE_OK) return rc;
+  AdamDesc d;
+  d.n = st->P; d.m = st->adam_m; d.v = st->adam_v; d.G = st->G;
+  d.lr = st->cfg.lr; d.beta1 = st->cfg.beta1; d.beta2 = st->cfg.beta2; d.eps = st->cfg.adam_eps;
+  d.inv_m = 1.0f / (float)st->cfg.m;
+  d.c1 = (float)(1.0 / (1.0 - std::pow((double)st->cfg.beta1, (double)step)));
+  d.c2 = (float)(1.0 / (1.0 - std::pow((double)st->cfg.beta2, (double)step)));
+  double bytes;
+  if (st->dtype == kBF16) {
+    d.w_cur = st->master; d.w_next = st->master; d.w_next_lp = reinterpret_cast<bf16_t*>(st->wbuf[wb]);
+    bytes = 30.0 * st->P;
+  } else {
+    d.w_cur = reinterpret_cast<const float*>(st->wbuf[rb]); d.w_next = reinterpret_cast<float*>(st->wbuf[wb]);
+    bytes = 28.0 * st->P;
+  }
+  HIP_TRY(timed(st, STAGE_K_ADAM, 0.0, bytes, [&] { return adam_step(d, st->stream); }));
+  return STAGE_OK;
+}
+
+int stage_swap_versions(stage_t* st) {
+  if (!st) return STAGE_ERR_INVALID_ARG;
+  return st->sched.swap_versions();
+}
+
+int stage_destroy(stage_t* st) {
+  if (!st) return STAGE_ERR_INVALID_ARG;
+  (void)hipStreamSynchronize(st->stream);
+  int rc = free_all(st);
+  delete st;
+  return rc;
+}
+
+static int read_f32(stage_t* st, const float* dev, float* host) {
+  HIP_TRY(hipStreamSynchronize(st->stream));
+  HIP_TRY(hipMemcpy(host, dev, (size_t)st->P * 4, hipMemcpyDeviceToHost));
+  return STAGE_OK;
+}
+
+int stage_read_weights(stage_t* st, int which, float* out_host) {
+  if (!st || !out_host) return STAGE_ERR_INVALID_ARG;
+  if (which == STAGE_WEIGHTS_MASTER) {
+    if (st->dtype == kBF16) return read_f32(st, st->master, out_host);
+    which = Schedule::buffer_of(st->sched.updates());
+  }
+  if (which != 0 && which != 1) return STAGE_ERR_INVALID_ARG;
+  if (st->dtype == kF32) return read_f32(st, reinterpret_cast<const float*>(st->wbuf[which]), out_host);
+  std::vector<uint16_t> tmp;
+  try { tmp.resize((size_t)st->P); } catch (...) { return STAGE_ERR_OOM; }
+  HIP_TRY(hipStreamSynchronize(st->stream));
+  HIP_TRY(hipMemcpy(tmp.data(), st->wbuf[which], (size_t)st->P * 2, hipMemcpyDeviceToHost));
+  for (int64_t i = 0; i < st->P; ++i) {
+    const uint32_t u = (uint32_t)tmp[i] << 16;
+    std::memcpy(&out_host[i], &u, 4);
+  }
+  return STAGE_OK;
+}
+
+int stage_read_grad_accum(stage_t* st, float* out_host) {
+  if (!st || !out_host) return STAGE_ERR_INVALID_ARG;
+  return read_f32(st, st->G, out_host);
+}
+
+int stage_read_adam(stage_t* st, float* m_out_host, float* v_out_host) {
+  if (!st) return STAGE_ERR_INVALID_ARG;
+  if (m_out_host) { int rc = read_f32(st, st->adam_m, m_out_host); if (rc) return rc; }
+  if (v_out_host) { int rc = read_f32(st, st->adam_v, v_out_host); if (rc) return rc; }
+  return STAGE_OK;
+}
+
+int stage_query(stage_t* st, int what, int64_t* out) {
+  if (!st || !out) return STAGE_ERR_INVALID_ARG;
+  switch (what) {
+    case STAGE_Q_UPDATES: *out = st->sched.updates(); break;
+    case STAGE_Q_READ_VERSION: *out = st->sched.read_version(); break;
+    case STAGE_Q_INFLIGHT: *out = st->sched.inflight(); break;
+    case STAGE_Q_ACCUMULATED: *out = st->sched.accumulated(); break;
+    case STAGE_Q_BYTES_ALLOCATED: *out = st->bytes_total; break;
+    case STAGE_Q_BYTES_WEIGHTS: *out = st->bytes_weights; break;
+    case STAGE_Q_BYTES_STASH: *out = st->bytes_stash; break;
+    case STAGE_Q_BUFFER_OF_NEWEST: *out = Schedule::buffer_of(st->sched.updates()); break;
+    case STAGE_Q_BUFFER_OF_READ: *out = Schedule::buffer_of(st->sched.read_version()); break;
+    default: return STAGE_ERR_INVALID_ARG;
+  }
+  return STAGE_OK;
+}
+
+const char* stage_strerror(int code) {
+  switch (code) {
+    case STAGE_OK: return "ok";
+    case STAGE_ERR_INVALID_ARG: return "invalid argument";
+    case STAGE_ERR_BAD_STATE: return "call violates the 2BW schedule";
+    case STAGE_ERR_OOM: return "out of memory";
+    case STAGE_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error code";
+  }
+}
+
+int stage_timing_enable(stage_t* st, int enable, int32_t capacity) {
+  if (!st) return STAGE_ERR_INVALID_ARG;
+  HIP_TRY(hipStreamSynchronize(st->stream));
+  for (EventPair& e : st->events) {
+    (void)hipEventDestroy(e.start);
+    (void)hipEventDestroy(e.stop);
+  }
+  st->events.clear();
+  st->events_used = 0;
+  st->timing = false;
+  if (!enable) return STAGE_OK;
+  if (capacity < 1) return STAGE_ERR_INVALID_ARG;
+  try { st->events.reserve(capacity); } catch (...) { return STAGE_ERR_OOM; }
+  for (int i = 0; i < capacity; ++i) {
+    EventPair e{};
+    if (hipEventCreate(&e.start) != hipSuccess) return STAGE_ERR_HIP;
+    if (hipEventCreate(&e.stop) != hipSuccess) { (void)hipEventDestroy(e.start); return STAGE_ERR_HIP; }
+    st->events.push_back(e);
+  }
+  st->timing = true;
+  return STAGE_OK;
+}
+
+int stage_timing_collect(stage_t* st, double* ms_out, int64_t* launches_out, double* flops_out, double* bytes_out) {
+  if (!st || !ms_out || !launches_out || !flops_out || !bytes_out) return STAGE_ERR_INVALID_ARG;
+  HIP_TRY(hipStreamSynchronize(st->stream));
+  for (int i = 0; i < STAGE_K_COUNT; ++i) { ms_out[i] = 0; launches_out[i] = 0; flops_out[i] = 0; bytes_out[i] = 0; }
+  for (size_t i = 0; i < st->events_used; ++i) {
+    const EventPair& e = st->events[i];
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, e.start, e.stop));
+    ms_out[e.cls] += ms;
+    launches_out[e.cls] += 1;
+    flops_out[e.cls] += e.flops;
+    bytes_out[e.cls] += e.bytes;
+  }
+  st->events_used = 0;
+  return STAGE_OK;
+}
+
+// ---- the schedule alone -------------------------------------------------------------------
+
+struct stage_sched {
+  Schedule s;
+  stage_sched(int m, int p) : s(m, p) {}
+};
+
+int stage_sched_create(int32_t m, int32_t max_inflight, stage_sched_t** out) {
+  if (!out || m < 1 || max_inflight < 1 || m < max_inflight) return STAGE_ERR_INVALID_ARG;
+  *out = new (std::nothrow) stage_sched(m, max_inflight);
+  return *out ? STAGE_OK : STAGE_ERR_OOM;
+}
+int stage_sched_forward(stage_sched_t* s, int64_t mb, int32_t* slot_out, int64_t* version_out, int32_t* buffer_out) {
+  if (!s || !slot_out || !version_out || !buffer_out) return STAGE_ERR_INVALID_ARG;
+  int slot = 0, buf = 0;
+  int64_t ver = 0;
+  int rc = s->s.forward(mb, &slot, &ver, &buf);
+  if (rc == STAGE_OK) { *slot_out = slot; *version_out = ver; *buffer_out = buf; }
+  return rc;
+}
+int stage_sched_backward(stage_sched_t* s, int64_t mb, int32_t* slot_out, int64_t* version_out, int32_t* buffer_out,
+                         int32_t* first_of_batch_out) {
+  if (!s || !slot_out || !version_out || !buffer_out || !first_of_batch_out) return STAGE_ERR_INVALID_ARG;
+  int slot = 0, buf = 0, first = 0;
+  int64_t ver = 0;
+  int rc = s->s.backward(mb, &slot, &ver, &buf, &first);
+  if (rc == STAGE_OK) { *slot_out = slot; *version_out = ver; *buffer_out = buf; *first_of_batch_out = first; }
+  return rc;
+}
+int stage_sched_coalesce_update(stage_sched_t* s, int32_t* read_buffer_out, int32_t* write_buffer_out,
+                                int64_t* step_out) {
+  if (!s || !read_buffer_out || !write_buffer_out || !step_out) return STAGE_ERR_INVALID_ARG;
+  int rb = 0, wb = 0;
+  int64_t step = 0;
+  int rc = s->s.coalesce_update(&rb, &wb, &step);
+  if (rc == STAGE_OK) { *read_buffer_out = rb; *write_buffer_out = wb; *step_out = step; }
+  return rc;
+}
+int stage_sched_swap_versions(stage_sched_t* s) {
+  if (!s) return STAGE_ERR_INVALID_ARG;
+  return s->s.swap_versions();
+}
+int stage_sched_query(stage_sched_t* s, int what, int64_t* out) {
+  if (!s || !out) return STAGE_ERR_INVALID_ARG;
+  switch (what) {
+    case STAGE_Q_UPDATES: *out = s->s.updates(); break;
+    case STAGE_Q_READ_VERSION: *out = s->s.read_version(); break;
+    case STAGE_Q_INFLIGHT: *out = s->s.inflight(); break;
+    case STAGE_Q_ACCUMULATED: *out = s->s.accumulated(); break;
+    case STAGE_Q_BUFFER_OF_NEWEST: *out = Schedule::buffer_of(s->s.updates()); break;
+    case STAGE_Q_BUFFER_OF_READ: *out = Schedule::buffer_of(s->s.read_version()); break;
+    default: return STAGE_ERR_INVALID_ARG;
+  }
+  return STAGE_OK;
+}
+int stage_sched_destroy(stage_sched_t* s) {
+  if (!s) return STAGE_ERR_INVALID_ARG;
+  delete s;
+  return STAGE_OK;
+}
+
+}  // extern "C"
