@@ -91,6 +91,7 @@ struct AdamDesc {
   const float* G = nullptr;
   int64_t n = 0;
   float lr = 0, beta1 = 0, beta2 = 0, eps = 0, inv_m = 1, c1 = 1, c2 = 1;
+  float omb1 = 0, omb2 = 0;        // 1 - beta, rounded once from double
 };
 hipError_t adam_step(const AdamDesc& d, hipStream_t stream);
 

@@ -11,7 +11,7 @@ template <bool LP>
 __global__ __launch_bounds__(256) void adam_kernel(AdamDesc d) {
   const int64_t n4 = d.n / 4;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  const float omb1 = 1.0f - d.beta1, omb2 = 1.0f - d.beta2;
+  const float omb1 = d.omb1, omb2 = d.omb2;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
     const float4 w = reinterpret_cast<const float4*>(d.w_cur)[i];
     float4 m = reinterpret_cast<const float4*>(d.m)[i];
@@ -69,7 +69,10 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 
 }  // namespace
 
-hipError_t adam_step(const AdamDesc& d, hipStream_t stream) {
+hipError_t adam_step(const AdamDesc& d_in, hipStream_t stream) {
+  AdamDesc d = d_in;
+  d.omb1 = (float)(1.0 - (double)d.beta1);
+  d.omb2 = (float)(1.0 - (double)d.beta2);
   if (d.n <= 0 || d.n % 4 || !d.w_cur || !d.w_next || !d.m || !d.v || !d.G) return hipErrorInvalidValue;
   if (!aligned16(d.w_cur) || !aligned16(d.w_next) || !aligned16(d.m) || !aligned16(d.v) || !aligned16(d.G) ||
       (reinterpret_cast<uintptr_t>(d.w_next_lp) & 7))

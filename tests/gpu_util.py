@@ -1,0 +1,109 @@
+"""Helpers shared by the GPU parity tests: moving seeded arrays to the device in the stage's
+element type, running a stage through the C ABI in 1F1B order, and the oracle replay beside it."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import block as ob
+from oracle import twobw as tb
+from paper_2006_09503_amd import binding as B
+from paper_2006_09503_amd import synth
+
+TOL = {synth.PREC_FP32: 1e-4, synth.PREC_BF16: 2e-2}     # relative L2 bars (fp32 mode, bf16-MFMA mode)
+# The Adam step dW = lr * mhat / (sqrt(vhat) + eps) is scale-free in g: an element's relative
+# error in dW equals its relative error in g, and elements with |g| far below the typical size
+# carry rounding noise of the typical size.  With a smooth density of g around zero the relative
+# L2 error of dW grows like eps_g * sqrt(P) (eps_g: accumulation noise relative to the typical
+# |g|, P: parameters), so dW gets its own, looser bars; W itself stays under TOL.
+DW_TOL = {synth.PREC_FP32: 1e-3, synth.PREC_BF16: 0.25}
+
+
+def rel(a, b) -> float:
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def tdtype(precision):
+    return torch.bfloat16 if precision == synth.PREC_BF16 else torch.float32
+
+
+def to_dev(a: np.ndarray, precision) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda").to(tdtype(precision)).contiguous()
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy()
+
+
+def run_stage_gpu(cfg: synth.StageConfig, w0: np.ndarray, mbs, inflight: int, snapshot: bool = True):
+    """Drive the HIP stage over the microbatches; returns per-microbatch Y, dX and, per update,
+    the accumulator, Adam moments, both buffers and the master as read right after the update."""
+    st = B.Stage(cfg, w0)
+    n = len(mbs)
+    shape = (cfg.microbatch, cfg.seq, cfg.hidden)
+    X = {k: to_dev(mbs[k - 1][0], cfg.precision) for k in range(1, n + 1)}
+    DY = {k: to_dev(mbs[k - 1][1], cfg.precision) for k in range(1, n + 1)}
+    LEN = {k: (None if mbs[k - 1][2] is None else torch.from_numpy(mbs[k - 1][2]).to("cuda").to(torch.int32))
+           for k in range(1, n + 1)}
+    Y = {k: torch.full(shape, float("nan"), device="cuda", dtype=tdtype(cfg.precision)) for k in X}
+    DX = {k: torch.full(shape, float("nan"), device="cuda", dtype=tdtype(cfg.precision)) for k in X}
+    snaps = []
+
+    def on_update(t):
+        if not snapshot:
+            return
+        m_, v_ = st.read_adam()
+        snaps.append(dict(t=t, G=st.read_grad_accum(), m=m_, v=v_,
+                          buf0=st.read_weights(B.WEIGHTS_BUF0), buf1=st.read_weights(B.WEIGHTS_BUF1),
+                          master=st.read_weights(B.WEIGHTS_MASTER),
+                          newest=st.query(B.Q_BUFFER_OF_NEWEST), updates=st.query(B.Q_UPDATES)))
+
+    st.run_1f1b(1, n, lambda k: (X[k], LEN[k], DY[k]), lambda k: (Y[k], DX[k]), inflight, on_update)
+    torch.cuda.synchronize()
+    out = dict(Y={k: to_host(v) for k, v in Y.items()}, dX={k: to_host(v) for k, v in DX.items()}, snaps=snaps,
+               bytes=st.query(B.Q_BYTES_ALLOCATED))
+    st.close()
+    return out
+
+
+def run_stage_oracle(cfg: synth.StageConfig, w0: np.ndarray, mbs, inflight: int = 1) -> tb.Trace:
+    st = ob.Stage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.mask_mode, cfg.ln_eps)
+    f32 = lambda z: float(np.float32(z))        # the C ABI carries the hyper-parameters as floats
+    opt = tb.Adam(f32(cfg.lr), f32(cfg.beta1), f32(cfg.beta2), f32(cfg.adam_eps))
+    return tb.replay(lambda w, x, dy, lens: st.vjp(w, x, dy, lens), w0.astype(np.float64), mbs, cfg.m, opt,
+                     inflight=inflight)
+
+
+def compare_stage(cfg, gpu, tr: tb.Trace, tol=None, check_dw=True, check_weights=True):
+    """Element-wise comparison (relative L2) of everything the stage produces; returns the worst
+    ratios for reporting."""
+    tol = TOL[cfg.precision] if tol is None else tol
+    worst = {}
+
+    def chk(name, got, want, bar=tol):
+        r = rel(got, want)
+        worst[name] = max(worst.get(name, 0.0), r)
+        assert r <= bar, f"{name}: rel L2 {r:.3e} > {bar:.1e}"
+
+    for k in sorted(tr.Y):
+        chk("Y", gpu["Y"][k], tr.Y[k])
+        chk("dX", gpu["dX"][k], tr.dX[k])
+    for s in gpu["snaps"]:
+        t = s["t"]
+        assert s["updates"] == t and s["newest"] == t % 2
+        chk("G", s["G"], tr.G[t - 1])
+        chk("adam_m", s["m"], tr.opt_state[t - 1]["m"])
+        chk("adam_v", s["v"], tr.opt_state[t - 1]["v"])
+        if not check_weights:
+            continue
+        new, old = (s["buf1"], s["buf0"]) if t % 2 else (s["buf0"], s["buf1"])
+        chk("W_new_buffer", new, tr.W[t])
+        chk("W_other_buffer", old, tr.W[t - 1])        # the shadow version is still intact
+        chk("W_master", s["master"], tr.W[t])
+        if check_dw:
+            # the raw weights move by only ~lr/0.02 per step; the step itself is the sensitive quantity
+            dw_gpu = s["master"].astype(np.float64) - (gpu["snaps"][t - 2]["master"] if t >= 2 else tr.W[0])
+            chk("dW", dw_gpu, tr.W[t] - tr.W[t - 1], bar=DW_TOL[cfg.precision])
+    return worst

@@ -1,0 +1,132 @@
+"""The HIP stage, driven through the C ABI in 1F1B order, against the fp64 oracle's replay of
+the same seeded inputs: every Y_k, dX_k, the coalesced gradient before each update, Adam moments,
+the step dW, both weight buffers and which buffer holds which version.
+Bars: relative L2 <= 1e-4 in fp32 mode, <= 2e-2 in bf16-MFMA mode."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2006_09503_amd import binding as B
+from paper_2006_09503_amd import synth
+
+from gpu_util import compare_stage, rel, run_stage_gpu, run_stage_oracle, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def both(cfg, n_batches, inflight, seed=0):
+    gen = synth.StageInputs(cfg, seed)
+    w0 = gen.weights()
+    mbs = gen.microbatches(n_batches * cfg.m)
+    gpu = run_stage_gpu(cfg, w0, mbs, inflight)
+    tr = run_stage_oracle(cfg, w0, mbs)
+    return gpu, tr
+
+
+def test_tiny_config_fp32_three_updates():
+    """The tiny workload exactly as specified: 2 layers, h=128, 4 heads, f=512, s=64, b=2, m=4,
+    fp32, three Adam steps, seed 0."""
+    cfg = synth.PRESETS["C1"]
+    gpu, tr = both(cfg, 3, cfg.max_inflight)
+    worst = compare_stage(cfg, gpu, tr)
+    print("C1 fp32 worst rel-L2:", {k: f"{v:.2e}" for k, v in worst.items()})
+    assert [tr.version_used[k] for k in (1, 8, 9, 12)] == [0, 0, 1, 1]
+
+
+RAGGED = synth.StageConfig(n_layers=2, hidden=72, n_heads=3, ffn=136, seq=50, microbatch=3, m=3, max_inflight=2,
+                           lr=1e-3, min_len=20)
+
+
+@pytest.mark.parametrize("precision", [synth.PREC_FP32, synth.PREC_BF16])
+@pytest.mark.parametrize("mask", [synth.MASK_NONE, synth.MASK_CAUSAL, synth.MASK_PADDING])
+def test_ragged_small_stage(precision, mask):
+    """Nothing is a multiple of a tile: T = 150 tokens, h = 72, head size 24, f = 136."""
+    cfg = RAGGED.with_(precision=precision, mask_mode=mask)
+    gpu, tr = both(cfg, 3, 2, seed=1)
+    worst = compare_stage(cfg, gpu, tr)
+    print(f"ragged prec={precision} mask={mask}:", {k: f"{v:.2e}" for k, v in worst.items()})
+    if mask == synth.MASK_PADDING:          # padded positions get no gradient
+        gen = synth.StageInputs(cfg, 1); gen.weights()
+        for k in range(1, 4):
+            lens = gen.microbatch()[2]
+            for n in range(cfg.microbatch):
+                assert np.all(gpu["dX"][k][n, lens[n]:] == 0.0)
+
+
+@pytest.mark.parametrize("precision", [synth.PREC_FP32, synth.PREC_BF16])
+def test_inflight_depth_and_recompute_do_not_change_results(precision):
+    cfg = RAGGED.with_(precision=precision, mask_mode=synth.MASK_CAUSAL, m=4, max_inflight=4)
+    gen = synth.StageInputs(cfg, 2)
+    w0 = gen.weights()
+    mbs = gen.microbatches(3 * cfg.m)
+    ref = run_stage_gpu(cfg, w0, mbs, 1)
+    tr = run_stage_oracle(cfg, w0, mbs)
+    compare_stage(cfg, ref, tr)
+    for variant in (dict(inflight=4), dict(inflight=2, recompute=1)):
+        c2 = cfg.with_(recompute=variant.get("recompute", 0))
+        out = run_stage_gpu(c2, w0, mbs, variant["inflight"])
+        compare_stage(c2, out, tr)
+        # same kernels on the same data in the same order: the numbers agree to the last bit
+        for k in ref["Y"]:
+            assert np.array_equal(out["Y"][k], ref["Y"][k]) and np.array_equal(out["dX"][k], ref["dX"][k])
+        for a, b in zip(out["snaps"], ref["snaps"]):
+            assert np.array_equal(a["G"], b["G"]) and np.array_equal(a["master"], b["master"])
+    # recomputation keeps one activation set plus the stage inputs (Section 4.1)
+    full = run_stage_gpu(cfg, w0, mbs[:cfg.m], 4, snapshot=False)["bytes"]
+    rec = run_stage_gpu(cfg.with_(recompute=1), w0, mbs[:cfg.m], 4, snapshot=False)["bytes"]
+    assert rec < full
+
+
+def test_bf16_sees_the_weight_version():
+    """With eps = 1 Adam's step is nearly linear in g (no sign sensitivity) and lr = 1 moves the
+    weights by ~5% per update: running a batch on the wrong version then changes G by 15-20%,
+    far outside the 2e-2 bar the correct schedule must meet."""
+    cfg = RAGGED.with_(precision=synth.PREC_BF16, mask_mode=synth.MASK_CAUSAL, lr=1.0, adam_eps=1.0, hidden=64,
+                       n_heads=2, ffn=128, seq=32)
+    gpu, tr = both(cfg, 4, 2, seed=3)
+    compare_stage(cfg, gpu, tr)
+    from oracle import twobw as tb, block as ob
+    st = ob.Stage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.mask_mode, cfg.ln_eps)
+    gen = synth.StageInputs(cfg, 3); w0 = gen.weights(); mbs = gen.microbatches(4 * cfg.m)
+    wrong = tb.replay(lambda w, *mb: st.vjp(w, *mb), w0.astype(np.float64), mbs, cfg.m, tb.Adam(1.0, eps=1.0),
+                      version_rule=tb.weight_version_flush)
+    for t in (1, 2, 3):
+        assert rel(wrong.G[t], tr.G[t]) > 1e-1                      # the oracle separates the two rules
+        assert rel(gpu["snaps"][t]["G"], wrong.G[t]) > 1e-1         # and the GPU is not on the wrong one
+
+
+def test_schedule_errors_leave_the_stage_untouched():
+    cfg = synth.PRESETS["C1"]
+    gen = synth.StageInputs(cfg, 0)
+    w0 = gen.weights()
+    x, dy, _ = gen.microbatch()
+    st = B.Stage(cfg, w0)
+    X, DY = to_dev(x, cfg.precision), to_dev(dy, cfg.precision)
+    Y, DX = torch.empty_like(X), torch.empty_like(X)
+    L = B.lib()
+    assert L.stage_coalesce_update(st.h) == B.ERR_BAD_STATE
+    assert L.stage_swap_versions(st.h) == B.ERR_BAD_STATE
+    assert L.stage_backward(st.h, 1, DY.data_ptr(), DX.data_ptr()) == B.ERR_BAD_STATE
+    assert L.stage_forward(st.h, 9, X.data_ptr(), None, Y.data_ptr()) == B.ERR_BAD_STATE       # needs version 1
+    assert L.stage_forward(st.h, 1, X.data_ptr(), None, X.data_ptr()) == B.ERR_INVALID_ARG     # aliasing
+    st.forward(1, X, None, Y)
+    st.forward(2, X, None, Y)
+    assert L.stage_forward(st.h, 3, X.data_ptr(), None, Y.data_ptr()) == B.ERR_BAD_STATE       # stash full
+    assert st.query(B.Q_INFLIGHT) == 2 and st.query(B.Q_UPDATES) == 0
+    for which in (B.WEIGHTS_BUF0, B.WEIGHTS_BUF1, B.WEIGHTS_MASTER):
+        assert np.array_equal(st.read_weights(which), w0)      # both buffers start as W(0)
+    st.close()
+
+
+def test_memory_report_matches_the_papers_formula():
+    """2 weight versions + in-flight activation stashes (Section 3.1, Memory Footprint)."""
+    cfg = synth.PRESETS["C1"].with_(precision=synth.PREC_BF16)
+    st = B.Stage(cfg, synth.StageInputs(cfg, 0).weights())
+    P = st.n_params
+    assert st.query(B.Q_BYTES_WEIGHTS) >= 2 * 2 * P + 4 * P
+    assert st.query(B.Q_BYTES_WEIGHTS) < 2 * 2 * P + 4 * P + 4096
+    T, h, f = cfg.tokens, cfg.hidden, cfg.ffn
+    per_mb = cfg.n_layers * ((8 * h + 2 * f) * T * 2)
+    stash = st.query(B.Q_BYTES_STASH)
+    assert cfg.max_inflight * per_mb <= stash < cfg.max_inflight * per_mb * 1.2
+    st.close()
