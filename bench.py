@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Throughput of one 2BW pipeline stage on one MI355X.
+
+A "step" is one batch of the stage's steady-state 1F1B stream (Section 3.1 of the paper): m
+forward passes, m backward passes with in-place gradient coalescing, one Adam update into the
+other weight buffer and the version swap, with `max_inflight` microbatches in flight.  The
+default workload is the BERT-Large-shaped stage (6 layers, h=1024, f=4096, s=512, b=8, m=8,
+key-padding mask, bf16 compute with fp32 master weights).
+
+Prints ONE JSON line: stage samples/s (value), model TFLOP/s, fraction of the bf16 MFMA peak,
+a `roofline` object for the dominant kernel class (HIP-event timing of every launch of that
+class inside a second timed region of the same length) and a `cpu_baseline` object (the fp64
+oracle timed on this host on a bounded sample of the same workload).
+
+All inputs are seeded, synthetic and resident in HBM before the clock starts.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def model_flops_per_microbatch(cfg) -> float:
+    """3 x forward FLOPs; attention counted dense (4 b s^2 h per layer), no credit for recompute."""
+    T, h, f, s, b = cfg.tokens, cfg.hidden, cfg.ffn, cfg.seq, cfg.microbatch
+    fwd = cfg.n_layers * (2.0 * T * h * (3 * h) + 2.0 * T * h * h + 4.0 * T * h * f + 4.0 * b * s * s * h)
+    return 3.0 * fwd
+
+
+def cpu_baseline(cfg, seed):
+    """The oracle as it stands on this host: one layer x one microbatch forward+backward plus one
+    Adam step over the stage's parameters, extrapolated linearly in L and m."""
+    import numpy as np
+    from oracle import block as ob
+    from oracle import twobw as tb
+    from paper_2006_09503_amd import synth
+    one = cfg.with_(n_layers=1)
+    gen = synth.StageInputs(one, seed)
+    w = gen.weights().astype(np.float64)
+    x, dy, lens = gen.microbatch()
+    st = ob.Stage(1, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.mask_mode, cfg.ln_eps)
+    t0 = time.perf_counter()
+    st.vjp(w, x, dy, lens)
+    t_layer_mb = time.perf_counter() - t0
+    P = synth.param_count(cfg)
+    rng = np.random.default_rng(seed)
+    wf, g = rng.standard_normal(P), rng.standard_normal(P)
+    opt = tb.Adam(cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps)
+    state = opt.init(wf)
+    t0 = time.perf_counter()
+    opt.step(wf, g, state, 0)
+    t_adam = time.perf_counter() - t0
+    t_step = cfg.n_layers * cfg.m * t_layer_mb + t_adam
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    return {"value": cfg.microbatch * cfg.m / t_step, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"fp64 numpy oracle: 1 layer x 1 microbatch fwd+bwd ({t_layer_mb:.2f} s) and one Adam step over "
+                      f"all {P} parameters ({t_adam:.2f} s), extrapolated linearly to L={cfg.n_layers}, m={cfg.m}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C2", help="C1..C5 (see paper_2006_09503_amd/synth.py)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
+              "(no collectives or multi-GPU sharding are part of it)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2006_09503_amd import binding as B
+    from paper_2006_09503_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.PRESETS[args.workload]
+    p, m = cfg.max_inflight, cfg.m
+    K, W = args.steps, args.warmup
+    assert K >= 1 and W >= 2, "two warm-up batches are needed before the version rule leaves version 0"
+
+    gen = synth.StageInputs(cfg, args.seed)
+    w0 = gen.weights()
+    st = B.Stage(cfg, w0)
+    del w0
+    # a pool of m distinct microbatches, resident in HBM, reused batch after batch
+    dt = torch.bfloat16 if cfg.precision == synth.PREC_BF16 else torch.float32
+    g = torch.Generator(device="cuda").manual_seed(args.seed)
+    shape = (cfg.microbatch, cfg.seq, cfg.hidden)
+    X = [torch.randn(shape, generator=g, device="cuda", dtype=torch.float32).to(dt) for _ in range(m)]
+    DY = [(torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * 1e-2).to(dt) for _ in range(m)]
+    LEN = [None] * m
+    if cfg.mask_mode == synth.MASK_PADDING:
+        LEN = [torch.randint(cfg.min_len, cfg.seq + 1, (cfg.microbatch,), generator=g, device="cuda",
+                             dtype=torch.int32) for _ in range(m)]
+        for j in range(m):
+            keep = torch.arange(cfg.seq, device="cuda")[None, :] < LEN[j][:, None]
+            DY[j] = (DY[j] * keep[:, :, None]).contiguous()
+    Y = [torch.empty(shape, device="cuda", dtype=dt) for _ in range(p + 1)]
+    DX = torch.empty(shape, device="cuda", dtype=dt)
+
+    def iteration(k):
+        """One slot of the worker's 1F1B stream: backward of k-p, maybe update, maybe swap, forward of k."""
+        kb = k - p
+        if kb >= 1:
+            st.backward(kb, DY[(kb - 1) % m], DX)
+            if kb % m == 0:
+                st.coalesce_update()
+        if (k - 1) % m == 0 and (k - 1) // m >= 2:
+            st.swap_versions()
+        st.forward(k, X[(k - 1) % m], LEN[(k - 1) % m], Y[k % (p + 1)])
+
+    def run_steps(first_step, n_steps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(first_step * m + 1, (first_step + n_steps) * m + 1):
+            iteration(k)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    run_steps(0, W)
+    elapsed = run_steps(W, K)
+    ms_per_step = elapsed / K * 1e3
+    samples_per_s = cfg.microbatch * m * K / elapsed
+    flops_step = model_flops_per_microbatch(cfg) * m
+    tflops = flops_step * K / elapsed / 1e12
+
+    roofline, kernels = None, None
+    if not args.no_kernel_timing:
+        launches_per_step = m * cfg.n_layers * 64 + 16
+        st.timing_enable(True, launches_per_step * K + 64)
+        run_steps(W + K, K)
+        tm = st.timing_collect()
+        st.timing_enable(False)
+        kernels = {}
+        for name, r in tm.items():
+            if r["launches"] == 0:
+                continue
+            e = {"launches_per_step": r["launches"] / K, "ms_per_step": r["ms"] / K,
+                 "avg_us": r["ms"] / r["launches"] * 1e3}
+            if r["flops"] > 0:
+                e["tflops"] = r["flops"] / (r["ms"] * 1e-3) / 1e12
+                e["frac_of_bf16_peak"] = e["tflops"] / PEAK_BF16_TFLOPS
+            if r["bytes"] > 0:
+                e["gbs"] = r["bytes"] / (r["ms"] * 1e-3) / 1e9
+                e["frac_of_hbm_peak"] = e["gbs"] / PEAK_HBM_GBS
+            kernels[name] = e
+        gemms = [n for n in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad") if n in kernels]
+        dom = max(gemms, key=lambda n: kernels[n]["ms_per_step"])
+        achieved = kernels[dom]["tflops"]
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                    "avg_launch_us": kernels[dom]["avg_us"],
+                    "flops_per_launch": tm[dom]["flops"] / tm[dom]["launches"]}
+
+    # drain the microbatches still in flight so the stage ends at a batch boundary
+    last = (W + K + (0 if args.no_kernel_timing else K)) * m
+    for kb in range(last - p + 1, last + 1):
+        st.backward(kb, DY[(kb - 1) % m], DX)
+        if kb % m == 0:
+            st.coalesce_update()
+    torch.cuda.synchronize()
+    finite = bool(torch.isfinite(DX.float()).all().item())
+    alloc = st.query(B.Q_BYTES_ALLOCATED)
+    st.close()
+
+    out = {
+        "metric": "stage samples/sec + % bf16 MFMA peak (1 MI355X), 2BW fwd/bwd/update step",
+        "value": samples_per_s, "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.precision == synth.PREC_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: one 2BW stage, L={cfg.n_layers} h={cfg.hidden} a={cfg.n_heads} "
+                               f"f={cfg.ffn} s={cfg.seq} b={cfg.microbatch} m={cfg.m} inflight={p} "
+                               f"mask={('none', 'causal', 'padding')[cfg.mask_mode]} recompute={cfg.recompute}",
+                   "samples_per_step": cfg.microbatch * m, "model_flops_per_step": flops_step,
+                   "stage_bytes_allocated": alloc},
+        "model_tflops": tflops, "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS, "outputs_finite": finite,
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
