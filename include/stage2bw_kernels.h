@@ -74,6 +74,10 @@ int k2bw_adam(int64_t n, const float* w_cur, float* w_next, void* w_next_bf16, f
               const float* G, float lr, float beta1, float beta2, float eps, int m_micro, int64_t step,
               void* stream);
 
+/* Tuning aid: force the bf16 GEMM's workgroup tile (0 = built-in choice; 1: 256x256/4 waves,
+ * 2: 128x128/4, 3: 256x256/8, 4: 256x128/4, 5: 128x256/4, 6: 256x128/8).  Process-wide. */
+int k2bw_tune_gemm_tile(int id);
+
 /* Plain 16-byte copy (bytes multiple of 16): the reference kernel for scaling HBM counters. */
 int k2bw_copy(const void* in, void* out, int64_t bytes, void* stream);
 

@@ -80,6 +80,7 @@ def lib() -> C.CDLL:
             "k2bw_attention_bwd": (C.c_int, [C.c_int] * 6 + [vp, vp, vp, vp, vp, vp, vp, vp]),
             "k2bw_adam": (C.c_int, [i64, vp, vp, vp, vp, vp, vp, f32, f32, f32, f32, C.c_int, i64, vp]),
             "k2bw_copy": (C.c_int, [vp, vp, i64, vp]),
+            "k2bw_tune_gemm_tile": (C.c_int, [C.c_int]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)

@@ -80,6 +80,28 @@ __device__ __forceinline__ float gelu_grad_f(float u) {
   return cdf + u * pdf;
 }
 
+// Branch-free versions for bf16 epilogues: erf by the rational form 1 - poly(t) exp(-x^2),
+// t = 1/(1 + p|x|) (absolute error below 2e-7, far under bf16 resolution), sharing the
+// exponential with the density term of the derivative.
+__device__ __forceinline__ void gelu_parts(float u, float& cdf, float& e) {
+  const float x = fabsf(u) * 0.70710678118654752f;
+  e = __builtin_amdgcn_exp2f(-0.72134752044448170f * u * u);   // exp(-u^2/2)
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float erf_abs = 1.0f - poly * e;
+  cdf = 0.5f * (1.0f + copysignf(erf_abs, u));
+}
+__device__ __forceinline__ float gelu_fast(float u) {
+  float cdf, e;
+  gelu_parts(u, cdf, e);
+  return u * cdf;
+}
+__device__ __forceinline__ float gelu_grad_fast(float u) {
+  float cdf, e;
+  gelu_parts(u, cdf, e);
+  return cdf + u * 0.39894228040143268f * e;
+}
+
 inline int ceil_div(int64_t a, int64_t b) { return static_cast<int>((a + b - 1) / b); }
 
 }  // namespace k2bw

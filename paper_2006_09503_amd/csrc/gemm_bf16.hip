@@ -9,13 +9,18 @@
 //     each thread loads a 4(k) x 8(row) patch with four 16-byte loads along the contiguous
 //     dimension, transposes it in registers and writes eight 8-byte pieces.
 // so the MFMA loop is the same for the forward (NN), data-gradient (NT) and weight-gradient
-// (TN) forms.  Two LDS stages; the global loads of step k+1 are in flight while step k runs
-// on the matrix cores.  Each wave owns a WM x WN sub-tile = (WM/32) x (WN/32) accumulators of
-// 32x32 (16 fp32 registers per lane each).
+// (TN) forms.  Two LDS stages.  Per K step a wave issues the global loads of the next tile
+// first, runs its MFMAs with the LDS fragment reads of sub-step ks+1 in flight behind the MFMAs
+// of sub-step ks, and writes the prefetched tile to the other LDS stage during the last two
+// sub-steps; one barrier per K step.  Out-of-range rows/chunks are loaded from a clamped
+// address and zeroed by select, so the loop has no divergent branches.
 //
-// Lane layout of v_mfma_f32_32x32x16_bf16: lane l supplies row (l % 32) of A and column
-// (l % 32) of B, k = 8*(l/32) .. +7; it receives column (l % 32) of D, rows
-// 8*(r/4) + 4*(l/32) + (r % 4) for accumulator register r.
+// Lane layout of v_mfma_f32_32x32x16_bf16: lane l supplies row (l % 32) of the first operand and
+// column (l % 32) of the second, k = 8*(l/32) .. +7; it receives column (l % 32) of D, rows
+// 8*(r/4) + 4*(l/32) + (r % 4) for accumulator register r.  The kernel feeds the B tile as the
+// first operand and the A tile as the second, i.e. it accumulates C^T blocks: a lane then owns
+// one row m of C and four consecutive columns n per register quad, which makes the epilogue's
+// global accesses 8-byte (bf16) or 16-byte (fp32 accumulator) vectors.
 #include "kernels.hpp"
 
 namespace k2bw {
@@ -37,31 +42,47 @@ struct BfParams {
 // chunk swizzle: conflict-free for 8 or 16 consecutive rows reading the same logical chunk
 __device__ __forceinline__ int swz(int row) { return (row + (row >> 3)) & 7; }
 
+__device__ __forceinline__ uint4 select_zero(bool ok, uint4 v) {
+  v.x = ok ? v.x : 0u; v.y = ok ? v.y : 0u; v.z = ok ? v.z : 0u; v.w = ok ? v.w : 0u;
+  return v;
+}
+
 // Operand with K contiguous in HBM: tile rows = R, 8 chunks of 8 bf16 per row.
 template <int R, int NT>
 struct DirectLoader {
   static constexpr int kIters = R * 8 / NT;
   static_assert(R * 8 % NT == 0, "tile/threads mismatch");
   uint4 regs[kIters];
-  // base: element (row0, k = 0); rows_valid: rows of the tile inside the matrix
-  __device__ __forceinline__ void load(const bf16_t* base, int ld, int rows_valid, int k0, int K, int tid) {
+  const bf16_t* ptr[kIters];   // row base (clamped row), k = 0
+  int lds_idx[kIters];
+  bool row_ok[kIters];
+  int c8;                      // this thread's k offset inside a tile (same for every iter)
+  // base: element (row0, k = 0); rows_valid >= 1: rows of the tile inside the matrix
+  __device__ __forceinline__ void init(const bf16_t* base, int ld, int rows_valid, int tid) {
+    c8 = (tid & 7) * 8;
 #pragma unroll
     for (int i = 0; i < kIters; ++i) {
       const int idx = tid + i * NT;
       const int row = idx >> 3, c = idx & 7;
-      const int k = k0 + c * 8;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (row < rows_valid && k < K) v = *reinterpret_cast<const uint4*>(base + (int64_t)row * ld + k);
-      regs[i] = v;
+      row_ok[i] = row < rows_valid;
+      const int rc = row_ok[i] ? row : rows_valid - 1;
+      ptr[i] = base + (int64_t)rc * ld;
+      lds_idx[i] = row * 8 + (c ^ swz(row));
     }
   }
-  __device__ __forceinline__ void store(uint4* tile, int tid) const {
+  // The zeroing of out-of-range data happens at store time, so that nothing waits on the
+  // loads before the MFMAs of the current tile have been issued.
+  bool k_ok;
+  __device__ __forceinline__ void load(int k0, int K) {
+    const int k = k0 + c8;
+    k_ok = k < K;
+    const int kc = k_ok ? k : K - 8;
 #pragma unroll
-    for (int i = 0; i < kIters; ++i) {
-      const int idx = tid + i * NT;
-      const int row = idx >> 3, c = idx & 7;
-      tile[row * 8 + (c ^ swz(row))] = regs[i];
-    }
+    for (int i = 0; i < kIters; ++i) regs[i] = *reinterpret_cast<const uint4*>(ptr[i] + kc);
+  }
+  __device__ __forceinline__ void store(uint4* tile) const {
+#pragma unroll
+    for (int i = 0; i < kIters; ++i) tile[lds_idx[i]] = select_zero(k_ok && row_ok[i], regs[i]);
   }
 };
 
@@ -76,41 +97,67 @@ struct TransposingLoader {
   static constexpr int kIters = kUnits / NT;
   static_assert(kUnits % NT == 0, "tile/threads mismatch");
   uint4 regs[kIters][4];
-  __device__ __forceinline__ void load(const bf16_t* base, int ld, int rows_valid, int k0, int K, int tid) {
+  const bf16_t* ptr[kIters];   // (clamped) row chunk, k = 0
+  int kq[kIters], rc8[kIters];
+  bool row_ok[kIters];
+  int ld_, k_left;   // k_left: K - k0 of the tile held in regs
+  // rows_valid: multiple of 8, >= 8
+  __device__ __forceinline__ void init(const bf16_t* base, int ld, int rows_valid, int tid) {
+    ld_ = ld;
 #pragma unroll
     for (int i = 0; i < kIters; ++i) {
       const int u = tid + i * NT;
-      const int rc = u % (R / 8), kq = u / (R / 8);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int k = k0 + kq * 4 + j;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (rc * 8 < rows_valid && k < K) v = *reinterpret_cast<const uint4*>(base + (int64_t)k * ld + rc * 8);
-        regs[i][j] = v;
-      }
+      const int rc = u % (R / 8);
+      kq[i] = u / (R / 8);
+      rc8[i] = rc * 8;
+      row_ok[i] = rc * 8 < rows_valid;
+      ptr[i] = base + (row_ok[i] ? rc * 8 : rows_valid - 8);
     }
   }
-  __device__ __forceinline__ void store(uint4* tile, int tid) const {
-    uint2* t2 = reinterpret_cast<uint2*>(tile);
+  __device__ __forceinline__ void load(int k0, int K) {
 #pragma unroll
     for (int i = 0; i < kIters; ++i) {
-      const int u = tid + i * NT;
-      const int rc = u % (R / 8), kq = u / (R / 8);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int k = k0 + kq[i] * 4 + j;
+        const int kc = k < K ? k : K - 1;
+        regs[i][j] = *reinterpret_cast<const uint4*>(ptr[i] + (int64_t)kc * ld_);
+      }
+    }
+    k_left = K - k0;
+  }
+  __device__ __forceinline__ void store(uint4* tile) {
+    uint2* t2 = reinterpret_cast<uint2*>(tile);
+    // zero what lies outside the matrix: whole row chunks always, single k rows only in the
+    // last, partial K tile (uniform branch)
+#pragma unroll
+    for (int i = 0; i < kIters; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) regs[i][j] = select_zero(row_ok[i], regs[i][j]);
+    if (k_left < BK) {
+#pragma unroll
+      for (int i = 0; i < kIters; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) regs[i][j] = select_zero(kq[i] * 4 + j < k_left, regs[i][j]);
+    }
+#pragma unroll
+    for (int i = 0; i < kIters; ++i) {
 #pragma unroll
       for (int ii = 0; ii < 8; ++ii) {
         const int wd = ii >> 1;
         const uint32_t w0 = word(regs[i][0], wd), w1 = word(regs[i][1], wd);
         const uint32_t w2 = word(regs[i][2], wd), w3 = word(regs[i][3], wd);
+        // v_perm_b32 picks bytes from {first operand: bytes 4..7, second operand: bytes 0..3}
         uint2 o;
-        if (ii & 1) {
-          o.x = (w0 >> 16) | (w1 & 0xffff0000u);
-          o.y = (w2 >> 16) | (w3 & 0xffff0000u);
-        } else {
-          o.x = (w0 & 0xffffu) | (w1 << 16);
-          o.y = (w2 & 0xffffu) | (w3 << 16);
+        if (ii & 1) {   // (w0 >> 16) | (w1 & 0xffff0000)
+          o.x = __builtin_amdgcn_perm(w1, w0, 0x07060302u);
+          o.y = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
+        } else {        // (w0 & 0xffff) | (w1 << 16)
+          o.x = __builtin_amdgcn_perm(w1, w0, 0x05040100u);
+          o.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
         }
-        const int row = rc * 8 + ii;
-        t2[(row * 8 + ((kq >> 1) ^ swz(row))) * 2 + (kq & 1)] = o;
+        const int row = rc8[i] + ii;
+        t2[(row * 8 + ((kq[i] >> 1) ^ swz(row))) * 2 + (kq[i] & 1)] = o;
       }
     }
   }
@@ -121,11 +168,20 @@ struct LoaderSel { using type = DirectLoader<R, NT>; };
 template <int R, int NT>
 struct LoaderSel<R, NT, false> { using type = TransposingLoader<R, NT>; };
 
+__device__ __forceinline__ uint2 pack4(const float (&v)[4]) {
+  return make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+}
+__device__ __forceinline__ void unpack4(uint2 w, float (&v)[4]) {
+  v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xffff0000u);
+  v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
+}
+
 template <int BM, int BN, int WM, int WN, bool TA, bool TB, int EPI>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(BfParams p) {
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
   constexpr int MI = WM / 32, NI = WN / 32;
   constexpr int WAVES_N = BN / WN;
+  constexpr int KS = BK / 16;
   extern __shared__ uint4 smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -142,12 +198,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(B
   const int bm = wg / p.tiles_n, bn = wg % p.tiles_n;
   const int m0 = bm * BM, n0 = bn * BN;
 
-  const bf16_t* a_base = TA ? p.A + m0 : p.A + (int64_t)m0 * p.lda;
-  const bf16_t* b_base = TB ? p.B + (int64_t)n0 * p.ldb : p.B + n0;
-  const int a_rows = p.M - m0, b_rows = p.N - n0;
-
   typename LoaderSel<BM, NT, !TA>::type ld_a;
   typename LoaderSel<BN, NT, TB>::type ld_b;
+  ld_a.init(TA ? p.A + m0 : p.A + (int64_t)m0 * p.lda, p.lda, p.M - m0, tid);
+  ld_b.init(TB ? p.B + (int64_t)n0 * p.ldb : p.B + n0, p.ldb, p.N - n0, tid);
 
   constexpr int kStage = (BM + BN) * 8;  // uint4 per stage
   f32x16 acc[MI][NI];
@@ -159,79 +213,110 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(B
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
   const int nk = (p.K + BK - 1) / BK;
-  ld_a.load(a_base, p.lda, a_rows, 0, p.K, tid);
-  ld_b.load(b_base, p.ldb, b_rows, 0, p.K, tid);
-  ld_a.store(smem, tid);
-  ld_b.store(smem + BM * 8, tid);
+  ld_a.load(0, p.K);
+  ld_b.load(0, p.K);
+  ld_a.store(smem);
+  ld_b.store(smem + BM * 8);
   __syncthreads();
 
-  const int a_row0 = wm * WM + (lane & 31);
-  const int b_row0 = wn * WN + (lane & 31);
   const int khalf = lane >> 5;
+  // fragment addresses (uint4 index inside a stage's A / B tile) for sub-step 0; sub-step ks
+  // flips chunk bits: chunk = (2*ks + khalf) ^ swz(row)
+  int a_row[MI], b_row[NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) a_row[mi] = wm * WM + mi * 32 + (lane & 31);
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni) b_row[ni] = wn * WN + ni * 32 + (lane & 31);
 
   for (int kt = 0; kt < nk; ++kt) {
     const uint4* sA = smem + (kt & 1) * kStage;
     const uint4* sB = sA + BM * 8;
+    uint4* dA = smem + ((kt + 1) & 1) * kStage;
     const bool more = kt + 1 < nk;
     if (more) {
-      ld_a.load(a_base, p.lda, a_rows, (kt + 1) * BK, p.K, tid);
-      ld_b.load(b_base, p.ldb, b_rows, (kt + 1) * BK, p.K, tid);
+      ld_a.load((kt + 1) * BK, p.K);
+      ld_b.load((kt + 1) * BK, p.K);
     }
+    bf16x8 af[2][MI], bfr[2][NI];
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[MI], bfr[NI];
+    for (int mi = 0; mi < MI; ++mi)
+      af[0][mi] = __builtin_bit_cast(bf16x8, sA[a_row[mi] * 8 + (khalf ^ swz(a_row[mi]))]);
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi) {
-        const int row = a_row0 + mi * 32;
-        af[mi] = __builtin_bit_cast(bf16x8, sA[row * 8 + ((ks * 2 + khalf) ^ swz(row))]);
-      }
+    for (int ni = 0; ni < NI; ++ni)
+      bfr[0][ni] = __builtin_bit_cast(bf16x8, sB[b_row[ni] * 8 + (khalf ^ swz(b_row[ni]))]);
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) {
-        const int row = b_row0 + ni * 32;
-        bfr[ni] = __builtin_bit_cast(bf16x8, sB[row * 8 + ((ks * 2 + khalf) ^ swz(row))]);
+    for (int ks = 0; ks < KS; ++ks) {
+      const int cur = ks & 1, nxt = cur ^ 1;
+      if (ks + 1 < KS) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+          af[nxt][mi] = __builtin_bit_cast(bf16x8, sA[a_row[mi] * 8 + (((ks + 1) * 2 + khalf) ^ swz(a_row[mi]))]);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+          bfr[nxt][ni] = __builtin_bit_cast(bf16x8, sB[b_row[ni] * 8 + (((ks + 1) * 2 + khalf) ^ swz(b_row[ni]))]);
       }
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
-    }
-    if (more) {
-      uint4* dA = smem + ((kt + 1) & 1) * kStage;
-      ld_a.store(dA, tid);
-      ld_b.store(dA + BM * 8, tid);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
+      if (more && ks == KS - 2) ld_a.store(dA);
+      if (more && ks == KS - 1) ld_b.store(dA + BM * 8);
     }
     __syncthreads();
   }
 
-  // epilogue: lane holds column (lane % 32), rows 8*(r/4) + 4*(lane/32) + r%4 of each 32x32 block
+  // epilogue: lane owns row m = .. + (lane % 32) and, per register quad g, columns
+  // n = .. + 8*g + 4*(lane/32) + 0..3 of each 32x32 block
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
+    const int row = m0 + wm * WM + mi * 32 + (lane & 31);
+    if (row >= p.M) continue;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
-      const int col = n0 + wn * WN + ni * 32 + (lane & 31);
-      if (col >= p.N) continue;
-      float bias = 0.f;
-      if (EPI == kEpiStore || EPI == kEpiGelu) bias = p.bias ? bf16_to_f32(p.bias[col]) : 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * WM + mi * 32 + 8 * (r >> 2) + 4 * khalf + (r & 3);
-        if (row >= p.M) continue;
+      for (int g = 0; g < 4; ++g) {
+        const int col = n0 + wn * WN + ni * 32 + 8 * g + 4 * khalf;
+        if (col >= p.N) continue;   // N is a multiple of 8: a quad is inside or outside as a whole
         const int64_t idx = (int64_t)row * p.ldc + col;
-        float v = acc[mi][ni][r];
+        float v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = acc[mi][ni][4 * g + j];
+        if (EPI == kEpiStore || EPI == kEpiGelu) {
+          if (p.bias) {
+            float b[4];
+            unpack4(*reinterpret_cast<const uint2*>(p.bias + col), b);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] += b[j];
+          }
+        }
         if (EPI == kEpiStore) {
-          v += bias;
-          if (p.aux) v += bf16_to_f32(p.aux[idx]);
-          static_cast<bf16_t*>(p.C)[idx] = f32_to_bf16(v);
+          if (p.aux) {
+            float r[4];
+            unpack4(*reinterpret_cast<const uint2*>(p.aux + idx), r);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] += r[j];
+          }
+          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + idx) = pack4(v);
         } else if (EPI == kEpiGelu) {
-          v += bias;
-          static_cast<bf16_t*>(p.C)[idx] = f32_to_bf16(v);
-          p.aux_out[idx] = f32_to_bf16(gelu_f(v));
+          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + idx) = pack4(v);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = gelu_fast(v[j]);
+          *reinterpret_cast<uint2*>(p.aux_out + idx) = pack4(v);
         } else if (EPI == kEpiGeluGrad) {
-          static_cast<bf16_t*>(p.C)[idx] = f32_to_bf16(v * gelu_grad_f(bf16_to_f32(p.aux[idx])));
+          float u[4];
+          unpack4(*reinterpret_cast<const uint2*>(p.aux + idx), u);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] *= gelu_grad_fast(u[j]);
+          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + idx) = pack4(v);
         } else {
-          float* c = static_cast<float*>(p.C) + idx;
-          *c = p.accumulate ? *c + v : v;
+          float4* c = reinterpret_cast<float4*>(static_cast<float*>(p.C) + idx);
+          float4 o = make_float4(v[0], v[1], v[2], v[3]);
+          if (p.accumulate) {
+            const float4 old = *c;
+            o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
+          }
+          *c = o;
         }
       }
     }
@@ -256,17 +341,35 @@ hipError_t launch(BfParams p, hipStream_t s) {
   return hipGetLastError();
 }
 
+int g_tile_override = 0;  // 0: heuristic; 1..5 force a tile shape (tuning aid)
+
 template <bool TA, bool TB, int EPI>
 hipError_t pick_tile(const BfParams& p, hipStream_t s) {
-  // 256x256 tiles when they still give every CU work; otherwise 128x128.
-  const int64_t big = (int64_t)ceil_div(p.M, 256) * ceil_div(p.N, 256);
-  if (big >= 192) return launch<256, 256, 128, 128, TA, TB, EPI>(p, s);
-  return launch<128, 128, 64, 64, TA, TB, EPI>(p, s);
+  int tile = g_tile_override;
+  if (tile == 0) {
+    // 256x256 tiles when they still give every CU work; otherwise 128x128.
+    const int64_t big = (int64_t)ceil_div(p.M, 256) * ceil_div(p.N, 256);
+    tile = big >= 192 ? 3 : 2;
+  }
+  switch (tile) {
+    case 1: return launch<256, 256, 128, 128, TA, TB, EPI>(p, s);
+    case 2: return launch<128, 128, 64, 64, TA, TB, EPI>(p, s);
+    case 3: return launch<256, 256, 128, 64, TA, TB, EPI>(p, s);   // 8 waves
+    case 4: return launch<256, 128, 128, 64, TA, TB, EPI>(p, s);
+    case 5: return launch<128, 256, 64, 128, TA, TB, EPI>(p, s);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace
 
+void gemm_bf16_set_tile(int id) { g_tile_override = id; }
+
 hipError_t gemm_bf16(const GemmDesc& d, hipStream_t stream) {
+  // 8-byte / 16-byte vector accesses in the epilogue
+  if (d.N % 8 || d.ldc % 8 || (reinterpret_cast<uintptr_t>(d.C) & 15) || (reinterpret_cast<uintptr_t>(d.bias) & 7) ||
+      (reinterpret_cast<uintptr_t>(d.aux) & 7) || (reinterpret_cast<uintptr_t>(d.aux_out) & 7))
+    return hipErrorInvalidValue;
   BfParams p{static_cast<const bf16_t*>(d.A), static_cast<const bf16_t*>(d.B), d.C,
              d.M, d.N, d.K, d.lda, d.ldb, d.ldc, static_cast<const bf16_t*>(d.bias), static_cast<const bf16_t*>(d.aux),
              static_cast<bf16_t*>(d.aux_out), d.accumulate ? 1 : 0, 0, 0};

@@ -216,13 +216,33 @@ __global__ __launch_bounds__(kWg) void colsum_partial_kernel(const T* __restrict
   }
 }
 
+// 16 columns x 16 part-lanes per workgroup: 64-byte segments per part row, 8 loads in flight per
+// thread, then an LDS tree over the part-lanes.
 __global__ __launch_bounds__(kWg) void colsum_finalize_kernel(const float* __restrict__ partial, int parts, int n,
-                                                               float* __restrict__ out, int accumulate) {
-  const int col = blockIdx.x * kWg + threadIdx.x;
-  if (col >= n) return;
+                                                               int ld, float* __restrict__ out, int accumulate) {
+  __shared__ float red[16][17];
+  const int c = threadIdx.x & 15, pl = threadIdx.x >> 4;
+  const int col = blockIdx.x * 16 + c;
   float s = 0.f;
-  for (int p = 0; p < parts; ++p) s += partial[(int64_t)p * n + col];
-  out[col] = accumulate ? out[col] + s : s;
+  if (col < n) {
+    int p = pl;
+    for (; p + 7 * 16 < parts; p += 8 * 16) {
+      float v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = partial[(int64_t)(p + i * 16) * ld + col];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s += v[i];
+    }
+    for (; p < parts; p += 16) s += partial[(int64_t)p * ld + col];
+  }
+  red[pl][c] = s;
+  __syncthreads();
+  if (pl == 0 && col < n) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += red[i][c];
+    out[col] = accumulate ? out[col] + t : t;
+  }
 }
 
 // R, CPT for a row length: the fewest threads per row that keep CPT <= 4, else up to 8.
@@ -335,7 +355,7 @@ hipError_t colsum_partial(const void* y, int rows, int n, int ldy, float* partia
 hipError_t colsum_finalize(const float* partial, int parts, int n, float* out, bool accumulate,
                            hipStream_t stream) {
   if (parts <= 0 || n <= 0 || !partial || !out) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(colsum_finalize_kernel, dim3(ceil_div(n, kWg)), dim3(kWg), 0, stream, partial, parts, n, out,
+  hipLaunchKernelGGL(colsum_finalize_kernel, dim3(ceil_div(n, 16)), dim3(kWg), 0, stream, partial, parts, n, n, out,
                      accumulate ? 1 : 0);
   return hipGetLastError();
 }
