@@ -317,6 +317,17 @@ hipError_t bwd_launch(const AttnDesc& d, const void* qkv, const void* o, const f
 
 }  // namespace
 
+hipError_t attention_delta(const AttnDesc& d, const void* o, const void* d_o, float* delta, hipStream_t st) {
+  const int64_t rows = (int64_t)d.b * d.s * d.a;
+  if (d.dtype == kBF16)
+    hipLaunchKernelGGL((attn_delta_kernel<bf16_t>), dim3(ceil_div(rows, 256)), dim3(256), 0, st,
+                       static_cast<const bf16_t*>(o), static_cast<const bf16_t*>(d_o), delta, d.b, d.s, d.a, d.dh);
+  else
+    hipLaunchKernelGGL((attn_delta_kernel<float>), dim3(ceil_div(rows, 256)), dim3(256), 0, st,
+                       static_cast<const float*>(o), static_cast<const float*>(d_o), delta, d.b, d.s, d.a, d.dh);
+  return hipGetLastError();
+}
+
 hipError_t attention_fwd_simple(const AttnDesc& d, const void* qkv, void* o, float* lse, hipStream_t st) {
   const bool bf = d.dtype == kBF16;
   if (d.dh <= 32) return bf ? fwd_launch<bf16_t, 32>(d, qkv, o, lse, st) : fwd_launch<float, 32>(d, qkv, o, lse, st);
