@@ -5,6 +5,7 @@ namespace k2bw {
 
 hipError_t gemm_f32(const GemmDesc& d, hipStream_t stream);
 hipError_t gemm_bf16(const GemmDesc& d, hipStream_t stream);
+hipError_t gemm_bf16_grouped(const GemmDesc* d, int count, hipStream_t stream);
 hipError_t attention_fwd_simple(const AttnDesc& d, const void* qkv, void* o, float* lse, hipStream_t st);
 hipError_t attention_bwd_simple(const AttnDesc& d, const void* qkv, const void* o, const float* lse,
                                 const void* d_o, void* dqkv, float* delta, hipStream_t st);
@@ -17,7 +18,8 @@ namespace {
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 }
 
-hipError_t gemm(const GemmDesc& d, hipStream_t stream) {
+namespace {
+hipError_t check_gemm(const GemmDesc& d) {
   if (!d.A || !d.B || !d.C || d.M <= 0 || d.N <= 0 || d.K <= 0) return hipErrorInvalidValue;
   // extents of the stored matrices along their contiguous dimension
   const int a_cols = d.trans_a ? d.M : d.K;
@@ -26,12 +28,34 @@ hipError_t gemm(const GemmDesc& d, hipStream_t stream) {
   if (d.epilogue == kEpiGelu && (!d.bias || !d.aux_out)) return hipErrorInvalidValue;
   if (d.epilogue == kEpiGeluGrad && !d.aux) return hipErrorInvalidValue;
   if (d.epilogue < kEpiStore || d.epilogue > kEpiAccum) return hipErrorInvalidValue;
-  if (d.dtype == kF32) return gemm_f32(d, stream);
+  if (d.dtype == kF32) return hipSuccess;
   if (d.dtype != kBF16) return hipErrorInvalidValue;
   // 16-byte vector accesses along the contiguous dimensions
   if (a_cols % 8 || b_cols % 8 || d.lda % 8 || d.ldb % 8 || !aligned16(d.A) || !aligned16(d.B))
     return hipErrorInvalidValue;
-  return gemm_bf16(d, stream);
+  return hipSuccess;
+}
+}  // namespace
+
+hipError_t gemm(const GemmDesc& d, hipStream_t stream) {
+  hipError_t e = check_gemm(d);
+  if (e != hipSuccess) return e;
+  return d.dtype == kF32 ? gemm_f32(d, stream) : gemm_bf16(d, stream);
+}
+
+hipError_t gemm_grouped(const GemmDesc* d, int count, hipStream_t stream) {
+  if (!d || count < 1 || count > 4) return hipErrorInvalidValue;
+  for (int g = 0; g < count; ++g) {
+    hipError_t e = check_gemm(d[g]);
+    if (e != hipSuccess) return e;
+    if (d[g].dtype != d[0].dtype) return hipErrorInvalidValue;
+  }
+  if (d[0].dtype == kBF16) return gemm_bf16_grouped(d, count, stream);
+  for (int g = 0; g < count; ++g) {
+    hipError_t e = gemm_f32(d[g], stream);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 namespace {

@@ -29,7 +29,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 64;
+constexpr int kMaxGroup = 4;   // GEMMs of one form that may share a launch
 
 struct BfParams {
   const bf16_t* A; const bf16_t* B; void* C;
@@ -39,19 +39,39 @@ struct BfParams {
   int tiles_m, tiles_n;
 };
 
-// chunk swizzle: conflict-free for 8 or 16 consecutive rows reading the same logical chunk
-__device__ __forceinline__ int swz(int row) { return (row + (row >> 3)) & 7; }
+// Up to kMaxGroup independent GEMMs of the same form in one launch: workgroup ids
+// [tile_start[g], tile_start[g+1]) belong to problem g.
+struct GroupParams {
+  BfParams p[kMaxGroup];
+  int tile_start[kMaxGroup + 1];
+  int count;
+};
+
+// Chunk swizzle.  Three LDS access patterns have to avoid bank conflicts at once: fragment
+// reads (32 consecutive rows, same logical chunk, 16 bytes per lane), direct stores (the 8 or 16
+// chunks of a row by consecutive lanes) and transposing stores (rows 8 apart, same chunk, 8 bytes
+// per lane).  Rows of 8 chunks are 128 bytes, so two rows share a 256-byte bank line: XOR the
+// chunk with ((row >> 1) ^ (row >> 4)) & 7; rows of 16 chunks: (row ^ (row >> 4)) & 15.
+// Measured with rocprofv3 (SQ_LDS_BANK_CONFLICT, 8192^3): 0 for the form with two direct
+// operands; the transposing stores keep a 2-way conflict (4 cycles per 8-byte store wave-op).
+// Other candidates tried: (row + (row>>3)) & 7, row & 7, ((row>>1) ^ (row>>3)) & 7 cost 4 extra
+// cycles on every fragment read; (row >> 1) & 7 makes the transposing stores 4-way conflicted.
+template <int CH>
+__device__ __forceinline__ int swz(int row) {
+  return CH == 8 ? ((row >> 1) ^ (row >> 4)) & 7 : (row ^ (row >> 4)) & 15;
+}
 
 __device__ __forceinline__ uint4 select_zero(bool ok, uint4 v) {
   v.x = ok ? v.x : 0u; v.y = ok ? v.y : 0u; v.z = ok ? v.z : 0u; v.w = ok ? v.w : 0u;
   return v;
 }
 
-// Operand with K contiguous in HBM: tile rows = R, 8 chunks of 8 bf16 per row.
-template <int R, int NT>
+// Operand with K contiguous in HBM: tile rows = R, CH chunks of 8 bf16 per row.
+template <int R, int NT, int BK>
 struct DirectLoader {
-  static constexpr int kIters = R * 8 / NT;
-  static_assert(R * 8 % NT == 0, "tile/threads mismatch");
+  static constexpr int CH = BK / 8;
+  static constexpr int kIters = R * CH / NT;
+  static_assert(R * CH % NT == 0 && NT % CH == 0, "tile/threads mismatch");
   uint4 regs[kIters];
   const bf16_t* ptr[kIters];   // row base (clamped row), k = 0
   int lds_idx[kIters];
@@ -59,15 +79,15 @@ struct DirectLoader {
   int c8;                      // this thread's k offset inside a tile (same for every iter)
   // base: element (row0, k = 0); rows_valid >= 1: rows of the tile inside the matrix
   __device__ __forceinline__ void init(const bf16_t* base, int ld, int rows_valid, int tid) {
-    c8 = (tid & 7) * 8;
+    c8 = (tid % CH) * 8;
 #pragma unroll
     for (int i = 0; i < kIters; ++i) {
       const int idx = tid + i * NT;
-      const int row = idx >> 3, c = idx & 7;
+      const int row = idx / CH, c = idx % CH;
       row_ok[i] = row < rows_valid;
       const int rc = row_ok[i] ? row : rows_valid - 1;
       ptr[i] = base + (int64_t)rc * ld;
-      lds_idx[i] = row * 8 + (c ^ swz(row));
+      lds_idx[i] = row * CH + (c ^ swz<CH>(row));
     }
   }
   // The zeroing of out-of-range data happens at store time, so that nothing waits on the
@@ -80,7 +100,7 @@ struct DirectLoader {
 #pragma unroll
     for (int i = 0; i < kIters; ++i) regs[i] = *reinterpret_cast<const uint4*>(ptr[i] + kc);
   }
-  __device__ __forceinline__ void store(uint4* tile) const {
+  __device__ __forceinline__ void store(uint4* tile) {
 #pragma unroll
     for (int i = 0; i < kIters; ++i) tile[lds_idx[i]] = select_zero(k_ok && row_ok[i], regs[i]);
   }
@@ -91,8 +111,9 @@ __device__ __forceinline__ uint32_t word(const uint4& v, int i) {
 }
 
 // Operand with the row index contiguous in HBM (element (row, k) at base[k*ld + row]).
-template <int R, int NT>
+template <int R, int NT, int BK>
 struct TransposingLoader {
+  static constexpr int CH = BK / 8;
   static constexpr int kUnits = (BK / 4) * (R / 8);  // 4(k) x 8(row) patches per tile
   static constexpr int kIters = kUnits / NT;
   static_assert(kUnits % NT == 0, "tile/threads mismatch");
@@ -157,16 +178,16 @@ struct TransposingLoader {
           o.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
         }
         const int row = rc8[i] + ii;
-        t2[(row * 8 + ((kq[i] >> 1) ^ swz(row))) * 2 + (kq[i] & 1)] = o;
+        t2[(row * CH + ((kq[i] >> 1) ^ swz<CH>(row))) * 2 + (kq[i] & 1)] = o;
       }
     }
   }
 };
 
-template <int R, int NT, bool K_CONTIGUOUS>
-struct LoaderSel { using type = DirectLoader<R, NT>; };
-template <int R, int NT>
-struct LoaderSel<R, NT, false> { using type = TransposingLoader<R, NT>; };
+template <int R, int NT, int BK, bool K_CONTIGUOUS>
+struct LoaderSel { using type = DirectLoader<R, NT, BK>; };
+template <int R, int NT, int BK>
+struct LoaderSel<R, NT, BK, false> { using type = TransposingLoader<R, NT, BK>; };
 
 __device__ __forceinline__ uint2 pack4(const float (&v)[4]) {
   return make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
@@ -176,9 +197,10 @@ __device__ __forceinline__ void unpack4(uint2 w, float (&v)[4]) {
   v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
 }
 
-template <int BM, int BN, int WM, int WN, bool TA, bool TB, int EPI>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(BfParams p) {
+template <int BM, int BN, int WM, int WN, int BK, bool TA, bool TB, int EPI>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(GroupParams gp) {
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
+  constexpr int CH = BK / 8;
   constexpr int MI = WM / 32, NI = WN / 32;
   constexpr int WAVES_N = BN / WN;
   constexpr int KS = BK / 16;
@@ -189,21 +211,27 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(B
 
   // Workgroup -> tile: consecutive workgroup ids land on different XCDs (round-robin over 8),
   // so give each XCD a contiguous run of tiles: they share A rows / B columns in that XCD's L2.
-  const int n_tiles = p.tiles_m * p.tiles_n;
+  const int n_tiles = gp.tile_start[gp.count];
   int wg = blockIdx.x;
   {
     const int per_xcd = n_tiles / 8;
     if (wg < per_xcd * 8) wg = (wg % 8) * per_xcd + wg / 8;
   }
+  int g = 0;
+#pragma unroll
+  for (int q = 1; q < kMaxGroup; ++q)
+    if (q < gp.count && wg >= gp.tile_start[q]) g = q;
+  const BfParams& p = gp.p[g];
+  wg -= gp.tile_start[g];
   const int bm = wg / p.tiles_n, bn = wg % p.tiles_n;
   const int m0 = bm * BM, n0 = bn * BN;
 
-  typename LoaderSel<BM, NT, !TA>::type ld_a;
-  typename LoaderSel<BN, NT, TB>::type ld_b;
+  typename LoaderSel<BM, NT, BK, !TA>::type ld_a;
+  typename LoaderSel<BN, NT, BK, TB>::type ld_b;
   ld_a.init(TA ? p.A + m0 : p.A + (int64_t)m0 * p.lda, p.lda, p.M - m0, tid);
   ld_b.init(TB ? p.B + (int64_t)n0 * p.ldb : p.B + n0, p.ldb, p.N - n0, tid);
 
-  constexpr int kStage = (BM + BN) * 8;  // uint4 per stage
+  constexpr int kStage = (BM + BN) * CH;  // uint4 per stage
   f32x16 acc[MI][NI];
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi)
@@ -216,7 +244,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(B
   ld_a.load(0, p.K);
   ld_b.load(0, p.K);
   ld_a.store(smem);
-  ld_b.store(smem + BM * 8);
+  ld_b.store(smem + BM * CH);
+  if (nk > 1) {   // tile 1 stays in flight in registers during the first K step
+    ld_a.load(BK, p.K);
+    ld_b.load(BK, p.K);
+  }
   __syncthreads();
 
   const int khalf = lane >> 5;
@@ -228,40 +260,46 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(B
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni) b_row[ni] = wn * WN + ni * 32 + (lane & 31);
 
+  // K step kt: MFMAs on stage kt&1.  In the middle of the step the tile kt+1, whose global loads
+  // were issued one whole step earlier, goes from registers to the other stage, and the loads of
+  // tile kt+2 are issued into the freed registers: they have a full step to arrive.
   for (int kt = 0; kt < nk; ++kt) {
     const uint4* sA = smem + (kt & 1) * kStage;
-    const uint4* sB = sA + BM * 8;
+    const uint4* sB = sA + BM * CH;
     uint4* dA = smem + ((kt + 1) & 1) * kStage;
     const bool more = kt + 1 < nk;
-    if (more) {
-      ld_a.load((kt + 1) * BK, p.K);
-      ld_b.load((kt + 1) * BK, p.K);
-    }
+    const bool more2 = kt + 2 < nk;
     bf16x8 af[2][MI], bfr[2][NI];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
-      af[0][mi] = __builtin_bit_cast(bf16x8, sA[a_row[mi] * 8 + (khalf ^ swz(a_row[mi]))]);
+      af[0][mi] = __builtin_bit_cast(bf16x8, sA[a_row[mi] * CH + (khalf ^ swz<CH>(a_row[mi]))]);
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
-      bfr[0][ni] = __builtin_bit_cast(bf16x8, sB[b_row[ni] * 8 + (khalf ^ swz(b_row[ni]))]);
+      bfr[0][ni] = __builtin_bit_cast(bf16x8, sB[b_row[ni] * CH + (khalf ^ swz<CH>(b_row[ni]))]);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int cur = ks & 1, nxt = cur ^ 1;
       if (ks + 1 < KS) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
-          af[nxt][mi] = __builtin_bit_cast(bf16x8, sA[a_row[mi] * 8 + (((ks + 1) * 2 + khalf) ^ swz(a_row[mi]))]);
+          af[nxt][mi] = __builtin_bit_cast(bf16x8, sA[a_row[mi] * CH + (((ks + 1) * 2 + khalf) ^ swz<CH>(a_row[mi]))]);
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
-          bfr[nxt][ni] = __builtin_bit_cast(bf16x8, sB[b_row[ni] * 8 + (((ks + 1) * 2 + khalf) ^ swz(b_row[ni]))]);
+          bfr[nxt][ni] = __builtin_bit_cast(bf16x8, sB[b_row[ni] * CH + (((ks + 1) * 2 + khalf) ^ swz<CH>(b_row[ni]))]);
       }
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
-      if (more && ks == KS - 2) ld_a.store(dA);
-      if (more && ks == KS - 1) ld_b.store(dA + BM * 8);
+      if (ks == 0 && more) {
+        ld_a.store(dA);
+        if (more2) ld_a.load((kt + 2) * BK, p.K);
+      }
+      if (ks == 1 && more) {
+        ld_b.store(dA + BM * CH);
+        if (more2) ld_b.load((kt + 2) * BK, p.K);
+      }
     }
     __syncthreads();
   }
@@ -323,11 +361,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(B
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool TA, bool TB, int EPI>
-hipError_t launch(BfParams p, hipStream_t s) {
+template <int BM, int BN, int WM, int WN, int BK, bool TA, bool TB, int EPI>
+hipError_t launch(GroupParams gp, hipStream_t s) {
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
-  constexpr size_t lds = 2 * (BM + BN) * 8 * sizeof(uint4);
-  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, TA, TB, EPI>;
+  constexpr size_t lds = 2 * (BM + BN) * (BK / 8) * sizeof(uint4);
+  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, BK, TA, TB, EPI>;
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -335,54 +373,79 @@ hipError_t launch(BfParams p, hipStream_t s) {
     if (e != hipSuccess) return e;
     configured = true;
   }
-  p.tiles_m = ceil_div(p.M, BM);
-  p.tiles_n = ceil_div(p.N, BN);
-  hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n), dim3(NT), lds, s, p);
+  int total = 0;
+  for (int g = 0; g < gp.count; ++g) {
+    gp.p[g].tiles_m = ceil_div(gp.p[g].M, BM);
+    gp.p[g].tiles_n = ceil_div(gp.p[g].N, BN);
+    gp.tile_start[g] = total;
+    total += gp.p[g].tiles_m * gp.p[g].tiles_n;
+  }
+  for (int g = gp.count; g <= kMaxGroup; ++g) gp.tile_start[g] = total;
+  hipLaunchKernelGGL(kern, dim3(total), dim3(NT), lds, s, gp);
   return hipGetLastError();
 }
 
-int g_tile_override = 0;  // 0: heuristic; 1..5 force a tile shape (tuning aid)
+int g_tile_override = 0;  // 0: heuristic; else force a tile shape (tuning aid)
 
 template <bool TA, bool TB, int EPI>
-hipError_t pick_tile(const BfParams& p, hipStream_t s) {
+hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
   int tile = g_tile_override;
   if (tile == 0) {
     // 256x256 tiles when they still give every CU work; otherwise 128x128.
-    const int64_t big = (int64_t)ceil_div(p.M, 256) * ceil_div(p.N, 256);
+    int64_t big = 0;
+    for (int g = 0; g < gp.count; ++g) big += (int64_t)ceil_div(gp.p[g].M, 256) * ceil_div(gp.p[g].N, 256);
     tile = big >= 192 ? 3 : 2;
   }
   switch (tile) {
-    case 1: return launch<256, 256, 128, 128, TA, TB, EPI>(p, s);
-    case 2: return launch<128, 128, 64, 64, TA, TB, EPI>(p, s);
-    case 3: return launch<256, 256, 128, 64, TA, TB, EPI>(p, s);   // 8 waves
-    case 4: return launch<256, 128, 128, 64, TA, TB, EPI>(p, s);
-    case 5: return launch<128, 256, 64, 128, TA, TB, EPI>(p, s);
+    case 1: return launch<256, 256, 128, 128, 64, TA, TB, EPI>(gp, s);
+    case 2: return launch<128, 128, 64, 64, 64, TA, TB, EPI>(gp, s);
+    case 3: return launch<256, 256, 128, 64, 64, TA, TB, EPI>(gp, s);   // 8 waves
+    case 4: return launch<128, 128, 64, 64, 128, TA, TB, EPI>(gp, s);   // deeper K step
+    case 5: return launch<256, 128, 128, 64, 64, TA, TB, EPI>(gp, s);
     default: return hipErrorInvalidValue;
   }
+}
+
+bool vector_ok(const GemmDesc& d) {
+  // 8-byte / 16-byte vector accesses in the epilogue
+  return !(d.N % 8 || d.ldc % 8 || (reinterpret_cast<uintptr_t>(d.C) & 15) || (reinterpret_cast<uintptr_t>(d.bias) & 7) ||
+           (reinterpret_cast<uintptr_t>(d.aux) & 7) || (reinterpret_cast<uintptr_t>(d.aux_out) & 7));
+}
+
+BfParams to_params(const GemmDesc& d) {
+  return BfParams{static_cast<const bf16_t*>(d.A), static_cast<const bf16_t*>(d.B), d.C,
+                  d.M, d.N, d.K, d.lda, d.ldb, d.ldc, static_cast<const bf16_t*>(d.bias),
+                  static_cast<const bf16_t*>(d.aux), static_cast<bf16_t*>(d.aux_out), d.accumulate ? 1 : 0, 0, 0};
 }
 
 }  // namespace
 
 void gemm_bf16_set_tile(int id) { g_tile_override = id; }
 
-hipError_t gemm_bf16(const GemmDesc& d, hipStream_t stream) {
-  // 8-byte / 16-byte vector accesses in the epilogue
-  if (d.N % 8 || d.ldc % 8 || (reinterpret_cast<uintptr_t>(d.C) & 15) || (reinterpret_cast<uintptr_t>(d.bias) & 7) ||
-      (reinterpret_cast<uintptr_t>(d.aux) & 7) || (reinterpret_cast<uintptr_t>(d.aux_out) & 7))
-    return hipErrorInvalidValue;
-  BfParams p{static_cast<const bf16_t*>(d.A), static_cast<const bf16_t*>(d.B), d.C,
-             d.M, d.N, d.K, d.lda, d.ldb, d.ldc, static_cast<const bf16_t*>(d.bias), static_cast<const bf16_t*>(d.aux),
-             static_cast<bf16_t*>(d.aux_out), d.accumulate ? 1 : 0, 0, 0};
-  if (!d.trans_a && !d.trans_b) {
-    if (d.epilogue == kEpiStore) return pick_tile<false, false, kEpiStore>(p, stream);
-    if (d.epilogue == kEpiGelu) return pick_tile<false, false, kEpiGelu>(p, stream);
-  } else if (!d.trans_a && d.trans_b) {
-    if (d.epilogue == kEpiStore) return pick_tile<false, true, kEpiStore>(p, stream);
-    if (d.epilogue == kEpiGeluGrad) return pick_tile<false, true, kEpiGeluGrad>(p, stream);
-  } else if (d.trans_a && !d.trans_b) {
-    if (d.epilogue == kEpiAccum) return pick_tile<true, false, kEpiAccum>(p, stream);
+// `count` GEMMs (1..4) with the same form and epilogue in one launch.
+hipError_t gemm_bf16_grouped(const GemmDesc* d, int count, hipStream_t stream) {
+  if (count < 1 || count > kMaxGroup) return hipErrorInvalidValue;
+  GroupParams gp{};
+  gp.count = count;
+  for (int g = 0; g < count; ++g) {
+    if (!vector_ok(d[g])) return hipErrorInvalidValue;
+    if (d[g].trans_a != d[0].trans_a || d[g].trans_b != d[0].trans_b || d[g].epilogue != d[0].epilogue)
+      return hipErrorInvalidValue;
+    gp.p[g] = to_params(d[g]);
+  }
+  const GemmDesc& f = d[0];
+  if (!f.trans_a && !f.trans_b) {
+    if (f.epilogue == kEpiStore) return pick_tile<false, false, kEpiStore>(gp, stream);
+    if (f.epilogue == kEpiGelu) return pick_tile<false, false, kEpiGelu>(gp, stream);
+  } else if (!f.trans_a && f.trans_b) {
+    if (f.epilogue == kEpiStore) return pick_tile<false, true, kEpiStore>(gp, stream);
+    if (f.epilogue == kEpiGeluGrad) return pick_tile<false, true, kEpiGeluGrad>(gp, stream);
+  } else if (f.trans_a && !f.trans_b) {
+    if (f.epilogue == kEpiAccum) return pick_tile<true, false, kEpiAccum>(gp, stream);
   }
   return hipErrorInvalidValue;  // form/epilogue pair the stage never issues
 }
+
+hipError_t gemm_bf16(const GemmDesc& d, hipStream_t stream) { return gemm_bf16_grouped(&d, 1, stream); }
 
 }  // namespace k2bw

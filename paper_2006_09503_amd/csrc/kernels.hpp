@@ -35,6 +35,8 @@ struct GemmDesc {
   int dtype = kF32;
 };
 hipError_t gemm(const GemmDesc& d, hipStream_t stream);
+// 1..4 independent GEMMs of the same form, epilogue and dtype; bf16 runs them in one launch.
+hipError_t gemm_grouped(const GemmDesc* d, int count, hipStream_t stream);
 
 // ---------------------------------------------------------------------------- LayerNorm
 // y = gain * (x - mean) * rstd + shift over rows of length h; saves mean, rstd (fp32 per row).
@@ -43,7 +45,7 @@ hipError_t layernorm_fwd(const void* x, const void* gain, const void* shift, voi
                          float* mean, float* rstd, int rows, int h, float eps, int dtype,
                          hipStream_t stream);
 // dx = dres + rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)), dxhat = dy * gain;
-// dres may be null.  Column sums sum_r dy*xhat and sum_r dy go to partial[2][parts][h] (fp32);
+// dres may be null.  Column sums go to partial[parts][2h] (fp32; first h: sum_r dy*xhat, then sum_r dy);
 // *parts_out receives the number of partial rows written.  partial must hold
 // 2 * ln_bwd_max_parts() * h floats.
 int ln_bwd_max_parts();

@@ -313,12 +313,20 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     void* dx = (l == 0) ? dx_out : static_cast<void*>(st->dchain[l & 1]);
     hipError_t e;
     GemmDesc g;
+    // The four weight-gradient products of a layer are independent of the data-gradient chain
+    // once their operands exist, and each is small for 256 CUs: they are collected and issued as
+    // one grouped launch at the end of the layer (all operands are still intact then).
+    GemmDesc wg[4];
+    int n_wg = 0;
+    double wg_flops = 0.0;
     auto wgrad = [&](const void* act, int M, const void* grad, int N, float* out) {
-      GemmDesc w;
+      GemmDesc& w = wg[n_wg++];
+      w = GemmDesc();
       w.dtype = st->dtype;
       w.A = act; w.lda = M; w.trans_a = true; w.B = grad; w.ldb = N; w.C = out; w.ldc = N;
       w.M = M; w.N = N; w.K = T; w.epilogue = kEpiAccum; w.accumulate = acc;
-      return run_gemm(st, STAGE_K_GEMM_WGRAD, w);
+      wg_flops += 2.0 * M * N * T;
+      return hipSuccess;
     };
     auto dgrad = [&](const void* grad, int N, const char* w_, int K, void* out, const void* u) {
       // out[T,K] = grad[T,N] * W[K,N]^T
@@ -355,6 +363,8 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     e = dgrad(st->dqkv, 3 * h, wptr(st, buf, o.wqkv), h, st->tmp_h, nullptr);  if (e != hipSuccess) return e;
     // a = LN1(x); dx = dx1 + LN1'(da)
     e = run_ln_bwd(st, st->tmp_h, A.x, A.mean1, A.rstd1, wptr(st, buf, o.ln1_g), st->dx1, dx, st->G + o.ln1_g, acc);
+    if (e != hipSuccess) return e;
+    e = timed(st, STAGE_K_GEMM_WGRAD, wg_flops, 0.0, [&] { return gemm_grouped(wg, n_wg, st->stream); });
     if (e != hipSuccess) return e;
     dy = dx;
     (void)g;
