@@ -73,12 +73,14 @@ struct DirectLoader {
   static constexpr int kIters = R * CH / NT;
   static_assert(R * CH % NT == 0 && NT % CH == 0, "tile/threads mismatch");
   uint4 regs[kIters];
-  const bf16_t* ptr[kIters];   // row base (clamped row), k = 0
+  const bf16_t* base_;         // uniform: element (row0, k = 0)
+  uint32_t off[kIters];        // (clamped row) * ld, in elements: 32-bit offsets from base_
   int lds_idx[kIters];
   bool row_ok[kIters];
   int c8;                      // this thread's k offset inside a tile (same for every iter)
   // base: element (row0, k = 0); rows_valid >= 1: rows of the tile inside the matrix
   __device__ __forceinline__ void init(const bf16_t* base, int ld, int rows_valid, int tid) {
+    base_ = base;
     c8 = (tid % CH) * 8;
 #pragma unroll
     for (int i = 0; i < kIters; ++i) {
@@ -86,23 +88,40 @@ struct DirectLoader {
       const int row = idx / CH, c = idx % CH;
       row_ok[i] = row < rows_valid;
       const int rc = row_ok[i] ? row : rows_valid - 1;
-      ptr[i] = base + (int64_t)rc * ld;
+      off[i] = (uint32_t)rc * (uint32_t)ld;
       lds_idx[i] = row * CH + (c ^ swz<CH>(row));
     }
   }
   // The zeroing of out-of-range data happens at store time, so that nothing waits on the
   // loads before the MFMAs of the current tile have been issued.
-  bool k_ok;
-  __device__ __forceinline__ void load(int k0, int K) {
+  bool k_ok[kIters];
+  __device__ __forceinline__ void load_one(int i, int k0, int K) {
     const int k = k0 + c8;
-    k_ok = k < K;
-    const int kc = k_ok ? k : K - 8;
+    k_ok[i] = k < K;
+    regs[i] = *reinterpret_cast<const uint4*>(base_ + (off[i] + (uint32_t)(k_ok[i] ? k : K - 8)));
+  }
+  __device__ __forceinline__ void load(int k0, int K) {
 #pragma unroll
-    for (int i = 0; i < kIters; ++i) regs[i] = *reinterpret_cast<const uint4*>(ptr[i] + kc);
+    for (int i = 0; i < kIters; ++i) load_one(i, k0, K);
   }
   __device__ __forceinline__ void store(uint4* tile) {
 #pragma unroll
-    for (int i = 0; i < kIters; ++i) tile[lds_idx[i]] = select_zero(k_ok && row_ok[i], regs[i]);
+    for (int i = 0; i < kIters; ++i) tile[lds_idx[i]] = select_zero(k_ok[i] && row_ok[i], regs[i]);
+  }
+  // Slice `part` of `nparts` of the per-step work: store this slice of the tile held in
+  // registers, then refill those registers with the tile at k0_next.  Spreading the slices over
+  // the MFMA sub-steps keeps LDS stores from queueing up in front of the fragment reads.
+  // Unconditional on purpose (past the end the loads read a clamped, valid address and the
+  // stores fill a stage nobody reads): with no branches in the K loop the compiler can count
+  // outstanding loads exactly instead of waiting for all of them before every store.
+  __device__ __forceinline__ void step(int part, int nparts, uint4* tile, int k0_next, int K) {
+    static_assert(kIters % 2 == 0, "");
+#pragma unroll
+    for (int i = 0; i < kIters; ++i) {
+      if (i * nparts / kIters != part) continue;
+      tile[lds_idx[i]] = select_zero(k_ok[i] && row_ok[i], regs[i]);
+      load_one(i, k0_next, K);
+    }
   }
 };
 
@@ -118,13 +137,16 @@ struct TransposingLoader {
   static constexpr int kIters = kUnits / NT;
   static_assert(kUnits % NT == 0, "tile/threads mismatch");
   uint4 regs[kIters][4];
-  const bf16_t* ptr[kIters];   // (clamped) row chunk, k = 0
+  const bf16_t* base_;         // uniform: element (row0, k = 0)
+  uint32_t off[kIters];        // (clamped) row chunk, in elements
   int kq[kIters], rc8[kIters];
   bool row_ok[kIters];
-  int ld_, k_left;   // k_left: K - k0 of the tile held in regs
+  int ld_;
+  int k_left[kIters];   // K - k0 of the tile held in regs[i]
   // rows_valid: multiple of 8, >= 8
   __device__ __forceinline__ void init(const bf16_t* base, int ld, int rows_valid, int tid) {
     ld_ = ld;
+    base_ = base;
 #pragma unroll
     for (int i = 0; i < kIters; ++i) {
       const int u = tid + i * NT;
@@ -132,54 +154,63 @@ struct TransposingLoader {
       kq[i] = u / (R / 8);
       rc8[i] = rc * 8;
       row_ok[i] = rc * 8 < rows_valid;
-      ptr[i] = base + (row_ok[i] ? rc * 8 : rows_valid - 8);
+      off[i] = (uint32_t)(row_ok[i] ? rc * 8 : rows_valid - 8);
     }
+  }
+  __device__ __forceinline__ void load_one(int i, int k0, int K) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int k = k0 + kq[i] * 4 + j;
+      const int kc = k < K ? k : K - 1;
+      regs[i][j] = *reinterpret_cast<const uint4*>(base_ + (off[i] + (uint32_t)kc * (uint32_t)ld_));
+    }
+    k_left[i] = K - k0;
   }
   __device__ __forceinline__ void load(int k0, int K) {
 #pragma unroll
-    for (int i = 0; i < kIters; ++i) {
+    for (int i = 0; i < kIters; ++i) load_one(i, k0, K);
+  }
+  // zero what lies outside the matrix (row chunks past the edge, k rows past K); branch-free
+  __device__ __forceinline__ void mask_one(int i) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int k = k0 + kq[i] * 4 + j;
-        const int kc = k < K ? k : K - 1;
-        regs[i][j] = *reinterpret_cast<const uint4*>(ptr[i] + (int64_t)kc * ld_);
-      }
+    for (int j = 0; j < 4; ++j) regs[i][j] = select_zero(row_ok[i] && (kq[i] * 4 + j < k_left[i]), regs[i][j]);
+  }
+  __device__ __forceinline__ void store_piece(int i, int ii, uint2* t2) const {
+    const int wd = ii >> 1;
+    const uint32_t w0 = word(regs[i][0], wd), w1 = word(regs[i][1], wd);
+    const uint32_t w2 = word(regs[i][2], wd), w3 = word(regs[i][3], wd);
+    // v_perm_b32 picks bytes from {first operand: bytes 4..7, second operand: bytes 0..3}
+    uint2 o;
+    if (ii & 1) {   // (w0 >> 16) | (w1 & 0xffff0000)
+      o.x = __builtin_amdgcn_perm(w1, w0, 0x07060302u);
+      o.y = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
+    } else {        // (w0 & 0xffff) | (w1 << 16)
+      o.x = __builtin_amdgcn_perm(w1, w0, 0x05040100u);
+      o.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
     }
-    k_left = K - k0;
+    const int row = rc8[i] + ii;
+    t2[(row * CH + ((kq[i] >> 1) ^ swz<CH>(row))) * 2 + (kq[i] & 1)] = o;
   }
   __device__ __forceinline__ void store(uint4* tile) {
     uint2* t2 = reinterpret_cast<uint2*>(tile);
-    // zero what lies outside the matrix: whole row chunks always, single k rows only in the
-    // last, partial K tile (uniform branch)
-#pragma unroll
-    for (int i = 0; i < kIters; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) regs[i][j] = select_zero(row_ok[i], regs[i][j]);
-    if (k_left < BK) {
-#pragma unroll
-      for (int i = 0; i < kIters; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) regs[i][j] = select_zero(kq[i] * 4 + j < k_left, regs[i][j]);
-    }
 #pragma unroll
     for (int i = 0; i < kIters; ++i) {
+      mask_one(i);
 #pragma unroll
-      for (int ii = 0; ii < 8; ++ii) {
-        const int wd = ii >> 1;
-        const uint32_t w0 = word(regs[i][0], wd), w1 = word(regs[i][1], wd);
-        const uint32_t w2 = word(regs[i][2], wd), w3 = word(regs[i][3], wd);
-        // v_perm_b32 picks bytes from {first operand: bytes 4..7, second operand: bytes 0..3}
-        uint2 o;
-        if (ii & 1) {   // (w0 >> 16) | (w1 & 0xffff0000)
-          o.x = __builtin_amdgcn_perm(w1, w0, 0x07060302u);
-          o.y = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
-        } else {        // (w0 & 0xffff) | (w1 << 16)
-          o.x = __builtin_amdgcn_perm(w1, w0, 0x05040100u);
-          o.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
-        }
-        const int row = rc8[i] + ii;
-        t2[(row * CH + ((kq[i] >> 1) ^ swz<CH>(row))) * 2 + (kq[i] & 1)] = o;
-      }
+      for (int ii = 0; ii < 8; ++ii) store_piece(i, ii, t2);
+    }
+  }
+  // see DirectLoader::step; a patch's registers are refilled once its eighth piece is stored
+  __device__ __forceinline__ void step(int part, int nparts, uint4* tile, int k0_next, int K) {
+    uint2* t2 = reinterpret_cast<uint2*>(tile);
+    constexpr int S = kIters * 8;
+#pragma unroll
+    for (int sidx = 0; sidx < S; ++sidx) {
+      if (sidx * nparts / S != part) continue;
+      const int i = sidx / 8, ii = sidx % 8;
+      if (ii == 0) mask_one(i);
+      store_piece(i, ii, t2);
+      if (ii == 7) load_one(i, k0_next, K);
     }
   }
 };
@@ -204,6 +235,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
   constexpr int MI = WM / 32, NI = WN / 32;
   constexpr int WAVES_N = BN / WN;
   constexpr int KS = BK / 16;
+  constexpr bool kFragDbuf = NT <= 256;
   extern __shared__ uint4 smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -245,10 +277,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
   ld_b.load(0, p.K);
   ld_a.store(smem);
   ld_b.store(smem + BM * CH);
-  if (nk > 1) {   // tile 1 stays in flight in registers during the first K step
-    ld_a.load(BK, p.K);
-    ld_b.load(BK, p.K);
-  }
+  ld_a.load(BK, p.K);   // tile 1 stays in flight in registers during the first K step
+  ld_b.load(BK, p.K);
   __syncthreads();
 
   const int khalf = lane >> 5;
@@ -267,39 +297,42 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
     const uint4* sA = smem + (kt & 1) * kStage;
     const uint4* sB = sA + BM * CH;
     uint4* dA = smem + ((kt + 1) & 1) * kStage;
-    const bool more = kt + 1 < nk;
-    const bool more2 = kt + 2 < nk;
-    bf16x8 af[2][MI], bfr[2][NI];
+    // With one wave per SIMD (4-wave configurations) the fragments of sub-step ks+1 are read
+    // while the MFMAs of sub-step ks run; with two waves per SIMD the other wave covers the LDS
+    // latency and the registers are better spent elsewhere.
+    constexpr int FB = kFragDbuf ? 2 : 1;
+    bf16x8 af[FB][MI], bfr[FB][NI];
+    if (kFragDbuf) {
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-      af[0][mi] = __builtin_bit_cast(bf16x8, sA[a_row[mi] * CH + (khalf ^ swz<CH>(a_row[mi]))]);
+      for (int mi = 0; mi < MI; ++mi)
+        af[0][mi] = __builtin_bit_cast(bf16x8, sA[a_row[mi] * CH + (khalf ^ swz<CH>(a_row[mi]))]);
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-      bfr[0][ni] = __builtin_bit_cast(bf16x8, sB[b_row[ni] * CH + (khalf ^ swz<CH>(b_row[ni]))]);
+      for (int ni = 0; ni < NI; ++ni)
+        bfr[0][ni] = __builtin_bit_cast(bf16x8, sB[b_row[ni] * CH + (khalf ^ swz<CH>(b_row[ni]))]);
+    }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const int cur = ks & 1, nxt = cur ^ 1;
-      if (ks + 1 < KS) {
+      const int cur = kFragDbuf ? (ks & 1) : 0, nxt = kFragDbuf ? (cur ^ 1) : 0;
+      const int kr = kFragDbuf ? ks + 1 : ks;   // sub-step whose fragments are read now
+      if (kr < KS) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
-          af[nxt][mi] = __builtin_bit_cast(bf16x8, sA[a_row[mi] * CH + (((ks + 1) * 2 + khalf) ^ swz<CH>(a_row[mi]))]);
+          af[nxt][mi] = __builtin_bit_cast(bf16x8, sA[a_row[mi] * CH + ((kr * 2 + khalf) ^ swz<CH>(a_row[mi]))]);
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
-          bfr[nxt][ni] = __builtin_bit_cast(bf16x8, sB[b_row[ni] * CH + (((ks + 1) * 2 + khalf) ^ swz<CH>(b_row[ni]))]);
+          bfr[nxt][ni] = __builtin_bit_cast(bf16x8, sB[b_row[ni] * CH + ((kr * 2 + khalf) ^ swz<CH>(b_row[ni]))]);
       }
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
-      if (ks == 0 && more) {
-        ld_a.store(dA);
-        if (more2) ld_a.load((kt + 2) * BK, p.K);
-      }
-      if (ks == 1 && more) {
-        ld_b.store(dA + BM * CH);
-        if (more2) ld_b.load((kt + 2) * BK, p.K);
-      }
+      // sub-steps 0..KS/2-1 move slices of the A tile, the rest slices of the B tile
+      if (ks < KS / 2) ld_a.step(ks, KS / 2, dA, (kt + 2) * BK, p.K);
+      else ld_b.step(ks - KS / 2, KS / 2, dA + BM * CH, (kt + 2) * BK, p.K);
+      // keep each slice's stores and loads inside its sub-step: left alone, the scheduler sinks
+      // every global load to the end of the K step and hoists the selects that wait for them
+      __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
   }
@@ -391,10 +424,14 @@ template <bool TA, bool TB, int EPI>
 hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
   int tile = g_tile_override;
   if (tile == 0) {
-    // 256x256 tiles when they still give every CU work; otherwise 128x128.
+    // Measured on MI355X (M = 4096..8192): 128x128 tiles with two workgroups per CU win until the
+    // problem fills the chip several times over with 256x256 tiles; then the 8-wave 256x256
+    // kernel is fastest when both operands are K-contiguous, the 4-wave one (512 registers per
+    // lane, no spills in the transposing loaders) otherwise.
     int64_t big = 0;
     for (int g = 0; g < gp.count; ++g) big += (int64_t)ceil_div(gp.p[g].M, 256) * ceil_div(gp.p[g].N, 256);
-    tile = big >= 192 ? 3 : 2;
+    if (!TA && TB) tile = big >= 192 ? 3 : 2;
+    else tile = big >= 512 ? 1 : 2;
   }
   switch (tile) {
     case 1: return launch<256, 256, 128, 128, 64, TA, TB, EPI>(gp, s);
