@@ -62,6 +62,15 @@ hipError_t colsum_partial(const void* y, int rows, int n, int ldy, float* partia
 hipError_t colsum_finalize(const float* partial, int parts, int n, float* out, bool accumulate,
                            hipStream_t stream);
 
+// Grouped forms: column sums of up to 4 matrices [rows, n_i] in one launch into
+// partial[parts][sum n_i] (segment i starts at column sum_{j<i} n_j), and the final reduction
+// of up to 8 (partial, out) pairs in one launch.
+struct ColsumItem { const void* y; int n; int ld; };
+hipError_t colsum_partial_grouped(const ColsumItem* items, int count, int rows, float* partial, int* parts_out,
+                                  int* total_cols_out, int dtype, hipStream_t stream);
+struct FinalizeItem { const float* partial; int parts; int ld; int n; float* out; };
+hipError_t colsum_finalize_grouped(const FinalizeItem* items, int count, bool accumulate, hipStream_t stream);
+
 // ---------------------------------------------------------------------------- attention
 // qkv: [b*s, 3h] rows = tokens, columns Q|K|V each head-major (head size dh = h/a).
 // o: [b*s, h]; lse: [b, a, s] fp32 (log-sum-exp of the scaled, masked scores).

@@ -12,6 +12,19 @@ namespace {
 
 constexpr int kWg = 256;
 
+struct ColsumGroup {
+  const void* y[4];
+  int n[4], ld[4], block0[4], col0[4];
+  int count, rows, rows_per_part, total_cols;
+  float* partial;
+};
+struct FinalizeGroup {
+  const float* partial[8];
+  float* out[8];
+  int parts[8], n[8], ld[8], block0[8];
+  int count, accumulate;
+};
+
 // sum over the R threads that share a row; R == 64 needs no LDS
 template <int R>
 __device__ __forceinline__ float group_sum(float v, float* red, int tid) {
@@ -245,6 +258,80 @@ __global__ __launch_bounds__(kWg) void colsum_finalize_kernel(const float* __res
   }
 }
 
+// Column sums of up to 4 matrices with the same row count in one launch: blockIdx.x walks the
+// 256-column blocks of all segments, blockIdx.y the row slabs.  partial is [parts][total_cols]:
+// segment s owns columns [col0_s, col0_s + n_s).
+template <typename T>
+__global__ __launch_bounds__(kWg) void colsum_partial_grouped_kernel(ColsumGroup g) {
+  __shared__ float comb[7][8][32];
+  int sidx = 0;
+#pragma unroll
+  for (int q = 1; q < 4; ++q)
+    if (q < g.count && (int)blockIdx.x >= g.block0[q]) sidx = q;
+  const T* y = static_cast<const T*>(g.y[sidx]);
+  const int n = g.n[sidx], ld = g.ld[sidx];
+  const int tid = threadIdx.x;
+  const int cc = tid % 32, rl = tid / 32;
+  const int col = ((blockIdx.x - g.block0[sidx]) * 32 + cc) * 8;
+  const int r0 = blockIdx.y * g.rows_per_part;
+  const int r1 = min(g.rows, r0 + g.rows_per_part);
+  float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (col < n) {
+    for (int r = r0 + rl; r < r1; r += 8) {
+      float v[8];
+      load8(y + (int64_t)r * ld + col, v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s[i] += v[i];
+    }
+  }
+  if (rl > 0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) comb[rl - 1][i][cc] = s[i];
+  }
+  __syncthreads();
+  if (rl == 0 && col < n) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int rr = 0; rr < 7; ++rr) s[i] += comb[rr][i][cc];
+    store8(g.partial + (int64_t)blockIdx.y * g.total_cols + g.col0[sidx] + col, s);
+  }
+}
+
+// out_s[n_s] (+)= sum over parts_s rows of partial_s, for up to 8 segments in one launch
+__global__ __launch_bounds__(kWg) void colsum_finalize_grouped_kernel(FinalizeGroup g) {
+  __shared__ float red[16][17];
+  int sidx = 0;
+#pragma unroll
+  for (int q = 1; q < 8; ++q)
+    if (q < g.count && (int)blockIdx.x >= g.block0[q]) sidx = q;
+  const float* partial = g.partial[sidx];
+  const int parts = g.parts[sidx], n = g.n[sidx], ld = g.ld[sidx];
+  const int c = threadIdx.x & 15, pl = threadIdx.x >> 4;
+  const int col = (blockIdx.x - g.block0[sidx]) * 16 + c;
+  float s = 0.f;
+  if (col < n) {
+    int p = pl;
+    for (; p + 7 * 16 < parts; p += 8 * 16) {
+      float v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = partial[(int64_t)(p + i * 16) * ld + col];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s += v[i];
+    }
+    for (; p < parts; p += 16) s += partial[(int64_t)p * ld + col];
+  }
+  red[pl][c] = s;
+  __syncthreads();
+  if (pl == 0 && col < n) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += red[i][c];
+    float* out = g.out[sidx];
+    out[col] = g.accumulate ? out[col] + t : t;
+  }
+}
+
 // R, CPT for a row length: the fewest threads per row that keep CPT <= 4, else up to 8.
 struct RowShape { int R, CPT; };
 RowShape row_shape(int h) {
@@ -357,6 +444,54 @@ hipError_t colsum_finalize(const float* partial, int parts, int n, float* out, b
   if (parts <= 0 || n <= 0 || !partial || !out) return hipErrorInvalidValue;
   hipLaunchKernelGGL(colsum_finalize_kernel, dim3(ceil_div(n, 16)), dim3(kWg), 0, stream, partial, parts, n, n, out,
                      accumulate ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t colsum_partial_grouped(const ColsumItem* items, int count, int rows, float* partial, int* parts_out,
+                                  int* total_cols_out, int dtype, hipStream_t stream) {
+  if (!items || count < 1 || count > 4 || rows <= 0 || !partial || !parts_out || !total_cols_out || !aligned16(partial))
+    return hipErrorInvalidValue;
+  ColsumGroup g{};
+  g.count = count;
+  int blocks = 0, cols = 0;
+  for (int i = 0; i < count; ++i) {
+    const ColsumItem& it = items[i];
+    if (!it.y || it.n <= 0 || it.n % 8 || it.ld % 8 || it.ld < it.n || !aligned16(it.y)) return hipErrorInvalidValue;
+    g.y[i] = it.y; g.n[i] = it.n; g.ld[i] = it.ld; g.block0[i] = blocks; g.col0[i] = cols;
+    blocks += ceil_div(it.n, 256);
+    cols += it.n;
+  }
+  int parts = ceil_div(rows, 64);
+  if (parts > colsum_max_parts()) parts = colsum_max_parts();
+  g.rows = rows;
+  g.rows_per_part = ceil_div(rows, parts);
+  parts = ceil_div(rows, g.rows_per_part);
+  g.total_cols = cols;
+  g.partial = partial;
+  dim3 grid(blocks, parts);
+  if (dtype == kBF16)
+    hipLaunchKernelGGL((colsum_partial_grouped_kernel<bf16_t>), grid, dim3(kWg), 0, stream, g);
+  else
+    hipLaunchKernelGGL((colsum_partial_grouped_kernel<float>), grid, dim3(kWg), 0, stream, g);
+  *parts_out = parts;
+  *total_cols_out = cols;
+  return hipGetLastError();
+}
+
+hipError_t colsum_finalize_grouped(const FinalizeItem* items, int count, bool accumulate, hipStream_t stream) {
+  if (!items || count < 1 || count > 8) return hipErrorInvalidValue;
+  FinalizeGroup g{};
+  g.count = count;
+  g.accumulate = accumulate ? 1 : 0;
+  int blocks = 0;
+  for (int i = 0; i < count; ++i) {
+    const FinalizeItem& it = items[i];
+    if (!it.partial || !it.out || it.parts <= 0 || it.n <= 0 || it.ld < it.n) return hipErrorInvalidValue;
+    g.partial[i] = it.partial; g.parts[i] = it.parts; g.n[i] = it.n; g.ld[i] = it.ld; g.out[i] = it.out;
+    g.block0[i] = blocks;
+    blocks += ceil_div(it.n, 16);
+  }
+  hipLaunchKernelGGL(colsum_finalize_grouped_kernel, dim3(blocks), dim3(kWg), 0, stream, g);
   return hipGetLastError();
 }
 

@@ -75,7 +75,7 @@ struct stage2bw {
   // backward workspace
   char *tmp_h = nullptr, *dx1 = nullptr, *dchain[2] = {nullptr, nullptr}, *du = nullptr, *dqkv = nullptr;
   char* y_scratch = nullptr;  // recompute: output of the re-run forward
-  float *delta = nullptr, *ln_partial = nullptr, *cs_partial = nullptr;
+  float *delta = nullptr, *ln_partial = nullptr, *ln_partial2 = nullptr, *cs_partial = nullptr;
 
   // timing
   bool timing = false;
@@ -219,29 +219,14 @@ hipError_t run_ln_fwd(stage2bw* st, const void* x, const void* gain, const void*
   });
 }
 
-// LayerNorm backward + its two parameter gradients (gain | shift are adjacent in G).
+// LayerNorm backward; its two parameter gradients (gain | shift are adjacent in G) are left as
+// per-workgroup partial rows in `partial` and reduced at the end of the layer.
 hipError_t run_ln_bwd(stage2bw* st, const void* dy, const void* x, const float* mean, const float* rstd,
-                      const void* gain, const void* dres, void* dx, float* g_gain, bool accumulate) {
+                      const void* gain, const void* dres, void* dx, float* partial, int* parts) {
   const int h = st->cfg.hidden;
-  int parts = 0;
   const double bytes = 4.0 * st->T * h * st->esize + 8.0 * st->T;
-  hipError_t e = timed(st, STAGE_K_LN_BWD, 0.0, bytes, [&] {
-    return layernorm_bwd(dy, x, mean, rstd, gain, dres, dx, st->ln_partial, &parts, st->T, h, st->dtype, st->stream);
-  });
-  if (e != hipSuccess) return e;
-  return timed(st, STAGE_K_BIAS_GRAD, 0.0, 4.0 * parts * 2 * h, [&] {
-    return colsum_finalize(st->ln_partial, parts, 2 * h, g_gain, accumulate, st->stream);
-  });
-}
-
-hipError_t run_bias_grad(stage2bw* st, const void* dy, int n, float* g_bias, bool accumulate) {
-  int parts = 0;
-  hipError_t e = timed(st, STAGE_K_BIAS_GRAD, 0.0, (double)st->T * n * st->esize, [&] {
-    return colsum_partial(dy, st->T, n, n, st->cs_partial, &parts, st->dtype, st->stream);
-  });
-  if (e != hipSuccess) return e;
-  return timed(st, STAGE_K_BIAS_GRAD, 0.0, 4.0 * parts * n, [&] {
-    return colsum_finalize(st->cs_partial, parts, n, g_bias, accumulate, st->stream);
+  return timed(st, STAGE_K_LN_BWD, 0.0, bytes, [&] {
+    return layernorm_bwd(dy, x, mean, rstd, gain, dres, dx, partial, parts, st->T, h, st->dtype, st->stream);
   });
 }
 
@@ -339,18 +324,16 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     };
     // y = x1 + GELU(u) W2 + b2
     e = wgrad(A.g, f, dy, h, st->G + o.w2);                              if (e != hipSuccess) return e;
-    e = run_bias_grad(st, dy, h, st->G + o.b2, acc);                     if (e != hipSuccess) return e;
     e = dgrad(dy, h, wptr(st, buf, o.w2), f, st->du, A.u);               if (e != hipSuccess) return e;
     // u = c W1 + b1
     e = wgrad(A.c, h, st->du, f, st->G + o.w1);                          if (e != hipSuccess) return e;
-    e = run_bias_grad(st, st->du, f, st->G + o.b1, acc);                 if (e != hipSuccess) return e;
     e = dgrad(st->du, f, wptr(st, buf, o.w1), h, st->tmp_h, nullptr);    if (e != hipSuccess) return e;
     // c = LN2(x1); dx1 = dy + LN2'(dc)
-    e = run_ln_bwd(st, st->tmp_h, A.x1, A.mean2, A.rstd2, wptr(st, buf, o.ln2_g), dy, st->dx1, st->G + o.ln2_g, acc);
+    int ln2_parts = 0, ln1_parts = 0;
+    e = run_ln_bwd(st, st->tmp_h, A.x1, A.mean2, A.rstd2, wptr(st, buf, o.ln2_g), dy, st->dx1, st->ln_partial, &ln2_parts);
     if (e != hipSuccess) return e;
     // x1 = x + o Wo + bo
     e = wgrad(A.o, h, st->dx1, h, st->G + o.wo);                         if (e != hipSuccess) return e;
-    e = run_bias_grad(st, st->dx1, h, st->G + o.bo, acc);                if (e != hipSuccess) return e;
     e = dgrad(st->dx1, h, wptr(st, buf, o.wo), h, st->tmp_h, nullptr);   if (e != hipSuccess) return e;
     // attention
     e = timed(st, STAGE_K_ATTN_BWD, attn_flops, 0.0, [&] {
@@ -359,12 +342,30 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     if (e != hipSuccess) return e;
     // qkv = a Wqkv + bqkv
     e = wgrad(A.a, h, st->dqkv, 3 * h, st->G + o.wqkv);                  if (e != hipSuccess) return e;
-    e = run_bias_grad(st, st->dqkv, 3 * h, st->G + o.bqkv, acc);         if (e != hipSuccess) return e;
     e = dgrad(st->dqkv, 3 * h, wptr(st, buf, o.wqkv), h, st->tmp_h, nullptr);  if (e != hipSuccess) return e;
     // a = LN1(x); dx = dx1 + LN1'(da)
-    e = run_ln_bwd(st, st->tmp_h, A.x, A.mean1, A.rstd1, wptr(st, buf, o.ln1_g), st->dx1, dx, st->G + o.ln1_g, acc);
+    e = run_ln_bwd(st, st->tmp_h, A.x, A.mean1, A.rstd1, wptr(st, buf, o.ln1_g), st->dx1, dx, st->ln_partial2, &ln1_parts);
     if (e != hipSuccess) return e;
     e = timed(st, STAGE_K_GEMM_WGRAD, wg_flops, 0.0, [&] { return gemm_grouped(wg, n_wg, st->stream); });
+    if (e != hipSuccess) return e;
+    // bias gradients (column sums of the four projection-output gradients) and the reduction of
+    // every partial of the layer: two launches
+    const ColsumItem cs[4] = {{dy, h, h}, {st->du, f, f}, {st->dx1, h, h}, {st->dqkv, 3 * h, 3 * h}};
+    int cs_parts = 0, cs_cols = 0;
+    e = timed(st, STAGE_K_BIAS_GRAD, 0.0, (double)T * (5.0 * h + f) * st->esize, [&] {
+      return colsum_partial_grouped(cs, 4, T, st->cs_partial, &cs_parts, &cs_cols, st->dtype, st->stream);
+    });
+    if (e != hipSuccess) return e;
+    const FinalizeItem fin[6] = {
+        {st->cs_partial, cs_parts, cs_cols, h, st->G + o.b2},
+        {st->cs_partial + h, cs_parts, cs_cols, f, st->G + o.b1},
+        {st->cs_partial + h + f, cs_parts, cs_cols, h, st->G + o.bo},
+        {st->cs_partial + 2 * h + f, cs_parts, cs_cols, 3 * h, st->G + o.bqkv},
+        {st->ln_partial, ln2_parts, 2 * h, 2 * h, st->G + o.ln2_g},
+        {st->ln_partial2, ln1_parts, 2 * h, 2 * h, st->G + o.ln1_g}};
+    e = timed(st, STAGE_K_BIAS_GRAD, 0.0, 4.0 * (cs_parts * (double)cs_cols + (ln1_parts + ln2_parts) * 2.0 * h), [&] {
+      return colsum_finalize_grouped(fin, 6, acc, st->stream);
+    });
     if (e != hipSuccess) return e;
     dy = dx;
     (void)g;
@@ -457,8 +458,8 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
   if (cfg->recompute) ALLOC(st->y_scratch, T * h * E, nullptr);
   ALLOC(st->delta, (int64_t)cfg->microbatch * cfg->n_heads * cfg->seq * 4, nullptr);
   ALLOC(st->ln_partial, (int64_t)ln_bwd_max_parts() * 2 * h * 4, nullptr);
-  const int64_t widest = (3 * h > f) ? 3 * h : f;
-  ALLOC(st->cs_partial, (int64_t)colsum_max_parts() * widest * 4, nullptr);
+  ALLOC(st->ln_partial2, (int64_t)ln_bwd_max_parts() * 2 * h * 4, nullptr);
+  ALLOC(st->cs_partial, (int64_t)colsum_max_parts() * (5 * h + f) * 4, nullptr);
 #undef ALLOC
 
   // upload W(0): fp32 mode -> both buffers; bf16 mode -> master, then both bf16 buffers
