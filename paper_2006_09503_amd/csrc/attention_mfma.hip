@@ -52,49 +52,75 @@ __device__ __forceinline__ uint32_t word(const uint4& v, int i) {
   return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w;
 }
 
+// Tiles go HBM -> registers -> LDS in two steps so that the loads of the next tile are in
+// flight while the current one is being consumed.
 // rows [row0, row0+64) x DH of a [*, ld] matrix -> row-major LDS tile; rows >= row_end are zero
 template <int DH>
-__device__ __forceinline__ void load_rows(const bf16_t* __restrict__ src, int64_t ld, int row0, int row_end,
-                                          uint4* tile, int tid) {
-  constexpr int C = DH / 8;
-  for (int e = tid; e < kTile * C; e += kThreads) {
-    const int r = e / C, c = e % C;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (row0 + r < row_end) v = *reinterpret_cast<const uint4*>(src + (int64_t)(row0 + r) * ld + c * 8);
-    tile[r * Cfg<DH>::KC + c] = v;
+struct RowFetch {
+  static constexpr int C = DH / 8;
+  static constexpr int N = (kTile * C + kThreads - 1) / kThreads;
+  uint4 v[N];
+  __device__ __forceinline__ void fetch(const bf16_t* __restrict__ src, int64_t ld, int row0, int row_end, int tid) {
+#pragma unroll
+    for (int it = 0; it < N; ++it) {
+      const int e = tid + it * kThreads;
+      const int r = e / C, c = e % C;
+      v[it] = make_uint4(0, 0, 0, 0);
+      if (e < kTile * C && row0 + r < row_end)
+        v[it] = *reinterpret_cast<const uint4*>(src + (int64_t)(row0 + r) * ld + c * 8);
+    }
   }
-}
+  __device__ __forceinline__ void commit(uint4* tile, int tid) const {
+#pragma unroll
+    for (int it = 0; it < N; ++it) {
+      const int e = tid + it * kThreads;
+      if (e < kTile * C) tile[(e / C) * Cfg<DH>::KC + e % C] = v[it];
+    }
+  }
+};
 
 // the same rows, transposed: tile[d][row] in 8-byte pieces of 4 consecutive rows
 template <int DH>
-__device__ __forceinline__ void load_rows_transposed(const bf16_t* __restrict__ src, int64_t ld, int row0,
-                                                     int row_end, uint2* tile, int tid) {
-  constexpr int C = DH / 8;
-  for (int u = tid; u < 16 * C; u += kThreads) {
-    const int rq = u % 16, c = u / 16;   // row quad, d chunk
-    uint4 v[4];
+struct TrFetch {
+  static constexpr int C = DH / 8;
+  static constexpr int N = (16 * C + kThreads - 1) / kThreads;
+  uint4 v[N][4];
+  __device__ __forceinline__ void fetch(const bf16_t* __restrict__ src, int64_t ld, int row0, int row_end, int tid) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int r = row0 + rq * 4 + j;
-      v[j] = make_uint4(0, 0, 0, 0);
-      if (r < row_end) v[j] = *reinterpret_cast<const uint4*>(src + (int64_t)r * ld + c * 8);
-    }
+    for (int it = 0; it < N; ++it) {
+      const int u = tid + it * kThreads;
+      const int rq = u % 16, c = u / 16;   // row quad, d chunk
 #pragma unroll
-    for (int ii = 0; ii < 8; ++ii) {
-      const int wd = ii >> 1;
-      const uint32_t w0 = word(v[0], wd), w1 = word(v[1], wd), w2 = word(v[2], wd), w3 = word(v[3], wd);
-      uint2 o;
-      if (ii & 1) {
-        o.x = __builtin_amdgcn_perm(w1, w0, 0x07060302u);
-        o.y = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
-      } else {
-        o.x = __builtin_amdgcn_perm(w1, w0, 0x05040100u);
-        o.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
+      for (int j = 0; j < 4; ++j) {
+        const int r = row0 + rq * 4 + j;
+        v[it][j] = make_uint4(0, 0, 0, 0);
+        if (u < 16 * C && r < row_end) v[it][j] = *reinterpret_cast<const uint4*>(src + (int64_t)r * ld + c * 8);
       }
-      tile[(c * 8 + ii) * kTP + rq] = o;
     }
   }
-}
+  __device__ __forceinline__ void commit(uint2* tile, int tid) const {
+#pragma unroll
+    for (int it = 0; it < N; ++it) {
+      const int u = tid + it * kThreads;
+      if (u >= 16 * C) continue;
+      const int rq = u % 16, c = u / 16;
+#pragma unroll
+      for (int ii = 0; ii < 8; ++ii) {
+        const int wd = ii >> 1;
+        const uint32_t w0 = word(v[it][0], wd), w1 = word(v[it][1], wd), w2 = word(v[it][2], wd), w3 = word(v[it][3], wd);
+        uint2 o;
+        if (ii & 1) {
+          o.x = __builtin_amdgcn_perm(w1, w0, 0x07060302u);
+          o.y = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
+        } else {
+          o.x = __builtin_amdgcn_perm(w1, w0, 0x05040100u);
+          o.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
+        }
+        tile[(c * 8 + ii) * kTP + rq] = o;
+      }
+    }
+  }
+};
 
 template <int DH>
 __device__ __forceinline__ void zero_pad_rows(uint2* tile, int tid) {
@@ -172,11 +198,17 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_mfma_kernel(const bf16_t* _
 
   zero_pad_rows<DH>(vt_lds, tid);
   const int jend = causal ? min(i0 + kBlockRows, s) : kv_len;
+  RowFetch<DH> kfetch;
+  TrFetch<DH> vfetch;
+  kfetch.fetch(base + h, ld, 0, jend, tid);
+  vfetch.fetch(base + 2 * h, ld, 0, jend, tid);
   for (int j0 = 0; j0 < jend; j0 += kTile) {
     __syncthreads();
-    load_rows<DH>(base + h, ld, j0, jend, k_lds, tid);
-    load_rows_transposed<DH>(base + 2 * h, ld, j0, jend, vt_lds, tid);
+    kfetch.commit(k_lds, tid);
+    vfetch.commit(vt_lds, tid);
     __syncthreads();
+    kfetch.fetch(base + h, ld, j0 + kTile, jend, tid);        // next tile, in flight during the MFMAs
+    vfetch.fetch(base + 2 * h, ld, j0 + kTile, jend, tid);
     if (causal && j0 > iw0 + 31) continue;   // every key of the tile lies after this wave's queries
 
     f32x16 sacc[2] = {zero16(), zero16()};
@@ -284,11 +316,20 @@ __global__ __launch_bounds__(kThreads) void attn_dq_mfma_kernel(const bf16_t* __
 
   zero_pad_rows<DH>(kt_lds, tid);
   const int jend = causal ? min(i0 + kBlockRows, s) : kv_len;
+  // (no register prefetch here: it would push the kernel past 256 registers per lane, and two
+  // waves per SIMD hide the tile loads better than one wave with prefetch -- measured)
   for (int j0 = 0; j0 < jend; j0 += kTile) {
     __syncthreads();
-    load_rows<DH>(base + h, ld, j0, jend, k_lds, tid);
-    load_rows<DH>(base + 2 * h, ld, j0, jend, v_lds, tid);
-    load_rows_transposed<DH>(base + h, ld, j0, jend, kt_lds, tid);
+    {
+      RowFetch<DH> kfetch, vfetch;
+      TrFetch<DH> ktfetch;
+      kfetch.fetch(base + h, ld, j0, jend, tid);
+      vfetch.fetch(base + 2 * h, ld, j0, jend, tid);
+      ktfetch.fetch(base + h, ld, j0, jend, tid);
+      kfetch.commit(k_lds, tid);
+      vfetch.commit(v_lds, tid);
+      ktfetch.commit(kt_lds, tid);
+    }
     __syncthreads();
     if (causal && j0 > iw0 + 31) continue;
 
@@ -383,10 +424,18 @@ __global__ __launch_bounds__(kThreads) void attn_dkv_mfma_kernel(const bf16_t* _
   const int istart = causal ? (j0 / kTile) * kTile : 0;    // earlier queries see none of these keys
   for (int i0 = istart; i0 < s && !wg_dead; i0 += kTile) {
     __syncthreads();
-    load_rows<DH>(base, ld, i0, s, q_lds, tid);
-    load_rows<DH>(dobase, (int64_t)h, i0, s, do_lds, tid);
-    load_rows_transposed<DH>(base, ld, i0, s, qt_lds, tid);
-    load_rows_transposed<DH>(dobase, (int64_t)h, i0, s, dot_lds, tid);
+    {
+      RowFetch<DH> qfetch, dofetch;
+      TrFetch<DH> qtfetch, dotfetch;
+      qfetch.fetch(base, ld, i0, s, tid);
+      dofetch.fetch(dobase, (int64_t)h, i0, s, tid);
+      qtfetch.fetch(base, ld, i0, s, tid);
+      dotfetch.fetch(dobase, (int64_t)h, i0, s, tid);
+      qfetch.commit(q_lds, tid);
+      dofetch.commit(do_lds, tid);
+      qtfetch.commit(qt_lds, tid);
+      dotfetch.commit(dot_lds, tid);
+    }
     if (tid < kTile) {
       const int i = i0 + tid;
       lse_lds[tid] = i < s ? lse_row[i] * kLog2e : INFINITY;   // +inf: probability 0 for rows past the end

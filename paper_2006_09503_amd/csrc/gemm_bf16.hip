@@ -58,7 +58,7 @@ struct GroupParams {
 // cycles on every fragment read; (row >> 1) & 7 makes the transposing stores 4-way conflicted.
 template <int CH>
 __device__ __forceinline__ int swz(int row) {
-  return CH == 8 ? ((row >> 1) ^ (row >> 4)) & 7 : (row ^ (row >> 4)) & 15;
+  return CH == 4 ? ((row >> 2) ^ (row >> 4)) & 3 : CH == 8 ? ((row >> 1) ^ (row >> 4)) & 7 : (row ^ (row >> 4)) & 15;
 }
 
 __device__ __forceinline__ uint4 select_zero(bool ok, uint4 v) {
@@ -228,6 +228,85 @@ __device__ __forceinline__ void unpack4(uint2 w, float (&v)[4]) {
   v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
 }
 
+// Tile order inside a problem: groups of kGroupM tile rows, walked column by column, so that
+// the workgroups running at the same time on an XCD (consecutive ids after the XCD remap) cover
+// a kGroupM x (32 / kGroupM) block of tiles and share A row panels and B column panels in that
+// XCD's L2 instead of streaming a whole row of B panels.
+#ifndef K2BW_GROUP_M
+#define K2BW_GROUP_M 8
+#endif
+constexpr int kGroupM = K2BW_GROUP_M;
+__device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int& bm, int& bn) {
+  const int per_group = kGroupM * tiles_n;
+  const int group = t / per_group;
+  const int first_m = group * kGroupM;
+  const int gm = min(kGroupM, tiles_m - first_m);
+  const int t_in = t - group * per_group;
+  bm = first_m + t_in % gm;
+  bn = t_in / gm;
+}
+
+// Epilogue shared by the GEMM kernels: lane owns row m = .. + (lane % 32) and, per register quad
+// g, columns n = .. + 8*g + 4*(lane/32) + 0..3 of each 32x32 block.
+template <int MI, int NI, int WM, int WN, int EPI>
+__device__ __forceinline__ void epilogue(const f32x16 (&acc)[MI][NI], const BfParams& p, int m0, int n0, int wm,
+                                         int wn, int lane) {
+  const int khalf = lane >> 5;
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+    const int row = m0 + wm * WM + mi * 32 + (lane & 31);
+    if (row >= p.M) continue;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = n0 + wn * WN + ni * 32 + 8 * g + 4 * khalf;
+        if (col >= p.N) continue;   // N is a multiple of 8: a quad is inside or outside as a whole
+        const int64_t idx = (int64_t)row * p.ldc + col;
+        float v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = acc[mi][ni][4 * g + j];
+        if (EPI == kEpiStore || EPI == kEpiGelu) {
+          if (p.bias) {
+            float b[4];
+            unpack4(*reinterpret_cast<const uint2*>(p.bias + col), b);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] += b[j];
+          }
+        }
+        if (EPI == kEpiStore) {
+          if (p.aux) {
+            float r[4];
+            unpack4(*reinterpret_cast<const uint2*>(p.aux + idx), r);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] += r[j];
+          }
+          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + idx) = pack4(v);
+        } else if (EPI == kEpiGelu) {
+          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + idx) = pack4(v);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = gelu_fast(v[j]);
+          *reinterpret_cast<uint2*>(p.aux_out + idx) = pack4(v);
+        } else if (EPI == kEpiGeluGrad) {
+          float u[4];
+          unpack4(*reinterpret_cast<const uint2*>(p.aux + idx), u);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] *= gelu_grad_fast(u[j]);
+          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + idx) = pack4(v);
+        } else {
+          float4* c = reinterpret_cast<float4*>(static_cast<float*>(p.C) + idx);
+          float4 o = make_float4(v[0], v[1], v[2], v[3]);
+          if (p.accumulate) {
+            const float4 old = *c;
+            o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
+          }
+          *c = o;
+        }
+      }
+    }
+  }
+}
+
 template <int BM, int BN, int WM, int WN, int BK, bool TA, bool TB, int EPI>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(GroupParams gp) {
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
@@ -255,7 +334,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
     if (q < gp.count && wg >= gp.tile_start[q]) g = q;
   const BfParams& p = gp.p[g];
   wg -= gp.tile_start[g];
-  const int bm = wg / p.tiles_n, bn = wg % p.tiles_n;
+  int bm, bn;
+  tile_coords(wg, p.tiles_m, p.tiles_n, bm, bn);
   const int m0 = bm * BM, n0 = bn * BN;
 
   typename LoaderSel<BM, NT, BK, !TA>::type ld_a;
@@ -337,61 +417,208 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
     __syncthreads();
   }
 
-  // epilogue: lane owns row m = .. + (lane % 32) and, per register quad g, columns
-  // n = .. + 8*g + 4*(lane/32) + 0..3 of each 32x32 block
+  epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Asynchronous variant (K a multiple of 64).  Tiles go from HBM straight into LDS with
+// global_load_lds (16 bytes per lane, a wave fills 1 KB of consecutive LDS), so no registers and
+// no LDS store instructions are spent on staging:
+//   * K-contiguous operand: LDS [row][8 chunks], chunk XOR-swizzled as above; lane i of a load
+//     owns LDS slot L0 + i and fetches the global chunk that belongs there.
+//   * K-strided operand: LDS keeps the HBM form [k][row] (rows contiguous), 16-byte pieces
+//     XOR-swizzled with (k & 3) << 1.  The MFMA fragment is read with ds_read_b64_tr_b16: within
+//     each 16-lane group, lane a + 4t supplies the address of 4 consecutive rows at k_t and lane
+//     4a + j receives (k_0..k_3) of row 4a + j -- measured on gfx950 -- so two such reads give a
+//     lane the 8 k-values of its row in the same slot order as a 16-byte read of the other form.
+// Out-of-range rows are fetched from a clamped address (their products only reach outputs that
+// are never stored).  Two LDS stages; the loads of tile kt+1 are issued before the MFMAs of kt.
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4i16 lds_v4i16_t;
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void glob_void_t;
+
+template <int R, int NW, int BKA, bool K_CONTIG>
+struct AsyncLoader {
+  static constexpr int CHK = BKA / 8;               // chunks per row of a K-contiguous tile
+  static constexpr int kSlots = R * CHK;            // 16-byte slots per tile
+  static constexpr int IPW = kSlots / 64 / NW;      // load instructions per wave
+  static_assert(kSlots % (64 * NW) == 0, "tile/waves mismatch");
+  const bf16_t* base_;
+  uint32_t voff[IPW];
+  int ld_, first_slot_;
+  __device__ __forceinline__ void init(const bf16_t* base, int ld, int rows_valid, int wave, int lane) {
+    base_ = base; ld_ = ld;
+    first_slot_ = wave * IPW * 64;
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi) {
-    const int row = m0 + wm * WM + mi * 32 + (lane & 31);
-    if (row >= p.M) continue;
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int col = n0 + wn * WN + ni * 32 + 8 * g + 4 * khalf;
-        if (col >= p.N) continue;   // N is a multiple of 8: a quad is inside or outside as a whole
-        const int64_t idx = (int64_t)row * p.ldc + col;
-        float v[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = acc[mi][ni][4 * g + j];
-        if (EPI == kEpiStore || EPI == kEpiGelu) {
-          if (p.bias) {
-            float b[4];
-            unpack4(*reinterpret_cast<const uint2*>(p.bias + col), b);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] += b[j];
-          }
-        }
-        if (EPI == kEpiStore) {
-          if (p.aux) {
-            float r[4];
-            unpack4(*reinterpret_cast<const uint2*>(p.aux + idx), r);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] += r[j];
-          }
-          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + idx) = pack4(v);
-        } else if (EPI == kEpiGelu) {
-          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + idx) = pack4(v);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = gelu_fast(v[j]);
-          *reinterpret_cast<uint2*>(p.aux_out + idx) = pack4(v);
-        } else if (EPI == kEpiGeluGrad) {
-          float u[4];
-          unpack4(*reinterpret_cast<const uint2*>(p.aux + idx), u);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] *= gelu_grad_fast(u[j]);
-          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + idx) = pack4(v);
-        } else {
-          float4* c = reinterpret_cast<float4*>(static_cast<float*>(p.C) + idx);
-          float4 o = make_float4(v[0], v[1], v[2], v[3]);
-          if (p.accumulate) {
-            const float4 old = *c;
-            o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
-          }
-          *c = o;
-        }
+    for (int j = 0; j < IPW; ++j) {
+      const int L = first_slot_ + j * 64 + lane;
+      if (K_CONTIG) {
+        const int row = L / CHK, pc = L % CHK;
+        const int c = pc ^ swz<CHK>(row);
+        const int rc = row < rows_valid ? row : rows_valid - 1;
+        voff[j] = (uint32_t)rc * (uint32_t)ld + c * 8;
+      } else {
+        constexpr int PPR = R / 8;                  // pieces per k row
+        const int k = L / PPR, pp = L % PPR;
+        const int piece = pp ^ ((k & 3) << 1);
+        int col = piece * 8;
+        if (col >= rows_valid) col = rows_valid - 8;
+        voff[j] = (uint32_t)k * (uint32_t)ld + col;
       }
     }
   }
+  // tile at k0 -> LDS tile starting at byte address tile_bytes (uniform)
+  __device__ __forceinline__ void issue(int k0, uint4* tile) const {
+    const bf16_t* b = K_CONTIG ? base_ + k0 : base_ + (int64_t)k0 * ld_;
+#pragma unroll
+    for (int j = 0; j < IPW; ++j)
+      __builtin_amdgcn_global_load_lds((glob_void_t*)(b + voff[j]), (lds_void_t*)(tile + first_slot_ + j * 64), 16, 0, 0);
+  }
+};
+
+// fragment of 32 rows starting at row0 for sub-step ks
+template <int R, int BKA, bool K_CONTIG>
+__device__ __forceinline__ bf16x8 read_frag(const uint4* tile, int row0, int ks, int lane) {
+  if (K_CONTIG) {
+    constexpr int CHK = BKA / 8;
+    const int row = row0 + (lane & 31);
+    return __builtin_bit_cast(bf16x8, tile[row * CHK + ((ks * 2 + (lane >> 5)) ^ swz<CHK>(row))]);
+  } else {
+    const int r = lane & 15, a = r & 3, t = r >> 2;
+    const int k = ks * 16 + (lane >> 5) * 8 + t;
+    const int col = row0 + ((lane >> 4) & 1) * 16 + 4 * a;
+    const int piece = (col >> 3) ^ (t << 1);        // (k & 3) == t
+    const int byte = k * (R * 2) + piece * 16 + ((col >> 2) & 1) * 8;
+    const lds_v4i16_t* p0 = (const lds_v4i16_t*)((const __attribute__((address_space(3))) char*)tile + byte);
+    const lds_v4i16_t* p1 = (const lds_v4i16_t*)((const __attribute__((address_space(3))) char*)tile + byte + 4 * R * 2);
+    const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t*)p0);
+    const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t*)p1);
+    typedef short v8i16 __attribute__((ext_vector_type(8)));
+    const v8i16 w = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, w);
+  }
+}
+
+// s_waitcnt immediate for "at most n vector-memory operations outstanding" (gfx9 encoding:
+// vmcnt = bits 3:0 and 15:14; expcnt and lgkmcnt fields left at their maxima = no wait)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+template <int BM, int BN, int WM, int WN, int BKA, int NSTAGE, bool TA, bool TB, int EPI>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_async_kernel(GroupParams gp) {
+  constexpr int NW = (BM / WM) * (BN / WN);
+  constexpr int MI = WM / 32, NI = WN / 32;
+  constexpr int WAVES_N = BN / WN;
+  constexpr int KS = BKA / 16, CHK = BKA / 8;
+  extern __shared__ uint4 smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int n_tiles = gp.tile_start[gp.count];
+  int wg = blockIdx.x;
+  {
+    const int per_xcd = n_tiles / 8;
+    if (wg < per_xcd * 8) wg = (wg % 8) * per_xcd + wg / 8;
+  }
+  int g = 0;
+#pragma unroll
+  for (int q = 1; q < kMaxGroup; ++q)
+    if (q < gp.count && wg >= gp.tile_start[q]) g = q;
+  const BfParams& p = gp.p[g];
+  wg -= gp.tile_start[g];
+  int bm, bn;
+  tile_coords(wg, p.tiles_m, p.tiles_n, bm, bn);
+  const int m0 = bm * BM, n0 = bn * BN;
+
+  AsyncLoader<BM, NW, BKA, !TA> ld_a;
+  AsyncLoader<BN, NW, BKA, TB> ld_b;
+  ld_a.init(TA ? p.A + m0 : p.A + (int64_t)m0 * p.lda, p.lda, p.M - m0, wave, lane);
+  ld_b.init(TB ? p.B + (int64_t)n0 * p.ldb : p.B + n0, p.ldb, p.N - n0, wave, lane);
+
+  constexpr int kStage = (BM + BN) * CHK;  // uint4 per stage
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+  const int nk = p.K / BKA;   // K is a multiple of 64
+  constexpr int kLoadsPerTile = AsyncLoader<BM, NW, BKA, !TA>::IPW + AsyncLoader<BN, NW, BKA, TB>::IPW;
+  static_assert((NSTAGE - 2) * kLoadsPerTile <= 63, "vmcnt range");
+  // prologue: tiles 0 .. NSTAGE-2 in flight (past the end: the last tile again, never read)
+#pragma unroll
+  for (int t = 0; t < NSTAGE - 1; ++t) {
+    const int kt_l = t < nk ? t : nk - 1;
+    ld_a.issue(kt_l * BKA, smem + t * kStage);
+    ld_b.issue(kt_l * BKA, smem + t * kStage + BM * CHK);
+  }
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * kLoadsPerTile));   // tile 0 has landed
+  __syncthreads();
+
+  int rs = 0;             // stage being read
+  int ws = NSTAGE - 1;    // stage being filled
+  for (int kt = 0; kt < nk; ++kt) {
+    const uint4* sA = smem + rs * kStage;
+    const uint4* sB = sA + BM * CHK;
+    uint4* dA = smem + ws * kStage;
+    // tile kt+NSTAGE-1 goes into the stage that was read in step kt-1 (all waves are past the
+    // barrier that ended it); past the end the last tile is fetched again: no branch, never read
+    const int k_next = (kt + NSTAGE - 1 < nk ? kt + NSTAGE - 1 : nk - 1) * BKA;
+    ld_a.issue(k_next, dA);
+    ld_b.issue(k_next, dA + BM * CHK);
+    bf16x8 af[2][MI], bfr[2][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) af[0][mi] = read_frag<BM, BKA, !TA>(sA, wm * WM + mi * 32, 0, lane);
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = read_frag<BN, BKA, TB>(sB, wn * WN + ni * 32, 0, lane);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int cur = ks & 1, nxt = cur ^ 1;
+      if (ks + 1 < KS) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) af[nxt][mi] = read_frag<BM, BKA, !TA>(sA, wm * WM + mi * 32, ks + 1, lane);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) bfr[nxt][ni] = read_frag<BN, BKA, TB>(sB, wn * WN + ni * 32, ks + 1, lane);
+      }
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
+    }
+    // this wave's share of tile kt+1 has landed once only the younger tiles' loads are outstanding
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * kLoadsPerTile));
+    __syncthreads();
+    rs = rs + 1 == NSTAGE ? 0 : rs + 1;
+    ws = ws + 1 == NSTAGE ? 0 : ws + 1;
+  }
+  epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane);
+}
+
+template <int BM, int BN, int WM, int WN, int BKA, int NSTAGE, bool TA, bool TB, int EPI>
+hipError_t launch_async(GroupParams gp, hipStream_t s) {
+  constexpr int NT = (BM / WM) * (BN / WN) * 64;
+  constexpr size_t lds = NSTAGE * (BM + BN) * (BKA / 8) * sizeof(uint4);
+  auto kern = gemm_bf16_async_kernel<BM, BN, WM, WN, BKA, NSTAGE, TA, TB, EPI>;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  int total = 0;
+  for (int g = 0; g < gp.count; ++g) {
+    gp.p[g].tiles_m = ceil_div(gp.p[g].M, BM);
+    gp.p[g].tiles_n = ceil_div(gp.p[g].N, BN);
+    gp.tile_start[g] = total;
+    total += gp.p[g].tiles_m * gp.p[g].tiles_n;
+  }
+  for (int g = gp.count; g <= kMaxGroup; ++g) gp.tile_start[g] = total;
+  hipLaunchKernelGGL(kern, dim3(total), dim3(NT), lds, s, gp);
+  return hipGetLastError();
 }
 
 template <int BM, int BN, int WM, int WN, int BK, bool TA, bool TB, int EPI>
@@ -424,14 +651,18 @@ template <bool TA, bool TB, int EPI>
 hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
   int tile = g_tile_override;
   if (tile == 0) {
-    // Measured on MI355X (M = 4096..8192): 128x128 tiles with two workgroups per CU win until the
-    // problem fills the chip several times over with 256x256 tiles; then the 8-wave 256x256
-    // kernel is fastest when both operands are K-contiguous, the 4-wave one (512 registers per
-    // lane, no spills in the transposing loaders) otherwise.
+    // Measured on MI355X (M = 4096..8192): 128x128 tiles with two workgroups per CU win until
+    // 256x256 tiles give at least 3/4 of the CUs a tile; then the 8-wave 256x256 kernels win, the
+    // asynchronous one when both operands are K-contiguous (it needs K % 64 == 0 and falls back
+    // to the register-staged kernel otherwise), the register-staged one for the other forms.
     int64_t big = 0;
     for (int g = 0; g < gp.count; ++g) big += (int64_t)ceil_div(gp.p[g].M, 256) * ceil_div(gp.p[g].N, 256);
-    if (!TA && TB) tile = big >= 192 ? 3 : 2;
-    else tile = big >= 512 ? 1 : 2;
+    if (big >= 192) tile = (!TA && TB) ? 13 : 3;
+    else tile = 2;
+  }
+  if (tile > 10) {   // the asynchronous kernels need whole K tiles
+    for (int g = 0; g < gp.count; ++g)
+      if (gp.p[g].K % 64) tile -= 10;
   }
   switch (tile) {
     case 1: return launch<256, 256, 128, 128, 64, TA, TB, EPI>(gp, s);
@@ -439,6 +670,13 @@ hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
     case 3: return launch<256, 256, 128, 64, 64, TA, TB, EPI>(gp, s);   // 8 waves
     case 4: return launch<128, 128, 64, 64, 128, TA, TB, EPI>(gp, s);   // deeper K step
     case 5: return launch<256, 128, 128, 64, 64, TA, TB, EPI>(gp, s);
+    case 11: return launch_async<256, 256, 128, 128, 64, 2, TA, TB, EPI>(gp, s);
+    case 12: return launch_async<128, 128, 64, 64, 64, 2, TA, TB, EPI>(gp, s);
+    case 13: return launch_async<256, 256, 128, 64, 64, 2, TA, TB, EPI>(gp, s);
+    case 14: return launch_async<256, 256, 128, 64, 32, 4, TA, TB, EPI>(gp, s);    // 8 waves, 4 x 32 KB
+    case 15: return launch_async<256, 256, 128, 128, 32, 4, TA, TB, EPI>(gp, s);   // 4 waves, 4 x 32 KB
+    case 16: return launch_async<256, 256, 128, 64, 32, 3, TA, TB, EPI>(gp, s);
+    case 17: return launch_async<128, 128, 64, 64, 32, 4, TA, TB, EPI>(gp, s);     // 4 x 16 KB: 2 workgroups per CU
     default: return hipErrorInvalidValue;
   }
 }
