@@ -28,6 +28,15 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# HBM bytes per launch (read + write) of kernel instances on the default workload, from rocprofv3
+# --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the same counters read for the
+# library's plain copy kernel of known size; see profiles/ for the runs.  None = not measured.
+TRAFFIC_BYTES_PER_LAUNCH = {
+    # grouped weight-gradient GEMM of one layer (4 problems): FETCH_SIZE 125725.8 KiB x 1.995 (copy-kernel
+    # factor) + WRITE_SIZE 59105.7 KiB x 1.000; algorithmic minimum 2.349e8 (operands once + accumulator RMW)
+    "gemm_bf16_kernel<256, 256, 128, 64, 64, true, false, 3>": 3.174e8,
+}
+
 
 def model_flops_per_microbatch(cfg) -> float:
     """3 x forward FLOPs; attention counted dense (4 b s^2 h per layer), no credit for recompute."""
@@ -148,6 +157,7 @@ def main():
         launches_per_step = m * cfg.n_layers * 64 + 16
         st.timing_enable(True, launches_per_step * K + 64)
         run_steps(W + K, K)
+        per_kernel = st.timing_collect_kernels()
         tm = st.timing_collect()
         st.timing_enable(False)
         kernels = {}
@@ -163,13 +173,22 @@ def main():
                 e["gbs"] = r["bytes"] / (r["ms"] * 1e-3) / 1e9
                 e["frac_of_hbm_peak"] = e["gbs"] / PEAK_HBM_GBS
             kernels[name] = e
-        gemms = [n for n in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad") if n in kernels]
-        dom = max(gemms, key=lambda n: kernels[n]["ms_per_step"])
-        achieved = kernels[dom]["tflops"]
+        # dominant kernel = the single kernel instance (name as rocprofv3 prints it) with the most
+        # time in the timed region; its algorithmic FLOPs per launch = 2*M*N*K summed over the
+        # problems of the launch, averaged over its launches
+        gemm_inst = {n: r for n, r in per_kernel.items() if n.startswith("gemm_") and r["flops"] > 0}
+        dom = max(gemm_inst, key=lambda n: gemm_inst[n]["ms"])
+        r = gemm_inst[dom]
+        achieved = r["flops"] / (r["ms"] * 1e-3) / 1e12
         roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
-                    "avg_launch_us": kernels[dom]["avg_us"],
-                    "flops_per_launch": tm[dom]["flops"] / tm[dom]["launches"]}
+                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(dom),
+                    "avg_launch_us": r["ms"] / r["launches"] * 1e3, "launches_per_step": r["launches"] / K,
+                    "flops_per_launch": r["flops"] / r["launches"],
+                    "share_of_step": r["ms"] / K / ms_per_step}
+        kernels["_by_instance"] = {n: {"launches_per_step": v["launches"] / K, "avg_us": v["ms"] / v["launches"] * 1e3,
+                                       **({"tflops": v["flops"] / (v["ms"] * 1e-3) / 1e12} if v["flops"] > 0 else {}),
+                                       **({"gbs": v["bytes"] / (v["ms"] * 1e-3) / 1e9} if v["bytes"] > 0 else {})}
+                                   for n, v in per_kernel.items()}
 
     # drain the microbatches still in flight so the stage ends at a batch boundary
     last = (W + K + (0 if args.no_kernel_timing else K)) * m

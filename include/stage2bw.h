@@ -168,6 +168,13 @@ int stage_timing_enable(stage_t* st, int enable, int32_t capacity);
 int stage_timing_collect(stage_t* st, double* ms_out, int64_t* launches_out, double* flops_out,
                          double* bytes_out);
 
+/* The same events grouped by kernel instance (name as a kernel trace prints it, 96 bytes per
+ * entry in names_out, which must hold capacity*96 bytes).  Does not reset the events: call it
+ * before stage_timing_collect.  count_out receives the number of entries filled. */
+int stage_timing_collect_kernels(stage_t* st, int32_t capacity, char* names_out, double* ms_out,
+                                 int64_t* launches_out, double* flops_out, double* bytes_out,
+                                 int32_t* count_out);
+
 /* ---- the schedule alone (host only, no device needed) ------------------------------------ */
 /*
  * The state machine the stage calls use, exposed so that the 2BW bookkeeping can be checked

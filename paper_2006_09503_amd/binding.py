@@ -62,6 +62,7 @@ def lib() -> C.CDLL:
             "stage_strerror": (C.c_char_p, [C.c_int]),
             "stage_timing_enable": (C.c_int, [vp, C.c_int, i32]),
             "stage_timing_collect": (C.c_int, [vp, vp, vp, vp, vp]),
+            "stage_timing_collect_kernels": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, C.POINTER(i32)]),
             "stage_sched_create": (C.c_int, [i32, i32, C.POINTER(vp)]),
             "stage_sched_forward": (C.c_int, [vp, i64, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32)]),
             "stage_sched_backward": (C.c_int, [vp, i64, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32),
@@ -202,6 +203,21 @@ def stage_timing_collect(st: int):
             for i, k in enumerate(KERNEL_CLASSES)}
 
 
+def stage_timing_collect_kernels(st: int, capacity: int = 64):
+    """{kernel instance name: dict(ms, launches, flops, bytes)}; call before stage_timing_collect."""
+    names = C.create_string_buffer(capacity * 96)
+    ms, fl, by = (np.zeros(capacity, dtype=np.float64) for _ in range(3))
+    cnt = np.zeros(capacity, dtype=np.int64)
+    n = C.c_int32()
+    _check(lib().stage_timing_collect_kernels(st, capacity, C.addressof(names), ms.ctypes.data, cnt.ctypes.data,
+                                              fl.ctypes.data, by.ctypes.data, C.byref(n)), "stage_timing_collect_kernels")
+    out = {}
+    for i in range(n.value):
+        name = names.raw[i * 96:(i + 1) * 96].split(b"\0")[0].decode()
+        out[name] = dict(ms=float(ms[i]), launches=int(cnt[i]), flops=float(fl[i]), bytes=float(by[i]))
+    return out
+
+
 # ----------------------------------------------------------------------------- schedule alone (host)
 
 class Sched:
@@ -268,6 +284,7 @@ class Stage:
     def read_adam(self): return stage_read_adam(self.h, self.n_params)
     def timing_enable(self, enable, capacity=0): stage_timing_enable(self.h, enable, capacity)
     def timing_collect(self): return stage_timing_collect(self.h)
+    def timing_collect_kernels(self, capacity=64): return stage_timing_collect_kernels(self.h, capacity)
 
     def close(self):
         if self.h:

@@ -1,4 +1,6 @@
 // Shape validation and routing of GEMM and attention calls to the kernel families.
+#include <cstdio>
+
 #include "kernels.hpp"
 
 namespace k2bw {
@@ -6,6 +8,7 @@ namespace k2bw {
 hipError_t gemm_f32(const GemmDesc& d, hipStream_t stream);
 hipError_t gemm_bf16(const GemmDesc& d, hipStream_t stream);
 hipError_t gemm_bf16_grouped(const GemmDesc* d, int count, hipStream_t stream);
+void gemm_bf16_kernel_name(const GemmDesc* d, int count, char* out, size_t cap);
 hipError_t attention_fwd_simple(const AttnDesc& d, const void* qkv, void* o, float* lse, hipStream_t st);
 hipError_t attention_bwd_simple(const AttnDesc& d, const void* qkv, const void* o, const float* lse,
                                 const void* d_o, void* dqkv, float* delta, hipStream_t st);
@@ -41,6 +44,11 @@ hipError_t gemm(const GemmDesc& d, hipStream_t stream) {
   hipError_t e = check_gemm(d);
   if (e != hipSuccess) return e;
   return d.dtype == kF32 ? gemm_f32(d, stream) : gemm_bf16(d, stream);
+}
+
+void gemm_kernel_name(const GemmDesc* d, int count, char* out, size_t cap) {
+  if (d[0].dtype == kBF16) gemm_bf16_kernel_name(d, count, out, cap);
+  else snprintf(out, cap, "gemm_f32_kernel<%s, %s, %d>", d[0].trans_a ? "true" : "false", d[0].trans_b ? "true" : "false", d[0].epilogue);
 }
 
 hipError_t gemm_grouped(const GemmDesc* d, int count, hipStream_t stream) {

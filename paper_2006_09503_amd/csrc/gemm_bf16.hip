@@ -21,6 +21,8 @@
 // first operand and the A tile as the second, i.e. it accumulates C^T blocks: a lane then owns
 // one row m of C and four consecutive columns n per register quad, which makes the epilogue's
 // global accesses 8-byte (bf16) or 16-byte (fp32 accumulator) vectors.
+#include <cstdio>
+
 #include "kernels.hpp"
 
 namespace k2bw {
@@ -647,8 +649,8 @@ hipError_t launch(GroupParams gp, hipStream_t s) {
 
 int g_tile_override = 0;  // 0: heuristic; else force a tile shape (tuning aid)
 
-template <bool TA, bool TB, int EPI>
-hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
+// Tile choice for a (grouped) problem; ta/tb as in GemmDesc.
+int choose_tile(const BfParams* p, int count, bool ta, bool tb) {
   int tile = g_tile_override;
   if (tile == 0) {
     // Measured on MI355X (M = 4096..8192): 128x128 tiles with two workgroups per CU win until
@@ -656,14 +658,21 @@ hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
     // asynchronous one when both operands are K-contiguous (it needs K % 64 == 0 and falls back
     // to the register-staged kernel otherwise), the register-staged one for the other forms.
     int64_t big = 0;
-    for (int g = 0; g < gp.count; ++g) big += (int64_t)ceil_div(gp.p[g].M, 256) * ceil_div(gp.p[g].N, 256);
-    if (big >= 192) tile = (!TA && TB) ? 13 : 3;
+    for (int g = 0; g < count; ++g) big += (int64_t)ceil_div(p[g].M, 256) * ceil_div(p[g].N, 256);
+    if (big >= 192) tile = (!ta && tb) ? 13 : 3;
     else tile = 2;
   }
   if (tile > 10) {   // the asynchronous kernels need whole K tiles
-    for (int g = 0; g < gp.count; ++g)
-      if (gp.p[g].K % 64) tile -= 10;
+    for (int g = 0; g < count; ++g)
+      if (p[g].K % 64) { tile -= 10; break; }
+    if (tile == 4 || tile == 5 || tile == 6 || tile == 7) tile = 2;   // no register-staged twin
   }
+  return tile;
+}
+
+template <bool TA, bool TB, int EPI>
+hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
+  const int tile = choose_tile(gp.p, gp.count, TA, TB);
   switch (tile) {
     case 1: return launch<256, 256, 128, 128, 64, TA, TB, EPI>(gp, s);
     case 2: return launch<128, 128, 64, 64, 64, TA, TB, EPI>(gp, s);
@@ -696,6 +705,23 @@ BfParams to_params(const GemmDesc& d) {
 }  // namespace
 
 void gemm_bf16_set_tile(int id) { g_tile_override = id; }
+
+// Name of the kernel instance a (grouped) call will run, in the form profilers print template
+// arguments, so that event timings can be matched with a kernel trace.
+void gemm_bf16_kernel_name(const GemmDesc* d, int count, char* out, size_t cap) {
+  BfParams p[kMaxGroup];
+  for (int g = 0; g < count && g < kMaxGroup; ++g) p[g] = to_params(d[g]);
+  const int tile = choose_tile(p, count < kMaxGroup ? count : kMaxGroup, d[0].trans_a, d[0].trans_b);
+  const char* ta = d[0].trans_a ? "true" : "false";
+  const char* tb = d[0].trans_b ? "true" : "false";
+  switch (tile) {
+    case 1: snprintf(out, cap, "gemm_bf16_kernel<256, 256, 128, 128, 64, %s, %s, %d>", ta, tb, d[0].epilogue); break;
+    case 2: snprintf(out, cap, "gemm_bf16_kernel<128, 128, 64, 64, 64, %s, %s, %d>", ta, tb, d[0].epilogue); break;
+    case 3: snprintf(out, cap, "gemm_bf16_kernel<256, 256, 128, 64, 64, %s, %s, %d>", ta, tb, d[0].epilogue); break;
+    case 13: snprintf(out, cap, "gemm_bf16_async_kernel<256, 256, 128, 64, 64, 2, %s, %s, %d>", ta, tb, d[0].epilogue); break;
+    default: snprintf(out, cap, "gemm_bf16 tile %d <%s, %s, %d>", tile, ta, tb, d[0].epilogue); break;
+  }
+}
 
 // `count` GEMMs (1..4) with the same form and epilogue in one launch.
 hipError_t gemm_bf16_grouped(const GemmDesc* d, int count, hipStream_t stream) {

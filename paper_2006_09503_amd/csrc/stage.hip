@@ -45,6 +45,7 @@ struct EventPair {
   hipEvent_t start, stop;
   int cls;
   double flops, bytes;
+  char name[96];   // kernel instance, as a kernel trace names it
 };
 
 }  // namespace
@@ -189,11 +190,12 @@ int alloc_actset(stage2bw* st, ActSet* set) {
 
 // ---- launch wrapper with optional event timing ------------------------------------------------
 template <typename F>
-hipError_t timed(stage2bw* st, int cls, double flops, double bytes, F&& launch) {
+hipError_t timed(stage2bw* st, int cls, const char* name, double flops, double bytes, F&& launch) {
   EventPair* ev = nullptr;
   if (st->timing && st->events_used < st->events.size()) {
     ev = &st->events[st->events_used++];
     ev->cls = cls; ev->flops = flops; ev->bytes = bytes;
+    std::snprintf(ev->name, sizeof(ev->name), "%s", name);
     hipError_t e = hipEventRecord(ev->start, st->stream);
     if (e != hipSuccess) return e;
   }
@@ -208,13 +210,15 @@ const char* wptr(const stage2bw* st, int buffer, int64_t elem_off) {
 }
 
 hipError_t run_gemm(stage2bw* st, int cls, const GemmDesc& d) {
-  return timed(st, cls, 2.0 * d.M * d.N * d.K, 0.0, [&] { return gemm(d, st->stream); });
+  char name[96] = "";
+  if (st->timing) gemm_kernel_name(&d, 1, name, sizeof(name));
+  return timed(st, cls, name, 2.0 * d.M * d.N * d.K, 0.0, [&] { return gemm(d, st->stream); });
 }
 
 hipError_t run_ln_fwd(stage2bw* st, const void* x, const void* gain, const void* shift, void* y, float* mean,
                       float* rstd) {
   const double bytes = 2.0 * st->T * st->cfg.hidden * st->esize + 8.0 * st->T;
-  return timed(st, STAGE_K_LN_FWD, 0.0, bytes, [&] {
+  return timed(st, STAGE_K_LN_FWD, "ln_fwd_kernel", 0.0, bytes, [&] {
     return layernorm_fwd(x, gain, shift, y, mean, rstd, st->T, st->cfg.hidden, st->cfg.ln_eps, st->dtype, st->stream);
   });
 }
@@ -225,7 +229,7 @@ hipError_t run_ln_bwd(stage2bw* st, const void* dy, const void* x, const float* 
                       const void* gain, const void* dres, void* dx, float* partial, int* parts) {
   const int h = st->cfg.hidden;
   const double bytes = 4.0 * st->T * h * st->esize + 8.0 * st->T;
-  return timed(st, STAGE_K_LN_BWD, 0.0, bytes, [&] {
+  return timed(st, STAGE_K_LN_BWD, "ln_bwd_kernel", 0.0, bytes, [&] {
     return layernorm_bwd(dy, x, mean, rstd, gain, dres, dx, partial, parts, st->T, h, st->dtype, st->stream);
   });
 }
@@ -255,7 +259,7 @@ hipError_t run_forward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens,
     g.M = T; g.N = 3 * h; g.K = h; g.bias = wptr(st, buf, o.bqkv);
     e = run_gemm(st, STAGE_K_GEMM_FWD, g);
     if (e != hipSuccess) return e;
-    e = timed(st, STAGE_K_ATTN_FWD, attn_flops, 0.0, [&] {
+    e = timed(st, STAGE_K_ATTN_FWD, st->dtype == kBF16 ? "attn_fwd_mfma_kernel" : "attn_fwd_simple", attn_flops, 0.0, [&] {
       return attention_fwd(attn_desc(st, lens), A.qkv, A.o, A.lse, st->stream);
     });
     if (e != hipSuccess) return e;
@@ -336,7 +340,7 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     e = wgrad(A.o, h, st->dx1, h, st->G + o.wo);                         if (e != hipSuccess) return e;
     e = dgrad(st->dx1, h, wptr(st, buf, o.wo), h, st->tmp_h, nullptr);   if (e != hipSuccess) return e;
     // attention
-    e = timed(st, STAGE_K_ATTN_BWD, attn_flops, 0.0, [&] {
+    e = timed(st, STAGE_K_ATTN_BWD, "attention backward (delta + dq + dkv kernels)", attn_flops, 0.0, [&] {
       return attention_bwd(attn_desc(st, lens), A.qkv, A.o, A.lse, st->tmp_h, st->dqkv, st->delta, st->stream);
     });
     if (e != hipSuccess) return e;
@@ -346,13 +350,15 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     // a = LN1(x); dx = dx1 + LN1'(da)
     e = run_ln_bwd(st, st->tmp_h, A.x, A.mean1, A.rstd1, wptr(st, buf, o.ln1_g), st->dx1, dx, st->ln_partial2, &ln1_parts);
     if (e != hipSuccess) return e;
-    e = timed(st, STAGE_K_GEMM_WGRAD, wg_flops, 0.0, [&] { return gemm_grouped(wg, n_wg, st->stream); });
+    char wg_name[96] = "";
+    if (st->timing) gemm_kernel_name(wg, n_wg, wg_name, sizeof(wg_name));
+    e = timed(st, STAGE_K_GEMM_WGRAD, wg_name, wg_flops, 0.0, [&] { return gemm_grouped(wg, n_wg, st->stream); });
     if (e != hipSuccess) return e;
     // bias gradients (column sums of the four projection-output gradients) and the reduction of
     // every partial of the layer: two launches
     const ColsumItem cs[4] = {{dy, h, h}, {st->du, f, f}, {st->dx1, h, h}, {st->dqkv, 3 * h, 3 * h}};
     int cs_parts = 0, cs_cols = 0;
-    e = timed(st, STAGE_K_BIAS_GRAD, 0.0, (double)T * (5.0 * h + f) * st->esize, [&] {
+    e = timed(st, STAGE_K_BIAS_GRAD, "colsum_partial_grouped_kernel", 0.0, (double)T * (5.0 * h + f) * st->esize, [&] {
       return colsum_partial_grouped(cs, 4, T, st->cs_partial, &cs_parts, &cs_cols, st->dtype, st->stream);
     });
     if (e != hipSuccess) return e;
@@ -363,7 +369,7 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
         {st->cs_partial + 2 * h + f, cs_parts, cs_cols, 3 * h, st->G + o.bqkv},
         {st->ln_partial, ln2_parts, 2 * h, 2 * h, st->G + o.ln2_g},
         {st->ln_partial2, ln1_parts, 2 * h, 2 * h, st->G + o.ln1_g}};
-    e = timed(st, STAGE_K_BIAS_GRAD, 0.0, 4.0 * (cs_parts * (double)cs_cols + (ln1_parts + ln2_parts) * 2.0 * h), [&] {
+    e = timed(st, STAGE_K_BIAS_GRAD, "colsum_finalize_grouped_kernel", 0.0, 4.0 * (cs_parts * (double)cs_cols + (ln1_parts + ln2_parts) * 2.0 * h), [&] {
       return colsum_finalize_grouped(fin, 6, acc, st->stream);
     });
     if (e != hipSuccess) return e;
@@ -496,7 +502,7 @@ int stage_forward(stage_t* st, int64_t mb, const void* x_dev, const int32_t* seq
   ActSet& acts = st->cfg.recompute ? st->slot_acts[0] : st->slot_acts[slot];
   // stash the stage input (with recompute it is the only thing kept)
   char* x_keep = st->cfg.recompute ? st->slot_x0[slot] : acts.layer[0].x;
-  HIP_TRY(timed(st, STAGE_K_OTHER, 0.0, 2.0 * in_bytes, [&] { return copy_bytes(x_dev, x_keep, in_bytes, st->stream); }));
+  HIP_TRY(timed(st, STAGE_K_OTHER, "copy16_kernel", 0.0, 2.0 * in_bytes, [&] { return copy_bytes(x_dev, x_keep, in_bytes, st->stream); }));
   const int32_t* lens = nullptr;
   if (st->cfg.mask_mode == STAGE_MASK_PADDING) {
     HIP_TRY(hipMemcpyAsync(st->slot_lens[slot], seqlens_dev, (size_t)st->cfg.microbatch * 4, hipMemcpyDeviceToDevice,
@@ -567,7 +573,7 @@ int stage_coalesce_update(stage_t* st) {
     d.w_cur = reinterpret_cast<const float*>(st->wbuf[rb]); d.w_next = reinterpret_cast<float*>(st->wbuf[wb]);
     bytes = 28.0 * st->P;
   }
-  HIP_TRY(timed(st, STAGE_K_ADAM, 0.0, bytes, [&] { return adam_step(d, st->stream); }));
+  HIP_TRY(timed(st, STAGE_K_ADAM, "adam_kernel", 0.0, bytes, [&] { return adam_step(d, st->stream); }));
   return STAGE_OK;
 }
 
@@ -669,6 +675,31 @@ int stage_timing_enable(stage_t* st, int enable, int32_t capacity) {
     st->events.push_back(e);
   }
   st->timing = true;
+  return STAGE_OK;
+}
+
+int stage_timing_collect_kernels(stage_t* st, int32_t capacity, char* names_out, double* ms_out,
+                                 int64_t* launches_out, double* flops_out, double* bytes_out, int32_t* count_out) {
+  if (!st || capacity < 1 || !names_out || !ms_out || !launches_out || !flops_out || !bytes_out || !count_out)
+    return STAGE_ERR_INVALID_ARG;
+  HIP_TRY(hipStreamSynchronize(st->stream));
+  int n = 0;
+  for (size_t i = 0; i < st->events_used; ++i) {
+    const EventPair& e = st->events[i];
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, e.start, e.stop));
+    int k = 0;
+    for (; k < n; ++k)
+      if (std::strncmp(names_out + (size_t)k * 96, e.name, 96) == 0) break;
+    if (k == n) {
+      if (n == capacity) continue;   // more distinct kernels than the caller has room for
+      std::snprintf(names_out + (size_t)k * 96, 96, "%s", e.name);
+      ms_out[k] = 0; launches_out[k] = 0; flops_out[k] = 0; bytes_out[k] = 0;
+      ++n;
+    }
+    ms_out[k] += ms; launches_out[k] += 1; flops_out[k] += e.flops; bytes_out[k] += e.bytes;
+  }
+  *count_out = n;
   return STAGE_OK;
 }
 
