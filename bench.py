@@ -34,7 +34,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 TRAFFIC_BYTES_PER_LAUNCH = {
     # grouped weight-gradient GEMM of one layer (4 problems): FETCH_SIZE 125725.8 KiB x 1.995 (copy-kernel
     # factor) + WRITE_SIZE 59105.7 KiB x 1.000; algorithmic minimum 2.349e8 (operands once + accumulator RMW)
-    "gemm_bf16_kernel<256, 256, 128, 64, 64, true, false, 3>": 3.174e8,
+    "gemm_bf16_kernel<256, 256, 128, 64, 64, true, false, 3, 1>": 3.174e8,
 }
 
 

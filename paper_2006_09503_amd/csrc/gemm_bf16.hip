@@ -248,78 +248,134 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
   bn = t_in / gm;
 }
 
-// Epilogue shared by the GEMM kernels: lane owns row m = .. + (lane % 32) and, per register quad
-// g, columns n = .. + 8*g + 4*(lane/32) + 0..3 of each 32x32 block.
+// Epilogue shared by the GEMM kernels.  A lane's accumulators are one row m = .. + (lane % 32) and,
+// per register quad g, columns n = .. + 8*g + 4*(lane/32) + 0..3 of each 32x32 block: stored as they
+// are, one store instruction would touch 32 rows with 16 bytes each, and HBM sees partly filled
+// lines (measured: 1.7x the output bytes for the two-output GELU epilogue).  So every 32-row strip
+// of the wave's sub-tile goes through a wave-private piece of LDS (fp32, 16-byte chunks
+// XOR-swizzled with the row: both sides at the LDS's full rate) and leaves in row-major order:
+// 8 lanes (bf16 outputs, 8 columns per lane) or 16 lanes (fp32 accumulator, 4 columns per lane)
+// cover 128 / 256 contiguous bytes of a row, and the residual / pre-activation operands are read
+// the same way.  The arithmetic and its order are those of a direct store: one rounding to bf16.
+__device__ __forceinline__ void unpack8(uint4 w, float (&v)[8]) {
+  v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xffff0000u);
+  v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
+  v[4] = __uint_as_float(w.z << 16); v[5] = __uint_as_float(w.z & 0xffff0000u);
+  v[6] = __uint_as_float(w.w << 16); v[7] = __uint_as_float(w.w & 0xffff0000u);
+}
+__device__ __forceinline__ uint4 pack8(const float (&v)[8]) {
+  return make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+}
+__device__ __forceinline__ void wave_lds_sync() {
+  // LDS serves one wave's instructions in order; this only keeps the compiler from moving the
+  // strip's reads above its writes (or the next strip's writes above these reads)
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <int MI, int NI, int WM, int WN, int EPI>
 __device__ __forceinline__ void epilogue(const f32x16 (&acc)[MI][NI], const BfParams& p, int m0, int n0, int wm,
-                                         int wn, int lane) {
-  const int khalf = lane >> 5;
+                                         int wn, int lane, uint4* smem, int wave, int mi_begin, int mi_count) {
+  constexpr int CPR = WN / 4;   // 16-byte chunks per strip row
+  static_assert(CPR >= 16, "row swizzle spans 16 chunks");
+  float4* strip = reinterpret_cast<float4*>(smem) + wave * (32 * CPR);
+  const int r = lane & 31, khalf = lane >> 5;
+  const int col_base = n0 + wn * WN;
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
-    const int row = m0 + wm * WM + mi * 32 + (lane & 31);
-    if (row >= p.M) continue;
+    if (mi < mi_begin || mi >= mi_begin + mi_count) continue;   // wave-uniform
+    const int row_base = m0 + wm * WM + mi * 32;
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
+    for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int col = n0 + wn * WN + ni * 32 + 8 * g + 4 * khalf;
-        if (col >= p.N) continue;   // N is a multiple of 8: a quad is inside or outside as a whole
-        const int64_t idx = (int64_t)row * p.ldc + col;
-        float v[4];
+        const int chunk = ni * 8 + 2 * g + khalf;
+        strip[r * CPR + (chunk ^ (r & 15))] =
+            make_float4(acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2], acc[mi][ni][4 * g + 3]);
+      }
+    wave_lds_sync();
+    if (EPI == kEpiAccum) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = acc[mi][ni][4 * g + j];
-        if (EPI == kEpiStore || EPI == kEpiGelu) {
-          if (p.bias) {
-            float b[4];
-            unpack4(*reinterpret_cast<const uint2*>(p.bias + col), b);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] += b[j];
-          }
-        }
-        if (EPI == kEpiStore) {
-          if (p.aux) {
-            float r[4];
-            unpack4(*reinterpret_cast<const uint2*>(p.aux + idx), r);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] += r[j];
-          }
-          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + idx) = pack4(v);
-        } else if (EPI == kEpiGelu) {
-          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + idx) = pack4(v);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = gelu_fast(v[j]);
-          *reinterpret_cast<uint2*>(p.aux_out + idx) = pack4(v);
-        } else if (EPI == kEpiGeluGrad) {
-          float u[4];
-          unpack4(*reinterpret_cast<const uint2*>(p.aux + idx), u);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] *= gelu_grad_fast(u[j]);
-          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + idx) = pack4(v);
-        } else {
-          float4* c = reinterpret_cast<float4*>(static_cast<float*>(p.C) + idx);
-          float4 o = make_float4(v[0], v[1], v[2], v[3]);
+      for (int it = 0; it < WN / 8; ++it) {
+        const int L = it * 64 + lane;
+        const int rr = L / CPR, c = L % CPR;
+        const float4 v = strip[rr * CPR + (c ^ (rr & 15))];
+        const int row = row_base + rr, col = col_base + c * 4;
+        if (row < p.M && col < p.N) {
+          float4* dst = reinterpret_cast<float4*>(static_cast<float*>(p.C) + (int64_t)row * p.ldc + col);
+          float4 o = v;
           if (p.accumulate) {
-            const float4 old = *c;
+            const float4 old = *dst;
             o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
           }
-          *c = o;
+          *dst = o;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int it = 0; it < WN / 16; ++it) {
+        const int L = it * 64 + lane;
+        const int rr = L / (WN / 8), c8 = L % (WN / 8);
+        const float4 lo = strip[rr * CPR + ((2 * c8) ^ (rr & 15))];
+        const float4 hi = strip[rr * CPR + ((2 * c8 + 1) ^ (rr & 15))];
+        const int row = row_base + rr, col = col_base + c8 * 8;
+        if (row < p.M && col < p.N) {   // N is a multiple of 8: a group of 8 columns is inside or outside as a whole
+          const int64_t idx = (int64_t)row * p.ldc + col;
+          float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+          if ((EPI == kEpiStore || EPI == kEpiGelu) && p.bias) {
+            float b[8];
+            unpack8(*reinterpret_cast<const uint4*>(p.bias + col), b);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] += b[j];
+          }
+          bf16_t* out = static_cast<bf16_t*>(p.C) + idx;
+          if (EPI == kEpiStore) {
+            if (p.aux) {
+              float res[8];
+              unpack8(*reinterpret_cast<const uint4*>(p.aux + idx), res);
+#pragma unroll
+              for (int j = 0; j < 8; ++j) v[j] += res[j];
+            }
+            *reinterpret_cast<uint4*>(out) = pack8(v);
+          } else if (EPI == kEpiGelu) {
+            *reinterpret_cast<uint4*>(out) = pack8(v);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = gelu_fast(v[j]);
+            *reinterpret_cast<uint4*>(p.aux_out + idx) = pack8(v);
+          } else {   // kEpiGeluGrad
+            float u[8];
+            unpack8(*reinterpret_cast<const uint4*>(p.aux + idx), u);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] *= gelu_grad_fast(u[j]);
+            *reinterpret_cast<uint4*>(out) = pack8(v);
+          }
         }
       }
     }
+    wave_lds_sync();
   }
 }
 
-template <int BM, int BN, int WM, int WN, int BK, bool TA, bool TB, int EPI>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(GroupParams gp) {
-  constexpr int NT = (BM / WM) * (BN / WN) * 64;
+// KSPLIT = 2: two groups of waves share the workgroup's tile and split its K range in halves, each
+// with its own pair of LDS stages; at the end the groups swap halves of their partial sums through
+// LDS and each finishes half of the tile's rows.  For launches with about one tile per CU this
+// doubles the waves per SIMD (the LDS and global-load latencies of one group hide behind the
+// MFMAs of the other) without shrinking the tile; the sum order is fixed, so results do not
+// depend on timing.
+template <int BM, int BN, int WM, int WN, int BK, bool TA, bool TB, int EPI, int KSPLIT>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KSPLIT) void gemm_bf16_kernel(GroupParams gp) {
+  constexpr int NT = (BM / WM) * (BN / WN) * 64;   // threads of one K group
   constexpr int CH = BK / 8;
   constexpr int MI = WM / 32, NI = WN / 32;
   constexpr int WAVES_N = BN / WN;
   constexpr int KS = BK / 16;
-  constexpr bool kFragDbuf = NT <= 256;
-  extern __shared__ uint4 smem[];
+  constexpr bool kFragDbuf = NT * KSPLIT <= 256;
+  static_assert(KSPLIT == 1 || (KSPLIT == 2 && MI % 2 == 0), "");
+  extern __shared__ uint4 smem_all[];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kg = KSPLIT == 1 ? 0 : (int)threadIdx.x / NT;   // wave-uniform
+  const int tid = threadIdx.x - kg * NT, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
   // Workgroup -> tile: consecutive workgroup ids land on different XCDs (round-robin over 8),
@@ -346,6 +402,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
   ld_b.init(TB ? p.B + (int64_t)n0 * p.ldb : p.B + n0, p.ldb, p.N - n0, tid);
 
   constexpr int kStage = (BM + BN) * CH;  // uint4 per stage
+  uint4* smem = smem_all + kg * 2 * kStage;
   f32x16 acc[MI][NI];
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi)
@@ -354,23 +411,34 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-  const int nk = (p.K + BK - 1) / BK;
-  ld_a.load(0, p.K);
-  ld_b.load(0, p.K);
+  // this group's K tiles: [kt0, kt0 + nk) in units of BK, elements below k_hi (a group whose range
+  // is short or empty runs the same number of steps on zero-filled tiles: barriers stay matched)
+  const int nk_all = (p.K + BK - 1) / BK;
+  const int nk = (nk_all + KSPLIT - 1) / KSPLIT;
+  const int kt0 = kg * nk;
+  const int k_hi = min(p.K, (kt0 + nk) * BK);
+  ld_a.load(kt0 * BK, k_hi);
+  ld_b.load(kt0 * BK, k_hi);
   ld_a.store(smem);
   ld_b.store(smem + BM * CH);
-  ld_a.load(BK, p.K);   // tile 1 stays in flight in registers during the first K step
-  ld_b.load(BK, p.K);
+  ld_a.load((kt0 + 1) * BK, k_hi);   // tile 1 stays in flight in registers during the first K step
+  ld_b.load((kt0 + 1) * BK, k_hi);
   __syncthreads();
 
   const int khalf = lane >> 5;
   // fragment addresses (uint4 index inside a stage's A / B tile) for sub-step 0; sub-step ks
-  // flips chunk bits: chunk = (2*ks + khalf) ^ swz(row)
-  int a_row[MI], b_row[NI];
+  // flips chunk bits: chunk = (2*ks + khalf) ^ swz(row), i.e. index ^ (2*ks)
+  int a_idx[MI], b_idx[NI];
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi) a_row[mi] = wm * WM + mi * 32 + (lane & 31);
+  for (int mi = 0; mi < MI; ++mi) {
+    const int row = wm * WM + mi * 32 + (lane & 31);
+    a_idx[mi] = row * CH + (khalf ^ swz<CH>(row));
+  }
 #pragma unroll
-  for (int ni = 0; ni < NI; ++ni) b_row[ni] = wn * WN + ni * 32 + (lane & 31);
+  for (int ni = 0; ni < NI; ++ni) {
+    const int row = wn * WN + ni * 32 + (lane & 31);
+    b_idx[ni] = row * CH + (khalf ^ swz<CH>(row));
+  }
 
   // K step kt: MFMAs on stage kt&1.  In the middle of the step the tile kt+1, whose global loads
   // were issued one whole step earlier, goes from registers to the other stage, and the loads of
@@ -379,6 +447,14 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
     const uint4* sA = smem + (kt & 1) * kStage;
     const uint4* sB = sA + BM * CH;
     uint4* dA = smem + ((kt + 1) & 1) * kStage;
+    // The per-sub-step addresses are one XOR away from a_idx / b_idx; hiding the values from the
+    // optimizer here keeps it from hoisting all KS x (MI + NI) of them out of the loop, where
+    // they would not fit in registers next to the accumulators.
+    int ai[MI], bi[NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) { ai[mi] = a_idx[mi]; asm volatile("" : "+v"(ai[mi])); }
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) { bi[ni] = b_idx[ni]; asm volatile("" : "+v"(bi[ni])); }
     // With one wave per SIMD (4-wave configurations) the fragments of sub-step ks+1 are read
     // while the MFMAs of sub-step ks run; with two waves per SIMD the other wave covers the LDS
     // latency and the registers are better spent elsewhere.
@@ -386,11 +462,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
     bf16x8 af[FB][MI], bfr[FB][NI];
     if (kFragDbuf) {
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
-        af[0][mi] = __builtin_bit_cast(bf16x8, sA[a_row[mi] * CH + (khalf ^ swz<CH>(a_row[mi]))]);
+      for (int mi = 0; mi < MI; ++mi) af[0][mi] = __builtin_bit_cast(bf16x8, sA[ai[mi]]);
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-        bfr[0][ni] = __builtin_bit_cast(bf16x8, sB[b_row[ni] * CH + (khalf ^ swz<CH>(b_row[ni]))]);
+      for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = __builtin_bit_cast(bf16x8, sB[bi[ni]]);
     }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -398,11 +472,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
       const int kr = kFragDbuf ? ks + 1 : ks;   // sub-step whose fragments are read now
       if (kr < KS) {
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-          af[nxt][mi] = __builtin_bit_cast(bf16x8, sA[a_row[mi] * CH + ((kr * 2 + khalf) ^ swz<CH>(a_row[mi]))]);
+        for (int mi = 0; mi < MI; ++mi) af[nxt][mi] = __builtin_bit_cast(bf16x8, sA[ai[mi] ^ (kr * 2)]);
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-          bfr[nxt][ni] = __builtin_bit_cast(bf16x8, sB[b_row[ni] * CH + ((kr * 2 + khalf) ^ swz<CH>(b_row[ni]))]);
+        for (int ni = 0; ni < NI; ++ni) bfr[nxt][ni] = __builtin_bit_cast(bf16x8, sB[bi[ni] ^ (kr * 2)]);
       }
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
@@ -410,8 +482,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
         for (int ni = 0; ni < NI; ++ni)
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
       // sub-steps 0..KS/2-1 move slices of the A tile, the rest slices of the B tile
-      if (ks < KS / 2) ld_a.step(ks, KS / 2, dA, (kt + 2) * BK, p.K);
-      else ld_b.step(ks - KS / 2, KS / 2, dA + BM * CH, (kt + 2) * BK, p.K);
+      if (ks < KS / 2) ld_a.step(ks, KS / 2, dA, (kt0 + kt + 2) * BK, k_hi);
+      else ld_b.step(ks - KS / 2, KS / 2, dA + BM * CH, (kt0 + kt + 2) * BK, k_hi);
       // keep each slice's stores and loads inside its sub-step: left alone, the scheduler sinks
       // every global load to the end of the K step and hoists the selects that wait for them
       __builtin_amdgcn_sched_barrier(0);
@@ -419,7 +491,43 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
     __syncthreads();
   }
 
-  epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane);
+  if (KSPLIT == 2) {
+    // group kg keeps block rows mi with mi / (MI/2) == kg and receives the other group's partial
+    // sums for them: slot j of thread t of group q sits at float4 index (j * 2 + q) * NT + t
+    float4* xb = reinterpret_cast<float4*>(smem_all);
+    constexpr int H = MI / 2;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      if ((mi / H) == kg) continue;
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          xb[(((mi % H) * NI + ni) * 4 + q) * 2 * NT + kg * NT + tid] =
+              make_float4(acc[mi][ni][4 * q], acc[mi][ni][4 * q + 1], acc[mi][ni][4 * q + 2], acc[mi][ni][4 * q + 3]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      if ((mi / H) != kg) continue;
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 o = xb[(((mi % H) * NI + ni) * 4 + q) * 2 * NT + (1 - kg) * NT + tid];
+          // fixed order: low K half + high K half
+          acc[mi][ni][4 * q] = kg == 0 ? acc[mi][ni][4 * q] + o.x : o.x + acc[mi][ni][4 * q];
+          acc[mi][ni][4 * q + 1] = kg == 0 ? acc[mi][ni][4 * q + 1] + o.y : o.y + acc[mi][ni][4 * q + 1];
+          acc[mi][ni][4 * q + 2] = kg == 0 ? acc[mi][ni][4 * q + 2] + o.z : o.z + acc[mi][ni][4 * q + 2];
+          acc[mi][ni][4 * q + 3] = kg == 0 ? acc[mi][ni][4 * q + 3] + o.w : o.w + acc[mi][ni][4 * q + 3];
+        }
+    }
+    // strips live behind the exchange buffer: no wave overwrites partial sums another still reads
+    constexpr int kXchg = H * NI * 4 * 2 * NT;   // float4 = uint4 units
+    epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane, smem_all + kXchg, (int)threadIdx.x >> 6, kg * H, H);
+  } else {
+    epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane, smem_all, wave, 0, MI);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -596,7 +704,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_async_ke
     rs = rs + 1 == NSTAGE ? 0 : rs + 1;
     ws = ws + 1 == NSTAGE ? 0 : ws + 1;
   }
-  epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane);
+  if (NSTAGE > 2) {   // prefetches past the end may still be landing in LDS
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+  }
+  epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane, smem, wave, 0, MI);
 }
 
 template <int BM, int BN, int WM, int WN, int BKA, int NSTAGE, bool TA, bool TB, int EPI>
@@ -623,11 +735,12 @@ hipError_t launch_async(GroupParams gp, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WM, int WN, int BK, bool TA, bool TB, int EPI>
+template <int BM, int BN, int WM, int WN, int BK, bool TA, bool TB, int EPI, int KSPLIT = 1>
 hipError_t launch(GroupParams gp, hipStream_t s) {
-  constexpr int NT = (BM / WM) * (BN / WN) * 64;
-  constexpr size_t lds = 2 * (BM + BN) * (BK / 8) * sizeof(uint4);
-  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, BK, TA, TB, EPI>;
+  constexpr int NT = (BM / WM) * (BN / WN) * 64 * KSPLIT;
+  constexpr size_t lds = KSPLIT * 2 * (BM + BN) * (BK / 8) * sizeof(uint4);
+  static_assert(KSPLIT == 1 || (BM * BN + NT / 64 * 32 * WN) * 4 <= lds, "exchange buffer + strips fit in the stages");
+  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, BK, TA, TB, EPI, KSPLIT>;
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -653,19 +766,23 @@ int g_tile_override = 0;  // 0: heuristic; else force a tile shape (tuning aid)
 int choose_tile(const BfParams* p, int count, bool ta, bool tb) {
   int tile = g_tile_override;
   if (tile == 0) {
-    // Measured on MI355X (M = 4096..8192): 128x128 tiles with two workgroups per CU win until
-    // 256x256 tiles give at least 3/4 of the CUs a tile; then the 8-wave 256x256 kernels win, the
-    // asynchronous one when both operands are K-contiguous (it needs K % 64 == 0 and falls back
-    // to the register-staged kernel otherwise), the register-staged one for the other forms.
-    int64_t big = 0;
-    for (int g = 0; g < count; ++g) big += (int64_t)ceil_div(p[g].M, 256) * ceil_div(p[g].N, 256);
+    // Measured on MI355X (M = 4096..8192): once 256x256 tiles give at least 3/4 of the CUs a tile
+    // the 8-wave 256x256 kernels win (the asynchronous one is on par when both operands are
+    // K-contiguous; it needs K % 64 == 0 and falls back to the register-staged kernel otherwise).
+    // Below that, 128x128 tiles: two workgroups per CU when there are enough tiles, and the
+    // variant with two K groups per workgroup when there is about one tile per CU (+15..25 %).
+    int64_t big = 0, small = 0;
+    for (int g = 0; g < count; ++g) {
+      big += (int64_t)ceil_div(p[g].M, 256) * ceil_div(p[g].N, 256);
+      small += (int64_t)ceil_div(p[g].M, 128) * ceil_div(p[g].N, 128);
+    }
     if (big >= 192) tile = (!ta && tb) ? 13 : 3;
-    else tile = 2;
+    else tile = small <= 256 ? 6 : 2;
   }
   if (tile > 10) {   // the asynchronous kernels need whole K tiles
     for (int g = 0; g < count; ++g)
       if (p[g].K % 64) { tile -= 10; break; }
-    if (tile == 4 || tile == 5 || tile == 6 || tile == 7) tile = 2;   // no register-staged twin
+    if (tile == 4 || tile == 5 || tile == 7) tile = 2;   // no register-staged twin
   }
   return tile;
 }
@@ -679,6 +796,7 @@ hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
     case 3: return launch<256, 256, 128, 64, 64, TA, TB, EPI>(gp, s);   // 8 waves
     case 4: return launch<128, 128, 64, 64, 128, TA, TB, EPI>(gp, s);   // deeper K step
     case 5: return launch<256, 128, 128, 64, 64, TA, TB, EPI>(gp, s);
+    case 6: return launch<128, 128, 64, 64, 64, TA, TB, EPI, 2>(gp, s);   // two K groups of 4 waves
     case 11: return launch_async<256, 256, 128, 128, 64, 2, TA, TB, EPI>(gp, s);
     case 12: return launch_async<128, 128, 64, 64, 64, 2, TA, TB, EPI>(gp, s);
     case 13: return launch_async<256, 256, 128, 64, 64, 2, TA, TB, EPI>(gp, s);
@@ -691,9 +809,9 @@ hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
 }
 
 bool vector_ok(const GemmDesc& d) {
-  // 8-byte / 16-byte vector accesses in the epilogue
-  return !(d.N % 8 || d.ldc % 8 || (reinterpret_cast<uintptr_t>(d.C) & 15) || (reinterpret_cast<uintptr_t>(d.bias) & 7) ||
-           (reinterpret_cast<uintptr_t>(d.aux) & 7) || (reinterpret_cast<uintptr_t>(d.aux_out) & 7));
+  // 16-byte vector accesses in the epilogue
+  return !(d.N % 8 || d.ldc % 8 || (reinterpret_cast<uintptr_t>(d.C) & 15) || (reinterpret_cast<uintptr_t>(d.bias) & 15) ||
+           (reinterpret_cast<uintptr_t>(d.aux) & 15) || (reinterpret_cast<uintptr_t>(d.aux_out) & 15));
 }
 
 BfParams to_params(const GemmDesc& d) {
@@ -715,9 +833,10 @@ void gemm_bf16_kernel_name(const GemmDesc* d, int count, char* out, size_t cap) 
   const char* ta = d[0].trans_a ? "true" : "false";
   const char* tb = d[0].trans_b ? "true" : "false";
   switch (tile) {
-    case 1: snprintf(out, cap, "gemm_bf16_kernel<256, 256, 128, 128, 64, %s, %s, %d>", ta, tb, d[0].epilogue); break;
-    case 2: snprintf(out, cap, "gemm_bf16_kernel<128, 128, 64, 64, 64, %s, %s, %d>", ta, tb, d[0].epilogue); break;
-    case 3: snprintf(out, cap, "gemm_bf16_kernel<256, 256, 128, 64, 64, %s, %s, %d>", ta, tb, d[0].epilogue); break;
+    case 1: snprintf(out, cap, "gemm_bf16_kernel<256, 256, 128, 128, 64, %s, %s, %d, 1>", ta, tb, d[0].epilogue); break;
+    case 2: snprintf(out, cap, "gemm_bf16_kernel<128, 128, 64, 64, 64, %s, %s, %d, 1>", ta, tb, d[0].epilogue); break;
+    case 3: snprintf(out, cap, "gemm_bf16_kernel<256, 256, 128, 64, 64, %s, %s, %d, 1>", ta, tb, d[0].epilogue); break;
+    case 6: snprintf(out, cap, "gemm_bf16_kernel<128, 128, 64, 64, 64, %s, %s, %d, 2>", ta, tb, d[0].epilogue); break;
     case 13: snprintf(out, cap, "gemm_bf16_async_kernel<256, 256, 128, 64, 64, 2, %s, %s, %d>", ta, tb, d[0].epilogue); break;
     default: snprintf(out, cap, "gemm_bf16 tile %d <%s, %s, %d>", tile, ta, tb, d[0].epilogue); break;
   }

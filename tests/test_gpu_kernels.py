@@ -114,6 +114,47 @@ def test_gemm_weight_gradient_form_coalesces_in_place(dtype, M, N, K):
     assert rel(to_host(G), g1 + x2.astype(np.float64).T @ d2.astype(np.float64)) < 2e-6
 
 
+@pytest.mark.parametrize("tile", [1, 2, 3, 5, 6, 11, 12, 13])
+@pytest.mark.parametrize("M,N,K", [(296, 264, 200), (328, 272, 192), (136, 520, 64)])
+def test_gemm_every_tile_variant(tile, M, N, K):
+    """Each tile shape / staging variant of the bf16 kernel, forced, on ragged shapes in all three forms:
+    K = 200 is not a multiple of the K step (the direct-to-LDS variants fall back), K = 192 is three K
+    steps (uneven halves for the variant with two K groups), K = 64 leaves its second group empty."""
+    rng = np.random.default_rng(tile * 1000 + M + N + K)
+    L = B.lib()
+    assert L.k2bw_tune_gemm_tile(tile) == 0
+    try:
+        x, w, b = rnd(rng, (M, K), BF16), rnd(rng, (K, N), BF16, 0.1), rnd(rng, (N,), BF16)
+        X, W, Bv = dev(x, BF16), dev(w, BF16), dev(b, BF16)
+        U, Gl = empty((M, N), BF16), empty((M, N), BF16)
+        assert L.k2bw_gemm(BF16, 0, 0, 1, M, N, K, X.data_ptr(), K, W.data_ptr(), N, U.data_ptr(), N, Bv.data_ptr(),
+                           None, Gl.data_ptr(), 0, None) == 0
+        sync()
+        want_u = x.astype(np.float64) @ w.astype(np.float64) + b
+        assert rel(to_host(U), want_u) < TIGHT[BF16]
+        assert rel(to_host(Gl), ob.gelu(want_u)) < TIGHT[BF16]
+
+        wt = rnd(rng, (N, K), BF16, 0.1)
+        Wt, Cc = dev(wt, BF16), empty((M, N), BF16)
+        u_host = to_host(U)
+        assert L.k2bw_gemm(BF16, 0, 1, 2, M, N, K, X.data_ptr(), K, Wt.data_ptr(), K, Cc.data_ptr(), N, None,
+                           U.data_ptr(), None, 0, None) == 0
+        sync()
+        want = (x.astype(np.float64) @ wt.astype(np.float64).T) * ob.gelu_grad(u_host.astype(np.float64))
+        assert rel(to_host(Cc), want) < TIGHT[BF16]
+
+        xt, dy = rnd(rng, (K, M), BF16), rnd(rng, (K, N), BF16)
+        G = torch.full((M, N), float("nan"), device="cuda", dtype=torch.float32)
+        Xt, DY = dev(xt, BF16), dev(dy, BF16)
+        for acc in (0, 1):
+            assert L.k2bw_gemm(BF16, 1, 0, 3, M, N, K, Xt.data_ptr(), M, DY.data_ptr(), N, G.data_ptr(), N, None,
+                               None, None, acc, None) == 0
+        sync()
+        assert rel(to_host(G), 2.0 * (xt.astype(np.float64).T @ dy.astype(np.float64))) < 2e-6
+    finally:
+        assert L.k2bw_tune_gemm_tile(0) == 0
+
+
 def test_gemm_rejects_shapes_it_cannot_take():
     L = B.lib()
     a = torch.zeros(64 * 64, device="cuda", dtype=torch.bfloat16)
