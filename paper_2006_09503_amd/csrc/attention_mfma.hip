@@ -15,27 +15,33 @@
 // second, k-slots 8*(l/32)..+7; it gets column l%32 of the result, rows 8*(r/4)+4*(l/32)+(r%4)
 // in register r.  Re-using a result as a second operand therefore fixes which actual index
 // sits in which k-slot (slot t of half hf <-> index 16*kk + 4*hf + t for t < 4, 16*kk + 8 +
-// 4*hf + t - 4 otherwise); the first operand is read from a transposed LDS tile in 8-byte
-// pieces of four consecutive indices to match.
+// 4*hf + t - 4 otherwise); the transposing LDS reads deliver the first operand in that order.
 //
-// LDS tiles: row-major [row][dh] with 16-byte chunks and one chunk of padding per row, and
-// transposed [d][64 rows] in 8-byte pieces with one piece of padding per row (odd strides:
-// conflict-free for 32 consecutive rows).  Masked keys get probability exactly zero.
+// LDS tiles are row-major [64 rows][dh] copies of K, V, Q or dO rows, filled straight from HBM by
+// global_load_lds (16 bytes per lane, no registers, no LDS store instructions), two stages deep:
+// the loads of tile t+1 are in flight while tile t is consumed, one barrier per tile.  A tile
+// serves both operand forms: rows as MFMA rows (16-byte reads along dh) and, through
+// ds_read_b64_tr_b16, columns as MFMA rows (the transposed operands K^T, V^T, Q^T, dO^T), so no
+// transposed copy is ever built.  16-byte chunks are XOR-swizzled by row so that both read
+// patterns are bank-conflict free.  Masked keys get probability exactly zero.
 #include "kernels.hpp"
 
 namespace k2bw {
-
-hipError_t attention_delta(const AttnDesc& d, const void* o, const void* d_o, float* delta, hipStream_t st);
 
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef short v8i16 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) v4i16 lds_v4i16_t;
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(3))) char lds_char_t;
+typedef __attribute__((address_space(1))) const void glob_void_t;
 
 constexpr int kThreads = 256;
 constexpr int kBlockRows = 128;   // rows (queries or keys) owned by a workgroup: 4 waves x 32
 constexpr int kTile = 64;         // rows streamed through LDS per step
-constexpr int kTP = 17;           // 8-byte pieces per row of a transposed tile (16 + 1 pad)
 constexpr float kLog2e = 1.4426950408889634f;
 
 template <int DH>
@@ -43,89 +49,61 @@ struct Cfg {
   static constexpr int KS = DH / 16;               // MFMA k-steps over the head dimension
   static constexpr int DHP = (DH + 31) / 32 * 32;  // head dimension padded to whole 32-row blocks
   static constexpr int DB = DHP / 32;
-  static constexpr int KC = DH / 8 + 1;            // 16-byte chunks per row of a row-major tile
-  static constexpr int kRowTile = kTile * KC;      // uint4 per row-major tile
-  static constexpr int kTrTile = DHP * kTP;        // uint2 per transposed tile
+  static constexpr int CH = DH / 8;                // 16-byte chunks per tile row
+  static constexpr int kTileU4 = kTile * CH;       // uint4 per tile
+  static constexpr int kPadU4 = 4;                 // transposing reads of the padded head columns run past a row
 };
 
-__device__ __forceinline__ uint32_t word(const uint4& v, int i) {
-  return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w;
+// Chunk swizzle per head size (rows are 64 / 128 / 160 / 256 bytes; the LDS has 64 banks of 4 bytes).
+// Checked against a bank model for both read patterns: 16-byte reads of 16 consecutive rows at one
+// logical chunk, and the transposing 8-byte reads (4 consecutive rows x 32 or 64 contiguous bytes).
+template <int DH>
+__device__ __forceinline__ int swz(int r) {
+  if (DH == 32) return (r >> 2) & 3;
+  if (DH == 64) { const int u = (r >> 1) & 7; return ((u & 1) << 2) | (u >> 1); }
+  if (DH == 80) return (r >> 3) & 1;
+  return ((r & 3) << 2) | ((r >> 2) & 3);
 }
 
-// Tiles go HBM -> registers -> LDS in two steps so that the loads of the next tile are in
-// flight while the current one is being consumed.
-// rows [row0, row0+64) x DH of a [*, ld] matrix -> row-major LDS tile; rows >= row_end are zero
-template <int DH>
-struct RowFetch {
-  static constexpr int C = DH / 8;
-  static constexpr int N = (kTile * C + kThreads - 1) / kThreads;
-  uint4 v[N];
-  __device__ __forceinline__ void fetch(const bf16_t* __restrict__ src, int64_t ld, int row0, int row_end, int tid) {
-#pragma unroll
-    for (int it = 0; it < N; ++it) {
-      const int e = tid + it * kThreads;
-      const int r = e / C, c = e % C;
-      v[it] = make_uint4(0, 0, 0, 0);
-      if (e < kTile * C && row0 + r < row_end)
-        v[it] = *reinterpret_cast<const uint4*>(src + (int64_t)(row0 + r) * ld + c * 8);
-    }
-  }
-  __device__ __forceinline__ void commit(uint4* tile, int tid) const {
-#pragma unroll
-    for (int it = 0; it < N; ++it) {
-      const int e = tid + it * kThreads;
-      if (e < kTile * C) tile[(e / C) * Cfg<DH>::KC + e % C] = v[it];
-    }
-  }
-};
+// s_waitcnt immediate for "at most n vector-memory operations outstanding" (gfx9 encoding)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
-// the same rows, transposed: tile[d][row] in 8-byte pieces of 4 consecutive rows
+// Rows [row0, row0 + 64) x DH of a [*, ld] matrix -> LDS tile; lane i of a load instruction owns
+// LDS slot L0 + i and fetches the chunk that belongs there.  Rows >= row_end are fetched from row
+// row_end - 1 (finite data; whatever they produce is masked or never stored).
 template <int DH>
-struct TrFetch {
-  static constexpr int C = DH / 8;
-  static constexpr int N = (16 * C + kThreads - 1) / kThreads;
-  uint4 v[N][4];
-  __device__ __forceinline__ void fetch(const bf16_t* __restrict__ src, int64_t ld, int row0, int row_end, int tid) {
+struct TileLoader {
+  static constexpr int CH = DH / 8;
+  static constexpr int kInstr = kTile * CH / 64;            // wave-instructions per tile
+  static constexpr int NI = (kInstr + 3) / 4;               // per wave (4 waves)
+  int row[NI], coff[NI];
+  int wave_;
+  __device__ __forceinline__ void init(int wave, int lane) {
+    wave_ = wave;
 #pragma unroll
-    for (int it = 0; it < N; ++it) {
-      const int u = tid + it * kThreads;
-      const int rq = u % 16, c = u / 16;   // row quad, d chunk
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int r = row0 + rq * 4 + j;
-        v[it][j] = make_uint4(0, 0, 0, 0);
-        if (u < 16 * C && r < row_end) v[it][j] = *reinterpret_cast<const uint4*>(src + (int64_t)r * ld + c * 8);
-      }
+    for (int j = 0; j < NI; ++j) {
+      const int L = (j * 4 + wave) * 64 + lane;
+      const int r = L / CH, pc = L % CH;
+      row[j] = r < kTile ? r : kTile - 1;
+      coff[j] = (pc ^ swz<DH>(r)) * 8;
     }
   }
-  __device__ __forceinline__ void commit(uint2* tile, int tid) const {
+  __device__ __forceinline__ void issue(const bf16_t* __restrict__ src, int64_t ld, int row0, int row_end, uint4* tile) const {
 #pragma unroll
-    for (int it = 0; it < N; ++it) {
-      const int u = tid + it * kThreads;
-      if (u >= 16 * C) continue;
-      const int rq = u % 16, c = u / 16;
-#pragma unroll
-      for (int ii = 0; ii < 8; ++ii) {
-        const int wd = ii >> 1;
-        const uint32_t w0 = word(v[it][0], wd), w1 = word(v[it][1], wd), w2 = word(v[it][2], wd), w3 = word(v[it][3], wd);
-        uint2 o;
-        if (ii & 1) {
-          o.x = __builtin_amdgcn_perm(w1, w0, 0x07060302u);
-          o.y = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
-        } else {
-          o.x = __builtin_amdgcn_perm(w1, w0, 0x05040100u);
-          o.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
-        }
-        tile[(c * 8 + ii) * kTP + rq] = o;
+    for (int j = 0; j < NI; ++j) {
+      if ((j * 4 + wave_) < kInstr) {   // wave-uniform
+        const int r = min(row0 + row[j], row_end - 1);
+        __builtin_amdgcn_global_load_lds((glob_void_t*)(src + (int64_t)r * ld + coff[j]),
+                                         (lds_void_t*)(tile + (j * 4 + wave_) * 64), 16, 0, 0);
       }
     }
   }
 };
 
-template <int DH>
-__device__ __forceinline__ void zero_pad_rows(uint2* tile, int tid) {
-  if (Cfg<DH>::DHP > DH)
-    for (int e = tid; e < (Cfg<DH>::DHP - DH) * kTP; e += kThreads) tile[DH * kTP + e] = make_uint2(0, 0);
+// 64 floats starting at src[i0] -> LDS, by one wave (4 bytes per lane); entries past n_valid repeat the last one
+__device__ __forceinline__ void issue_floats(const float* __restrict__ src, int i0, int n_valid, float* dst, int lane) {
+  const int i = min(i0 + lane, n_valid - 1);
+  __builtin_amdgcn_global_load_lds((glob_void_t*)(src + i), (lds_void_t*)dst, 4, 0, 0);
 }
 
 // 16-byte k-fragment of a row of a [*, ld] matrix straight from HBM (second MFMA operand)
@@ -139,6 +117,12 @@ __device__ __forceinline__ void load_frags(const bf16_t* __restrict__ row_ptr, b
   }
 }
 
+// first operand, rows of the tile as MFMA rows: row `row`, head columns 16*ks + 8*hf .. +7
+template <int DH>
+__device__ __forceinline__ bf16x8 read_rows(const uint4* tile, int row, int ks, int hf) {
+  return __builtin_bit_cast(bf16x8, tile[row * Cfg<DH>::CH + ((ks * 2 + hf) ^ swz<DH>(row))]);
+}
+
 // registers 8*half .. 8*half+7 of a result block -> second operand of the next MFMA
 __device__ __forceinline__ bf16x8 pack_half(const f32x16& v, int half) {
   uint4 w;
@@ -148,11 +132,23 @@ __device__ __forceinline__ bf16x8 pack_half(const f32x16& v, int half) {
   return __builtin_bit_cast(bf16x8, w);
 }
 
-// first operand from a transposed tile: row d, index group kk (16 indices), this lane's half
-__device__ __forceinline__ bf16x8 read_tr(const uint2* tile, int d, int kk, int hf) {
-  const uint2 p0 = tile[d * kTP + 4 * kk + hf];
-  const uint2 p1 = tile[d * kTP + 4 * kk + 2 + hf];
-  return __builtin_bit_cast(bf16x8, make_uint4(p0.x, p0.y, p1.x, p1.y));
+// First operand, head columns of the tile as MFMA rows: this lane's row is head column
+// d0 + lane % 32, its k-slots are tile rows 16*kk + 4*hf + 0..3 and 16*kk + 8 + 4*hf + 0..3 (the
+// order in which a 32x32 result block, re-used as second operand, holds them).
+// ds_read_b64_tr_b16, measured on gfx950: within each group of 16 lanes, lane a + 4t supplies the
+// address of 4 consecutive columns of row t, and lane 4a + j receives rows 0..3 of column 4a + j.
+template <int DH>
+__device__ __forceinline__ bf16x8 read_cols(const uint4* tile, int d0, int kk, int lane) {
+  const int r16 = lane & 15, a = r16 & 3, t = r16 >> 2, hf = lane >> 5;
+  const int col = d0 + ((lane >> 4) & 1) * 16 + 4 * a;
+  const int r0 = 16 * kk + 4 * hf + t, r1 = r0 + 8;
+  const int b0 = r0 * (DH * 2) + (((col >> 3) ^ swz<DH>(r0)) << 4) + ((col >> 2) & 1) * 8;
+  const int b1 = r1 * (DH * 2) + (((col >> 3) ^ swz<DH>(r1)) << 4) + ((col >> 2) & 1) * 8;
+  const lds_char_t* base = (const lds_char_t*)tile;
+  const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t*)(base + b0));
+  const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t*)(base + b1));
+  const v8i16 w = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, w);
 }
 
 __device__ __forceinline__ f32x16 zero16() {
@@ -173,9 +169,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_mfma_kernel(const bf16_t* _
                                                                   float* __restrict__ lse, int s, int a, int mask_mode,
                                                                   const int32_t* __restrict__ seqlens) {
   using C = Cfg<DH>;
-  extern __shared__ uint4 smem[];
-  uint4* k_lds = smem;
-  uint2* vt_lds = reinterpret_cast<uint2*>(smem + C::kRowTile);
+  extern __shared__ uint4 smem[];   // stage st: K tile at st * 2 * kTileU4, V tile behind it
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
   const int n = blockIdx.z, head = blockIdx.y, i0 = blockIdx.x * kBlockRows;
@@ -196,28 +190,30 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_mfma_kernel(const bf16_t* _
   for (int db = 0; db < C::DB; ++db) oacc[db] = zero16();
   float m_i = -INFINITY, l_i = 0.f;
 
-  zero_pad_rows<DH>(vt_lds, tid);
   const int jend = causal ? min(i0 + kBlockRows, s) : kv_len;
-  RowFetch<DH> kfetch;
-  TrFetch<DH> vfetch;
-  kfetch.fetch(base + h, ld, 0, jend, tid);
-  vfetch.fetch(base + 2 * h, ld, 0, jend, tid);
-  for (int j0 = 0; j0 < jend; j0 += kTile) {
-    __syncthreads();
-    kfetch.commit(k_lds, tid);
-    vfetch.commit(vt_lds, tid);
-    __syncthreads();
-    kfetch.fetch(base + h, ld, j0 + kTile, jend, tid);        // next tile, in flight during the MFMAs
-    vfetch.fetch(base + 2 * h, ld, j0 + kTile, jend, tid);
+  const int ntiles = (jend + kTile - 1) / kTile;
+  TileLoader<DH> loader;
+  loader.init(wave, lane);
+  loader.issue(base + h, ld, 0, jend, smem);
+  loader.issue(base + 2 * h, ld, 0, jend, smem + C::kTileU4);
+  for (int t = 0; t < ntiles; ++t) {
+    const int j0 = t * kTile;
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // this wave's share of tile t has landed
+    __syncthreads();                            // ... and everyone's; all waves are done with tile t-1
+    if (t + 1 < ntiles) {
+      uint4* nxt = smem + ((t + 1) & 1) * 2 * C::kTileU4;
+      loader.issue(base + h, ld, j0 + kTile, jend, nxt);
+      loader.issue(base + 2 * h, ld, j0 + kTile, jend, nxt + C::kTileU4);
+    }
     if (causal && j0 > iw0 + 31) continue;   // every key of the tile lies after this wave's queries
+    const uint4* k_lds = smem + (t & 1) * 2 * C::kTileU4;
+    const uint4* v_lds = k_lds + C::kTileU4;
 
     f32x16 sacc[2] = {zero16(), zero16()};
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) {
-      const bf16x8 k0 = __builtin_bit_cast(bf16x8, k_lds[l32 * C::KC + ks * 2 + hf]);
-      const bf16x8 k1 = __builtin_bit_cast(bf16x8, k_lds[(32 + l32) * C::KC + ks * 2 + hf]);
-      sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[ks], sacc[0], 0, 0, 0);
-      sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[ks], sacc[1], 0, 0, 0);
+      sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows<DH>(k_lds, l32, ks, hf), qf[ks], sacc[0], 0, 0, 0);
+      sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows<DH>(k_lds, 32 + l32, ks, hf), qf[ks], sacc[1], 0, 0, 0);
     }
     // masks (only tiles that touch a boundary need them) and the running maximum
     const bool need_mask = (j0 + kTile > kv_len) || (causal && j0 + kTile - 1 > iw0);
@@ -260,7 +256,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_mfma_kernel(const bf16_t* _
     for (int db = 0; db < C::DB; ++db)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr(vt_lds, db * 32 + l32, kk, hf), pb[kk], oacc[db], 0, 0, 0);
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_cols<DH>(v_lds, db * 32, kk, lane), pb[kk], oacc[db], 0, 0, 0);
   }
 
   const float l_tot = l_i + __shfl_xor(l_i, 32, 64);
@@ -280,17 +276,14 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_mfma_kernel(const bf16_t* _
 }
 
 // ------------------------------------------------------------------------------------------------
-// dQ
+// dQ (and delta = rowsum(dO * O), which the dK/dV kernel reads afterwards)
 template <int DH>
-__global__ __launch_bounds__(kThreads) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
-                                                                 const float* __restrict__ lse, const float* __restrict__ delta,
-                                                                 bf16_t* __restrict__ dqkv, int s, int a, int mask_mode,
-                                                                 const int32_t* __restrict__ seqlens) {
+__global__ __launch_bounds__(kThreads) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
+                                                                 const bf16_t* __restrict__ d_o, const float* __restrict__ lse,
+                                                                 float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s,
+                                                                 int a, int mask_mode, const int32_t* __restrict__ seqlens) {
   using C = Cfg<DH>;
-  extern __shared__ uint4 smem[];
-  uint4* k_lds = smem;
-  uint4* v_lds = smem + C::kRowTile;
-  uint2* kt_lds = reinterpret_cast<uint2*>(smem + 2 * C::kRowTile);
+  extern __shared__ uint4 smem[];   // stage st: K tile at st * 2 * kTileU4, V tile behind it
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
   const int n = blockIdx.z, head = blockIdx.y, i0 = blockIdx.x * kBlockRows;
@@ -305,43 +298,53 @@ __global__ __launch_bounds__(kThreads) void attn_dq_mfma_kernel(const bf16_t* __
   const float scale = 1.0f / sqrtf((float)DH);
   const float c = scale * kLog2e;
 
+  const int jend = causal ? min(i0 + kBlockRows, s) : kv_len;
+  const int ntiles = (jend + kTile - 1) / kTile;
+  TileLoader<DH> loader;
+  loader.init(wave, lane);
+  loader.issue(base + h, ld, 0, jend, smem);
+  loader.issue(base + 2 * h, ld, 0, jend, smem + C::kTileU4);
+
   bf16x8 qf[C::KS], dof[C::KS];
   load_frags<DH>(base + (int64_t)i * ld, row_ok, hf, qf);
   load_frags<DH>(d_o + ((int64_t)n * s + i) * h + head * DH, row_ok, hf, dof);
+  float delta_i;
+  {
+    bf16x8 of[C::KS];
+    load_frags<DH>(o + ((int64_t)n * s + i) * h + head * DH, row_ok, hf, of);
+    float part = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part = fmaf((float)dof[ks][e], (float)of[ks][e], part);
+    delta_i = part + __shfl_xor(part, 32, 64);
+    if (row_ok && hf == 0) delta[((int64_t)n * a + head) * s + i] = delta_i;
+  }
   const float lse_i = row_ok ? lse[((int64_t)n * a + head) * s + i] * kLog2e : INFINITY;
-  const float delta_i = row_ok ? delta[((int64_t)n * a + head) * s + i] : 0.f;
   f32x16 dq[C::DB];
 #pragma unroll
   for (int db = 0; db < C::DB; ++db) dq[db] = zero16();
 
-  zero_pad_rows<DH>(kt_lds, tid);
-  const int jend = causal ? min(i0 + kBlockRows, s) : kv_len;
-  // (no register prefetch here: it would push the kernel past 256 registers per lane, and two
-  // waves per SIMD hide the tile loads better than one wave with prefetch -- measured)
-  for (int j0 = 0; j0 < jend; j0 += kTile) {
+  for (int t = 0; t < ntiles; ++t) {
+    const int j0 = t * kTile;
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
-    {
-      RowFetch<DH> kfetch, vfetch;
-      TrFetch<DH> ktfetch;
-      kfetch.fetch(base + h, ld, j0, jend, tid);
-      vfetch.fetch(base + 2 * h, ld, j0, jend, tid);
-      ktfetch.fetch(base + h, ld, j0, jend, tid);
-      kfetch.commit(k_lds, tid);
-      vfetch.commit(v_lds, tid);
-      ktfetch.commit(kt_lds, tid);
+    if (t + 1 < ntiles) {
+      uint4* nxt = smem + ((t + 1) & 1) * 2 * C::kTileU4;
+      loader.issue(base + h, ld, j0 + kTile, jend, nxt);
+      loader.issue(base + 2 * h, ld, j0 + kTile, jend, nxt + C::kTileU4);
     }
-    __syncthreads();
     if (causal && j0 > iw0 + 31) continue;
+    const uint4* k_lds = smem + (t & 1) * 2 * C::kTileU4;
+    const uint4* v_lds = k_lds + C::kTileU4;
 
     f32x16 sacc[2] = {zero16(), zero16()}, dp[2] = {zero16(), zero16()};
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) {
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
-        const bf16x8 kf = __builtin_bit_cast(bf16x8, k_lds[(nb * 32 + l32) * C::KC + ks * 2 + hf]);
-        const bf16x8 vf = __builtin_bit_cast(bf16x8, v_lds[(nb * 32 + l32) * C::KC + ks * 2 + hf]);
-        sacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[nb], 0, 0, 0);
-        dp[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], dp[nb], 0, 0, 0);
+        sacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows<DH>(k_lds, nb * 32 + l32, ks, hf), qf[ks], sacc[nb], 0, 0, 0);
+        dp[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows<DH>(v_lds, nb * 32 + l32, ks, hf), dof[ks], dp[nb], 0, 0, 0);
       }
     }
     const bool need_mask = (j0 + kTile > kv_len) || (causal && j0 + kTile - 1 > iw0);
@@ -364,7 +367,7 @@ __global__ __launch_bounds__(kThreads) void attn_dq_mfma_kernel(const bf16_t* __
     for (int db = 0; db < C::DB; ++db)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr(kt_lds, db * 32 + l32, kk, hf), dsb[kk], dq[db], 0, 0, 0);
+        dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_cols<DH>(k_lds, db * 32, kk, lane), dsb[kk], dq[db], 0, 0, 0);
   }
   if (!row_ok) return;
   bf16_t* out = dqkv + ((int64_t)n * s + i) * ld + head * DH;
@@ -388,12 +391,8 @@ __global__ __launch_bounds__(kThreads) void attn_dkv_mfma_kernel(const bf16_t* _
                                                                   const int32_t* __restrict__ seqlens) {
   using C = Cfg<DH>;
   extern __shared__ uint4 smem[];
-  uint4* q_lds = smem;
-  uint4* do_lds = smem + C::kRowTile;
-  uint2* qt_lds = reinterpret_cast<uint2*>(smem + 2 * C::kRowTile);
-  uint2* dot_lds = qt_lds + C::kTrTile;
-  float* lse_lds = reinterpret_cast<float*>(dot_lds + C::kTrTile);
-  float* delta_lds = lse_lds + kTile;
+  // stage st: Q tile, dO tile, 64 lse, 64 delta
+  constexpr int kStageU4 = 2 * C::kTileU4 + 2 * kTile / 4;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
   const int n = blockIdx.z, head = blockIdx.y, j0 = blockIdx.x * kBlockRows;
@@ -418,43 +417,40 @@ __global__ __launch_bounds__(kThreads) void attn_dkv_mfma_kernel(const bf16_t* _
 #pragma unroll
   for (int db = 0; db < C::DB; ++db) { dk[db] = zero16(); dv[db] = zero16(); }
 
-  zero_pad_rows<DH>(qt_lds, tid);
-  zero_pad_rows<DH>(dot_lds, tid);
   const bool wg_dead = j0 >= kv_len;                       // every key of the workgroup is padding
   const int istart = causal ? (j0 / kTile) * kTile : 0;    // earlier queries see none of these keys
-  for (int i0 = istart; i0 < s && !wg_dead; i0 += kTile) {
+  const int ntiles = wg_dead ? 0 : (s - istart + kTile - 1) / kTile;
+  TileLoader<DH> loader;
+  loader.init(wave, lane);
+  auto issue_tile = [&](int i0, uint4* stage) {
+    loader.issue(base, ld, i0, s, stage);
+    loader.issue(dobase, (int64_t)h, i0, s, stage + C::kTileU4);
+    float* f = reinterpret_cast<float*>(stage + 2 * C::kTileU4);
+    if (wave == 0) issue_floats(lse_row, i0, s, f, lane);
+    if (wave == 1) issue_floats(delta_row, i0, s, f + kTile, lane);
+  };
+  if (ntiles > 0) issue_tile(istart, smem);
+  for (int t = 0; t < ntiles; ++t) {
+    const int i0 = istart + t * kTile;
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
-    {
-      RowFetch<DH> qfetch, dofetch;
-      TrFetch<DH> qtfetch, dotfetch;
-      qfetch.fetch(base, ld, i0, s, tid);
-      dofetch.fetch(dobase, (int64_t)h, i0, s, tid);
-      qtfetch.fetch(base, ld, i0, s, tid);
-      dotfetch.fetch(dobase, (int64_t)h, i0, s, tid);
-      qfetch.commit(q_lds, tid);
-      dofetch.commit(do_lds, tid);
-      qtfetch.commit(qt_lds, tid);
-      dotfetch.commit(dot_lds, tid);
-    }
-    if (tid < kTile) {
-      const int i = i0 + tid;
-      lse_lds[tid] = i < s ? lse_row[i] * kLog2e : INFINITY;   // +inf: probability 0 for rows past the end
-      delta_lds[tid] = i < s ? delta_row[i] : 0.f;
-    }
-    __syncthreads();
+    if (t + 1 < ntiles) issue_tile(i0 + kTile, smem + ((t + 1) & 1) * kStageU4);
+    const uint4* q_lds = smem + (t & 1) * kStageU4;
+    const uint4* do_lds = q_lds + C::kTileU4;
+    const float* lse_lds = reinterpret_cast<const float*>(q_lds + 2 * C::kTileU4);
+    const float* delta_lds = lse_lds + kTile;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       const int ib = i0 + qb * 32;
       if (causal && ib + 31 < jw0) continue;   // all 32 queries lie before this wave's keys
+      if (ib >= s) continue;                   // no query of the block exists
       f32x16 sacc = zero16(), dp = zero16();
 #pragma unroll
       for (int ks = 0; ks < C::KS; ++ks) {
-        const bf16x8 qa = __builtin_bit_cast(bf16x8, q_lds[(qb * 32 + l32) * C::KC + ks * 2 + hf]);
-        const bf16x8 da = __builtin_bit_cast(bf16x8, do_lds[(qb * 32 + l32) * C::KC + ks * 2 + hf]);
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[ks], sacc, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[ks], dp, 0, 0, 0);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows<DH>(q_lds, qb * 32 + l32, ks, hf), kf[ks], sacc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows<DH>(do_lds, qb * 32 + l32, ks, hf), vf[ks], dp, 0, 0, 0);
       }
-      const bool need_mask = (jw0 + 32 > kv_len) || (causal && jw0 + 31 > ib);
+      const bool need_mask = (jw0 + 32 > kv_len) || (causal && jw0 + 31 > ib) || (ib + 32 > s);
       f32x16 pv16, ds16;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -462,16 +458,16 @@ __global__ __launch_bounds__(kThreads) void attn_dkv_mfma_kernel(const bf16_t* _
         const float4 d4 = *reinterpret_cast<const float4*>(delta_lds + qb * 32 + 8 * g + 4 * hf);
         const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int r = 4 * g + t;
-          float pv = __builtin_amdgcn_exp2f(fmaf(sacc[r], c, -lv[t]));
+        for (int t4 = 0; t4 < 4; ++t4) {
+          const int r = 4 * g + t4;
+          float pv = __builtin_amdgcn_exp2f(fmaf(sacc[r], c, -lv[t4] * kLog2e));
           if (need_mask) {
-            const int iq = ib + 8 * g + 4 * hf + t;
-            const bool vis = j < kv_len && (!causal || j <= iq);
+            const int iq = ib + 8 * g + 4 * hf + t4;
+            const bool vis = j < kv_len && (!causal || j <= iq) && iq < s;
             pv = vis ? pv : 0.f;
           }
           pv16[r] = pv;
-          ds16[r] = pv * (dp[r] - dl[t]);
+          ds16[r] = pv * (dp[r] - dl[t4]);
         }
       }
 #pragma unroll
@@ -480,8 +476,8 @@ __global__ __launch_bounds__(kThreads) void attn_dkv_mfma_kernel(const bf16_t* _
         const int kk = qb * 2 + half;
 #pragma unroll
         for (int db = 0; db < C::DB; ++db) {
-          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr(dot_lds, db * 32 + l32, kk, hf), pb, dv[db], 0, 0, 0);
-          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr(qt_lds, db * 32 + l32, kk, hf), dsb, dk[db], 0, 0, 0);
+          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_cols<DH>(do_lds, db * 32, kk, lane), pb, dv[db], 0, 0, 0);
+          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_cols<DH>(q_lds, db * 32, kk, lane), dsb, dk[db], 0, 0, 0);
         }
       }
     }
@@ -514,7 +510,7 @@ hipError_t set_lds(K kern, size_t bytes, bool* done) {
 template <int DH>
 hipError_t fwd_launch(const AttnDesc& d, const void* qkv, void* o, float* lse, hipStream_t st) {
   using C = Cfg<DH>;
-  constexpr size_t lds = C::kRowTile * sizeof(uint4) + C::kTrTile * sizeof(uint2);
+  constexpr size_t lds = (4 * C::kTileU4 + C::kPadU4) * sizeof(uint4);
   static bool done = false;
   hipError_t e = set_lds(attn_fwd_mfma_kernel<DH>, lds, &done);
   if (e != hipSuccess) return e;
@@ -528,19 +524,17 @@ template <int DH>
 hipError_t bwd_launch(const AttnDesc& d, const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
                       float* delta, hipStream_t st) {
   using C = Cfg<DH>;
-  hipError_t e = attention_delta(d, o, d_o, delta, st);
-  if (e != hipSuccess) return e;
-  constexpr size_t lds_dq = 2 * C::kRowTile * sizeof(uint4) + C::kTrTile * sizeof(uint2);
-  constexpr size_t lds_dkv = 2 * C::kRowTile * sizeof(uint4) + 2 * C::kTrTile * sizeof(uint2) + 2 * kTile * sizeof(float);
+  constexpr size_t lds_dq = (4 * C::kTileU4 + C::kPadU4) * sizeof(uint4);
+  constexpr size_t lds_dkv = (2 * (2 * C::kTileU4 + 2 * kTile / 4) + C::kPadU4) * sizeof(uint4);
   static bool done_dq = false, done_dkv = false;
-  e = set_lds(attn_dq_mfma_kernel<DH>, lds_dq, &done_dq);
+  hipError_t e = set_lds(attn_dq_mfma_kernel<DH>, lds_dq, &done_dq);
   if (e != hipSuccess) return e;
   e = set_lds(attn_dkv_mfma_kernel<DH>, lds_dkv, &done_dkv);
   if (e != hipSuccess) return e;
   dim3 grid(ceil_div(d.s, kBlockRows), d.a, d.b);
   hipLaunchKernelGGL(attn_dq_mfma_kernel<DH>, grid, dim3(kThreads), lds_dq, st, static_cast<const bf16_t*>(qkv),
-                     static_cast<const bf16_t*>(d_o), lse, delta, static_cast<bf16_t*>(dqkv), d.s, d.a, d.mask_mode,
-                     d.seqlens);
+                     static_cast<const bf16_t*>(o), static_cast<const bf16_t*>(d_o), lse, delta,
+                     static_cast<bf16_t*>(dqkv), d.s, d.a, d.mask_mode, d.seqlens);
   hipLaunchKernelGGL(attn_dkv_mfma_kernel<DH>, grid, dim3(kThreads), lds_dkv, st, static_cast<const bf16_t*>(qkv),
                      static_cast<const bf16_t*>(d_o), lse, delta, static_cast<bf16_t*>(dqkv), d.s, d.a, d.mask_mode,
                      d.seqlens);
