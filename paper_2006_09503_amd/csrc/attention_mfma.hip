@@ -52,6 +52,10 @@ struct Cfg {
   static constexpr int CH = DH / 8;                // 16-byte chunks per tile row
   static constexpr int kTileU4 = kTile * CH;       // uint4 per tile
   static constexpr int kPadU4 = 4;                 // transposing reads of the padded head columns run past a row
+  // Two waves per SIMD cap a lane at 256 registers; the compiler then keeps MFMA results in
+  // ordinary VGPRs.  With 512 available it parks them in the accumulator file and copies every
+  // score to a VGPR and back around the softmax arithmetic, which costs more than the MFMAs.
+  static constexpr int kMinWaves = DH <= 64 ? 2 : 1;
 };
 
 // Chunk swizzle per head size (rows are 64 / 128 / 160 / 256 bytes; the LDS has 64 banks of 4 bytes).
@@ -165,13 +169,13 @@ __device__ __forceinline__ uint2 pack4f(float a, float b, float c, float d) {
 // ------------------------------------------------------------------------------------------------
 // forward
 template <int DH>
-__global__ __launch_bounds__(kThreads) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
+__global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
                                                                   float* __restrict__ lse, int s, int a, int mask_mode,
                                                                   const int32_t* __restrict__ seqlens) {
   using C = Cfg<DH>;
   extern __shared__ uint4 smem[];   // stage st: K tile at st * 2 * kTileU4, V tile behind it
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l32 = lane & 31, hf = lane >> 5;
   const int n = blockIdx.z, head = blockIdx.y, i0 = blockIdx.x * kBlockRows;
   const int h = a * DH;
   const int64_t ld = 3 * (int64_t)h;
@@ -217,18 +221,21 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_mfma_kernel(const bf16_t* _
     }
     // masks (only tiles that touch a boundary need them) and the running maximum
     const bool need_mask = (j0 + kTile > kv_len) || (causal && j0 + kTile - 1 > iw0);
-    float mloc = -INFINITY;
+    if (need_mask) {
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+      for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if (need_mask) {
+        for (int r = 0; r < 16; ++r) {
           const int key = j0 + nb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
           const bool vis = key < kv_len && (!causal || key <= i);
           sacc[nb][r] = vis ? sacc[nb][r] : -INFINITY;
         }
-        mloc = fmaxf(mloc, sacc[nb][r]);
-      }
+    }
+    float mloc = -INFINITY;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, sacc[nb][r]);
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
     const float m_new = fmaxf(m_i, mloc);
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;   // row with nothing visible yet
@@ -278,14 +285,14 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_mfma_kernel(const bf16_t* _
 // ------------------------------------------------------------------------------------------------
 // dQ (and delta = rowsum(dO * O), which the dK/dV kernel reads afterwards)
 template <int DH>
-__global__ __launch_bounds__(kThreads) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
+__global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
                                                                  const bf16_t* __restrict__ d_o, const float* __restrict__ lse,
                                                                  float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s,
                                                                  int a, int mask_mode, const int32_t* __restrict__ seqlens) {
   using C = Cfg<DH>;
   extern __shared__ uint4 smem[];   // stage st: K tile at st * 2 * kTileU4, V tile behind it
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l32 = lane & 31, hf = lane >> 5;
   const int n = blockIdx.z, head = blockIdx.y, i0 = blockIdx.x * kBlockRows;
   const int h = a * DH;
   const int64_t ld = 3 * (int64_t)h;
@@ -348,16 +355,21 @@ __global__ __launch_bounds__(kThreads) void attn_dq_mfma_kernel(const bf16_t* __
       }
     }
     const bool need_mask = (j0 + kTile > kv_len) || (causal && j0 + kTile - 1 > iw0);
+    if (need_mask) {   // a masked score of -inf gives probability exactly 0
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = j0 + nb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+          const bool vis = key < kv_len && (!causal || key <= i);
+          sacc[nb][r] = vis ? sacc[nb][r] : -INFINITY;
+        }
+    }
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float pv = __builtin_amdgcn_exp2f(fmaf(sacc[nb][r], c, -lse_i));
-        if (need_mask) {
-          const int key = j0 + nb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-          const bool vis = key < kv_len && (!causal || key <= i);
-          pv = vis ? pv : 0.f;
-        }
+        const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[nb][r], c, -lse_i));
         sacc[nb][r] = pv * (dp[nb][r] - delta_i);   // dS^T (the 1/sqrt(dh) factor is applied at the end)
       }
     bf16x8 dsb[4];
@@ -385,7 +397,7 @@ __global__ __launch_bounds__(kThreads) void attn_dq_mfma_kernel(const bf16_t* __
 // ------------------------------------------------------------------------------------------------
 // dK, dV
 template <int DH>
-__global__ __launch_bounds__(kThreads) void attn_dkv_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
+__global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dkv_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
                                                                   const float* __restrict__ lse, const float* __restrict__ delta,
                                                                   bf16_t* __restrict__ dqkv, int s, int a, int mask_mode,
                                                                   const int32_t* __restrict__ seqlens) {
@@ -394,7 +406,7 @@ __global__ __launch_bounds__(kThreads) void attn_dkv_mfma_kernel(const bf16_t* _
   // stage st: Q tile, dO tile, 64 lse, 64 delta
   constexpr int kStageU4 = 2 * C::kTileU4 + 2 * kTile / 4;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l32 = lane & 31, hf = lane >> 5;
   const int n = blockIdx.z, head = blockIdx.y, j0 = blockIdx.x * kBlockRows;
   const int h = a * DH;
   const int64_t ld = 3 * (int64_t)h;
@@ -451,6 +463,14 @@ __global__ __launch_bounds__(kThreads) void attn_dkv_mfma_kernel(const bf16_t* _
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows<DH>(do_lds, qb * 32 + l32, ks, hf), vf[ks], dp, 0, 0, 0);
       }
       const bool need_mask = (jw0 + 32 > kv_len) || (causal && jw0 + 31 > ib) || (ib + 32 > s);
+      if (need_mask) {   // a masked score of -inf gives probability exactly 0
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int iq = ib + 8 * (r >> 2) + 4 * hf + (r & 3);
+          const bool vis = j < kv_len && (!causal || j <= iq) && iq < s;
+          sacc[r] = vis ? sacc[r] : -INFINITY;
+        }
+      }
       f32x16 pv16, ds16;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -460,12 +480,7 @@ __global__ __launch_bounds__(kThreads) void attn_dkv_mfma_kernel(const bf16_t* _
 #pragma unroll
         for (int t4 = 0; t4 < 4; ++t4) {
           const int r = 4 * g + t4;
-          float pv = __builtin_amdgcn_exp2f(fmaf(sacc[r], c, -lv[t4] * kLog2e));
-          if (need_mask) {
-            const int iq = ib + 8 * g + 4 * hf + t4;
-            const bool vis = j < kv_len && (!causal || j <= iq) && iq < s;
-            pv = vis ? pv : 0.f;
-          }
+          const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[r], c, -lv[t4] * kLog2e));
           pv16[r] = pv;
           ds16[r] = pv * (dp[r] - dl[t4]);
         }
