@@ -52,7 +52,7 @@ void gemm_kernel_name(const GemmDesc* d, int count, char* out, size_t cap) {
 }
 
 hipError_t gemm_grouped(const GemmDesc* d, int count, hipStream_t stream) {
-  if (!d || count < 1 || count > 4) return hipErrorInvalidValue;
+  if (!d || count < 1 || count > kGemmMaxGroup) return hipErrorInvalidValue;
   for (int g = 0; g < count; ++g) {
     hipError_t e = check_gemm(d[g]);
     if (e != hipSuccess) return e;

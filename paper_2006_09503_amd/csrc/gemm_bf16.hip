@@ -31,7 +31,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kMaxGroup = 4;   // GEMMs of one form that may share a launch
+constexpr int kMaxGroup = kGemmMaxGroup;   // GEMMs of one form that may share a launch
 
 struct BfParams {
   const bf16_t* A; const bf16_t* B; void* C;

@@ -15,6 +15,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <algorithm>
 #include <vector>
 
 #include "../../include/stage2bw.h"
@@ -74,7 +75,11 @@ struct stage2bw {
   std::vector<int32_t*> slot_lens; // per slot: key lengths (padding mask)
 
   // backward workspace
-  char *tmp_h = nullptr, *dx1 = nullptr, *dchain[2] = {nullptr, nullptr}, *du = nullptr, *dqkv = nullptr;
+  // tmp_h is transient; the gradients that the weight-gradient products read (dx1, du, dqkv and
+  // each layer's input gradient dchain) exist once per layer, because those products run after
+  // the data-gradient chain of the whole stage
+  char* tmp_h = nullptr;
+  std::vector<char*> dx1, dchain, du, dqkv;
   char* y_scratch = nullptr;  // recompute: output of the re-run forward
   float *delta = nullptr, *ln_partial = nullptr, *ln_partial2 = nullptr, *cs_partial = nullptr;
 
@@ -296,25 +301,38 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
   const bool acc = !first;
   const double attn_flops = 10.0 * c.microbatch * (double)c.seq * c.seq * h;
   const void* dy = dy_in;
+  // The four weight-gradient products of a layer are independent of the data-gradient chain
+  // once their operands exist, and each is small for 256 CUs (a layer's four give 192 tiles of
+  // 256 x 256 at the BERT-Large shape): they are collected over the layers and issued in grouped
+  // launches of up to kGemmMaxGroup products after the chain, where several rounds of tiles keep
+  // every CU busy.  The chain's result dX is enqueued before them.
+  std::vector<GemmDesc> wg;
+  wg.reserve(4 * c.n_layers);
+  auto flush_wgrad = [&]() -> hipError_t {
+    for (size_t i0 = 0; i0 < wg.size(); i0 += kGemmMaxGroup) {
+      const int n = (int)std::min<size_t>(kGemmMaxGroup, wg.size() - i0);
+      double flops = 0.0;
+      for (int i = 0; i < n; ++i) flops += 2.0 * wg[i0 + i].M * (double)wg[i0 + i].N * wg[i0 + i].K;
+      char wg_name[96] = "";
+      if (st->timing) gemm_kernel_name(&wg[i0], n, wg_name, sizeof(wg_name));
+      hipError_t e = timed(st, STAGE_K_GEMM_WGRAD, wg_name, flops, 0.0, [&] { return gemm_grouped(&wg[i0], n, st->stream); });
+      if (e != hipSuccess) return e;
+    }
+    wg.clear();
+    return hipSuccess;
+  };
   for (int l = c.n_layers - 1; l >= 0; --l) {
     const LayerOff& o = st->off[l];
     LayerActs& A = acts.layer[l];
-    void* dx = (l == 0) ? dx_out : static_cast<void*>(st->dchain[l & 1]);
+    void* dx = (l == 0) ? dx_out : static_cast<void*>(st->dchain[l]);
+    char *du = st->du[l], *dx1 = st->dx1[l], *dqkv = st->dqkv[l];
     hipError_t e;
-    GemmDesc g;
-    // The four weight-gradient products of a layer are independent of the data-gradient chain
-    // once their operands exist, and each is small for 256 CUs: they are collected and issued as
-    // one grouped launch at the end of the layer (all operands are still intact then).
-    GemmDesc wg[4];
-    int n_wg = 0;
-    double wg_flops = 0.0;
     auto wgrad = [&](const void* act, int M, const void* grad, int N, float* out) {
-      GemmDesc& w = wg[n_wg++];
-      w = GemmDesc();
+      wg.emplace_back();
+      GemmDesc& w = wg.back();
       w.dtype = st->dtype;
       w.A = act; w.lda = M; w.trans_a = true; w.B = grad; w.ldb = N; w.C = out; w.ldc = N;
       w.M = M; w.N = N; w.K = T; w.epilogue = kEpiAccum; w.accumulate = acc;
-      wg_flops += 2.0 * M * N * T;
       return hipSuccess;
     };
     auto dgrad = [&](const void* grad, int N, const char* w_, int K, void* out, const void* u) {
@@ -328,35 +346,31 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     };
     // y = x1 + GELU(u) W2 + b2
     e = wgrad(A.g, f, dy, h, st->G + o.w2);                              if (e != hipSuccess) return e;
-    e = dgrad(dy, h, wptr(st, buf, o.w2), f, st->du, A.u);               if (e != hipSuccess) return e;
+    e = dgrad(dy, h, wptr(st, buf, o.w2), f, du, A.u);                   if (e != hipSuccess) return e;
     // u = c W1 + b1
-    e = wgrad(A.c, h, st->du, f, st->G + o.w1);                          if (e != hipSuccess) return e;
-    e = dgrad(st->du, f, wptr(st, buf, o.w1), h, st->tmp_h, nullptr);    if (e != hipSuccess) return e;
+    e = wgrad(A.c, h, du, f, st->G + o.w1);                              if (e != hipSuccess) return e;
+    e = dgrad(du, f, wptr(st, buf, o.w1), h, st->tmp_h, nullptr);        if (e != hipSuccess) return e;
     // c = LN2(x1); dx1 = dy + LN2'(dc)
     int ln2_parts = 0, ln1_parts = 0;
-    e = run_ln_bwd(st, st->tmp_h, A.x1, A.mean2, A.rstd2, wptr(st, buf, o.ln2_g), dy, st->dx1, st->ln_partial, &ln2_parts);
+    e = run_ln_bwd(st, st->tmp_h, A.x1, A.mean2, A.rstd2, wptr(st, buf, o.ln2_g), dy, dx1, st->ln_partial, &ln2_parts);
     if (e != hipSuccess) return e;
     // x1 = x + o Wo + bo
-    e = wgrad(A.o, h, st->dx1, h, st->G + o.wo);                         if (e != hipSuccess) return e;
-    e = dgrad(st->dx1, h, wptr(st, buf, o.wo), h, st->tmp_h, nullptr);   if (e != hipSuccess) return e;
+    e = wgrad(A.o, h, dx1, h, st->G + o.wo);                             if (e != hipSuccess) return e;
+    e = dgrad(dx1, h, wptr(st, buf, o.wo), h, st->tmp_h, nullptr);       if (e != hipSuccess) return e;
     // attention
-    e = timed(st, STAGE_K_ATTN_BWD, "attention backward (delta + dq + dkv kernels)", attn_flops, 0.0, [&] {
-      return attention_bwd(attn_desc(st, lens), A.qkv, A.o, A.lse, st->tmp_h, st->dqkv, st->delta, st->stream);
+    e = timed(st, STAGE_K_ATTN_BWD, "attention backward (dq + dkv kernels)", attn_flops, 0.0, [&] {
+      return attention_bwd(attn_desc(st, lens), A.qkv, A.o, A.lse, st->tmp_h, dqkv, st->delta, st->stream);
     });
     if (e != hipSuccess) return e;
     // qkv = a Wqkv + bqkv
-    e = wgrad(A.a, h, st->dqkv, 3 * h, st->G + o.wqkv);                  if (e != hipSuccess) return e;
-    e = dgrad(st->dqkv, 3 * h, wptr(st, buf, o.wqkv), h, st->tmp_h, nullptr);  if (e != hipSuccess) return e;
+    e = wgrad(A.a, h, dqkv, 3 * h, st->G + o.wqkv);                      if (e != hipSuccess) return e;
+    e = dgrad(dqkv, 3 * h, wptr(st, buf, o.wqkv), h, st->tmp_h, nullptr);  if (e != hipSuccess) return e;
     // a = LN1(x); dx = dx1 + LN1'(da)
-    e = run_ln_bwd(st, st->tmp_h, A.x, A.mean1, A.rstd1, wptr(st, buf, o.ln1_g), st->dx1, dx, st->ln_partial2, &ln1_parts);
-    if (e != hipSuccess) return e;
-    char wg_name[96] = "";
-    if (st->timing) gemm_kernel_name(wg, n_wg, wg_name, sizeof(wg_name));
-    e = timed(st, STAGE_K_GEMM_WGRAD, wg_name, wg_flops, 0.0, [&] { return gemm_grouped(wg, n_wg, st->stream); });
+    e = run_ln_bwd(st, st->tmp_h, A.x, A.mean1, A.rstd1, wptr(st, buf, o.ln1_g), dx1, dx, st->ln_partial2, &ln1_parts);
     if (e != hipSuccess) return e;
     // bias gradients (column sums of the four projection-output gradients) and the reduction of
     // every partial of the layer: two launches
-    const ColsumItem cs[4] = {{dy, h, h}, {st->du, f, f}, {st->dx1, h, h}, {st->dqkv, 3 * h, 3 * h}};
+    const ColsumItem cs[4] = {{dy, h, h}, {du, f, f}, {dx1, h, h}, {dqkv, 3 * h, 3 * h}};
     int cs_parts = 0, cs_cols = 0;
     e = timed(st, STAGE_K_BIAS_GRAD, "colsum_partial_grouped_kernel", 0.0, (double)T * (5.0 * h + f) * st->esize, [&] {
       return colsum_partial_grouped(cs, 4, T, st->cs_partial, &cs_parts, &cs_cols, st->dtype, st->stream);
@@ -374,9 +388,8 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     });
     if (e != hipSuccess) return e;
     dy = dx;
-    (void)g;
   }
-  return hipSuccess;
+  return flush_wgrad();
 }
 
 int free_all(stage2bw* st) {
@@ -456,11 +469,16 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
     if (cfg->recompute) ALLOC(st->slot_x0[i], T * h * E, &st->bytes_stash);
   }
   ALLOC(st->tmp_h, T * h * E, nullptr);
-  ALLOC(st->dx1, T * h * E, nullptr);
-  ALLOC(st->dchain[0], T * h * E, nullptr);
-  ALLOC(st->dchain[1], T * h * E, nullptr);
-  ALLOC(st->du, T * f * E, nullptr);
-  ALLOC(st->dqkv, T * 3 * h * E, nullptr);
+  st->dx1.assign(cfg->n_layers, nullptr);
+  st->dchain.assign(cfg->n_layers, nullptr);
+  st->du.assign(cfg->n_layers, nullptr);
+  st->dqkv.assign(cfg->n_layers, nullptr);
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    ALLOC(st->dx1[l], T * h * E, nullptr);
+    if (l > 0) ALLOC(st->dchain[l], T * h * E, nullptr);
+    ALLOC(st->du[l], T * f * E, nullptr);
+    ALLOC(st->dqkv[l], T * 3 * h * E, nullptr);
+  }
   if (cfg->recompute) ALLOC(st->y_scratch, T * h * E, nullptr);
   ALLOC(st->delta, (int64_t)cfg->microbatch * cfg->n_heads * cfg->seq * 4, nullptr);
   ALLOC(st->ln_partial, (int64_t)ln_bwd_max_parts() * 2 * h * 4, nullptr);
