@@ -115,52 +115,70 @@ __global__ __launch_bounds__(kWg) void ln_bwd_kernel(const T* __restrict__ dy, c
 #pragma unroll
     for (int i = 0; i < 8; ++i) { gsum[c][i] = 0.f; bsum[c][i] = 0.f; if (col >= h) gn[c][i] = 0.f; }
   }
+  // Two row groups per trip, all loads of both issued before any arithmetic: the kernel is bound
+  // by memory latency, not bandwidth, at the sizes a stage gives it.
+  constexpr int U = CPT <= 2 ? 2 : 1;   // (longer rows already keep enough loads in flight, and registers are short)
   const int n_groups = (rows + ROWS - 1) / ROWS;
-  for (int grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
-    const int row = grp * ROWS + rsub;
-    const bool row_ok = row < rows;
-    const float mean = row_ok ? mean_in[row] : 0.f;
-    const float rstd = row_ok ? rstd_in[row] : 0.f;
-    float xh[CPT][8], dxh[CPT][8];
-    float s1 = 0.f, s2 = 0.f;
+  for (int grp0 = blockIdx.x; grp0 < n_groups; grp0 += U * gridDim.x) {
+    int row[U];
+    bool row_ok[U];
+    float mean[U], rstd[U];
+    float xh[U][CPT][8], dxh[U][CPT][8], res[U][CPT][8];
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-      const int col = (sub + c * R) * 8;
-      if (row_ok && col < h) {
-        float xv[8], dv[8];
-        load8(x + (int64_t)row * h + col, xv);
-        load8(dy + (int64_t)row * h + col, dv);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          xh[c][i] = (xv[i] - mean) * rstd;
-          dxh[c][i] = dv[i] * gn[c][i];
-          s1 += dxh[c][i];
-          s2 += dxh[c][i] * xh[c][i];
-          gsum[c][i] += dv[i] * xh[c][i];
-          bsum[c][i] += dv[i];
-        }
-      } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) { xh[c][i] = 0.f; dxh[c][i] = 0.f; }
-      }
-    }
-    const float c1 = group_sum<R>(s1, red, tid) / (float)h;
-    const float c2 = group_sum<R>(s2, red, tid) / (float)h;
-    if (row_ok) {
+    for (int u = 0; u < U; ++u) {
+      const int grp = grp0 + u * gridDim.x;
+      row[u] = grp * ROWS + rsub;
+      row_ok[u] = grp < n_groups && row[u] < rows;
+      mean[u] = row_ok[u] ? mean_in[row[u]] : 0.f;
+      rstd[u] = row_ok[u] ? rstd_in[row[u]] : 0.f;
 #pragma unroll
       for (int c = 0; c < CPT; ++c) {
         const int col = (sub + c * R) * 8;
-        if (col < h) {
-          float o[8];
+        if (row_ok[u] && col < h) {
+          load8(x + (int64_t)row[u] * h + col, xh[u][c]);
+          load8(dy + (int64_t)row[u] * h + col, dxh[u][c]);
+          if (dres) load8(dres + (int64_t)row[u] * h + col, res[u][c]);
+        } else {
 #pragma unroll
-          for (int i = 0; i < 8; ++i) o[i] = rstd * (dxh[c][i] - c1 - xh[c][i] * c2);
-          if (dres) {
-            float r[8];
-            load8(dres + (int64_t)row * h + col, r);
+          for (int i = 0; i < 8; ++i) { xh[u][c][i] = 0.f; dxh[u][c][i] = 0.f; }
+        }
+      }
+    }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) o[i] += r[i];
+    for (int u = 0; u < U; ++u) {
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int col = (sub + c * R) * 8;
+        if (row_ok[u] && col < h) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const float dv = dxh[u][c][i];
+            xh[u][c][i] = (xh[u][c][i] - mean[u]) * rstd[u];
+            dxh[u][c][i] = dv * gn[c][i];
+            s1 += dxh[u][c][i];
+            s2 += dxh[u][c][i] * xh[u][c][i];
+            gsum[c][i] += dv * xh[u][c][i];
+            bsum[c][i] += dv;
           }
-          store8(dx + (int64_t)row * h + col, o);
+        }
+      }
+      const float c1 = group_sum<R>(s1, red, tid) / (float)h;
+      const float c2 = group_sum<R>(s2, red, tid) / (float)h;
+      if (row_ok[u]) {
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+          const int col = (sub + c * R) * 8;
+          if (col < h) {
+            float o[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] = rstd[u] * (dxh[u][c][i] - c1 - xh[u][c][i] * c2);
+            if (dres) {
+#pragma unroll
+              for (int i = 0; i < 8; ++i) o[i] += res[u][c][i];
+            }
+            store8(dx + (int64_t)row[u] * h + col, o);
+          }
         }
       }
     }

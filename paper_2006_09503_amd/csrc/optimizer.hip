@@ -7,18 +7,34 @@
 namespace k2bw {
 namespace {
 
+// One workgroup per 512 consecutive float4 (two per thread), no grid-stride loop: measured on
+// MI355X, a grid that simply walks memory front to back sustains 5.4 TB/s on this 16-byte-read /
+// 14-byte-write mix, against 4.4..4.7 TB/s for a capped grid with a strided loop (non-temporal
+// hints, deeper unrolling and workgroup-contiguous ranges made no difference).
+constexpr int kAdamPerThread = 2;
 template <bool LP>
 __global__ __launch_bounds__(256) void adam_kernel(AdamDesc d) {
   const int64_t n4 = d.n / 4;
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t base = (int64_t)blockIdx.x * (256 * kAdamPerThread) + threadIdx.x;
   const float omb1 = d.omb1, omb2 = d.omb2;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-    const float4 w = reinterpret_cast<const float4*>(d.w_cur)[i];
-    float4 m = reinterpret_cast<const float4*>(d.m)[i];
-    float4 v = reinterpret_cast<const float4*>(d.v)[i];
-    const float4 gs = reinterpret_cast<const float4*>(d.G)[i];
-    float wv[4] = {w.x, w.y, w.z, w.w}, mv[4] = {m.x, m.y, m.z, m.w}, vv[4] = {v.x, v.y, v.z, v.w};
-    const float gv[4] = {gs.x, gs.y, gs.z, gs.w};
+  float4 w[kAdamPerThread], m[kAdamPerThread], v[kAdamPerThread], gs[kAdamPerThread];
+#pragma unroll
+  for (int u = 0; u < kAdamPerThread; ++u) {
+    const int64_t i = base + u * 256;
+    if (i < n4) {
+      w[u] = reinterpret_cast<const float4*>(d.w_cur)[i];
+      m[u] = reinterpret_cast<const float4*>(d.m)[i];
+      v[u] = reinterpret_cast<const float4*>(d.v)[i];
+      gs[u] = reinterpret_cast<const float4*>(d.G)[i];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kAdamPerThread; ++u) {
+    const int64_t i = base + u * 256;
+    if (i >= n4) continue;
+    float wv[4] = {w[u].x, w[u].y, w[u].z, w[u].w}, mv[4] = {m[u].x, m[u].y, m[u].z, m[u].w};
+    float vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+    const float gv[4] = {gs[u].x, gs[u].y, gs[u].z, gs[u].w};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const float g = gv[k] * d.inv_m;
@@ -54,8 +70,8 @@ __global__ __launch_bounds__(256) void bf16_to_f32_kernel(const bf16_t* __restri
 }
 
 __global__ __launch_bounds__(256) void copy16_kernel(const uint4* __restrict__ in, uint4* __restrict__ out, int64_t n16) {
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) out[i] = in[i];
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;   // one element per thread (see adam_kernel)
+  if (i < n16) out[i] = in[i];
 }
 
 int stream_grid(int64_t items) {
@@ -77,7 +93,9 @@ hipError_t adam_step(const AdamDesc& d_in, hipStream_t stream) {
   if (!aligned16(d.w_cur) || !aligned16(d.w_next) || !aligned16(d.m) || !aligned16(d.v) || !aligned16(d.G) ||
       (reinterpret_cast<uintptr_t>(d.w_next_lp) & 7))
     return hipErrorInvalidValue;
-  const int grid = stream_grid(d.n / 4);
+  const int64_t blocks = (d.n / 4 + 256 * kAdamPerThread - 1) / (256 * kAdamPerThread);
+  if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+  const int grid = (int)blocks;
   if (d.w_next_lp)
     hipLaunchKernelGGL(adam_kernel<true>, dim3(grid), dim3(256), 0, stream, d);
   else
@@ -101,7 +119,8 @@ hipError_t convert_bf16_to_f32(const bf16_t* in, float* out, int64_t n, hipStrea
 
 hipError_t copy_bytes(const void* in, void* out, int64_t bytes, hipStream_t stream) {
   if (bytes <= 0 || bytes % 16 || !in || !out || !aligned16(in) || !aligned16(out)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(copy16_kernel, dim3(stream_grid(bytes / 16)), dim3(256), 0, stream,
+  if ((bytes / 16 + 255) / 256 > 0x7fffffff) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)((bytes / 16 + 255) / 256)), dim3(256), 0, stream,
                      static_cast<const uint4*>(in), static_cast<uint4*>(out), bytes / 16);
   return hipGetLastError();
 }
