@@ -38,6 +38,15 @@ int k2bw_gemm(int dtype, int trans_a, int trans_b, int epilogue, int M, int N, i
               int lda, const void* B, int ldb, void* C, int ldc, const void* bias, const void* aux,
               void* aux_out, int accumulate, void* stream);
 
+/* The FC2 data gradient with the GELU derivative and the FC1 bias gradient in one pass (bf16):
+ * du[M,N] = (dy[M,K] w[N,K]^T) * GELU'(u[M,N]);  dbias[N] (fp32) = (accumulate ? dbias : 0) +
+ * sum over rows of du, summed from the fp32 values before du is rounded to bf16.
+ * workspace: k2bw_gemm_dgrad_gelu_bias_workspace(M, N) floats. */
+int64_t k2bw_gemm_dgrad_gelu_bias_workspace(int M, int N);
+int k2bw_gemm_dgrad_gelu_bias(int M, int N, int K, const void* dy, int lda, const void* w, int ldb,
+                              void* du, int ldc, const void* u, float* dbias, int accumulate,
+                              float* workspace, void* stream);
+
 /* y = gain*(x-mean)*rstd + shift per row of length h (biased variance, eps under the root);
  * mean, rstd: fp32 [rows]. */
 int k2bw_layernorm_fwd(int dtype, int rows, int h, float eps, const void* x, const void* gain,
@@ -45,11 +54,13 @@ int k2bw_layernorm_fwd(int dtype, int rows, int h, float eps, const void* x, con
 
 /* Floats of workspace k2bw_layernorm_bwd needs for row length h. */
 int64_t k2bw_layernorm_bwd_workspace(int h);
-/* dx = (dres ? dres : 0) + LN'(dy); dgain_dshift: fp32 [2h] = (sum_r dy*xhat | sum_r dy),
- * overwritten or added to according to accumulate. */
+/* dx = (dres ? dres : 0) + LN'(dy); dgain_dshift: fp32 [2h] = (sum_r dy*xhat | sum_r dy);
+ * dx_colsum: fp32 [h] = sum_r dx (the bias gradient of the projection whose output gradient dx
+ * is), may be NULL.  Both are overwritten or added to according to accumulate. */
 int k2bw_layernorm_bwd(int dtype, int rows, int h, const void* dy, const void* x, const float* mean,
                        const float* rstd, const void* gain, const void* dres, void* dx,
-                       float* dgain_dshift, int accumulate, float* workspace, void* stream);
+                       float* dgain_dshift, float* dx_colsum, int accumulate, float* workspace,
+                       void* stream);
 
 /* Floats of workspace k2bw_bias_grad needs for n columns. */
 int64_t k2bw_bias_grad_workspace(int n);

@@ -73,8 +73,10 @@ def lib() -> C.CDLL:
             "stage_sched_destroy": (C.c_int, [vp]),
             "k2bw_gemm": (C.c_int, [C.c_int] * 7 + [vp, C.c_int, vp, C.c_int, vp, C.c_int, vp, vp, vp, C.c_int, vp]),
             "k2bw_layernorm_fwd": (C.c_int, [C.c_int, C.c_int, C.c_int, f32, vp, vp, vp, vp, vp, vp, vp]),
+            "k2bw_gemm_dgrad_gelu_bias_workspace": (i64, [C.c_int, C.c_int]),
+            "k2bw_gemm_dgrad_gelu_bias": (C.c_int, [C.c_int, C.c_int, C.c_int, vp, C.c_int, vp, C.c_int, vp, C.c_int, vp, vp, C.c_int, vp, vp]),
             "k2bw_layernorm_bwd_workspace": (i64, [C.c_int]),
-            "k2bw_layernorm_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, vp]),
+            "k2bw_layernorm_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, vp]),
             "k2bw_bias_grad_workspace": (i64, [C.c_int]),
             "k2bw_bias_grad": (C.c_int, [C.c_int, C.c_int, C.c_int, vp, vp, C.c_int, vp, vp]),
             "k2bw_attention_fwd": (C.c_int, [C.c_int] * 6 + [vp, vp, vp, vp, vp]),

@@ -31,6 +31,8 @@ hipError_t check_gemm(const GemmDesc& d) {
   if (d.epilogue == kEpiGelu && (!d.bias || !d.aux_out)) return hipErrorInvalidValue;
   if (d.epilogue == kEpiGeluGrad && !d.aux) return hipErrorInvalidValue;
   if (d.epilogue < kEpiStore || d.epilogue > kEpiAccum) return hipErrorInvalidValue;
+  if (d.colsum_partial && (d.dtype != kBF16 || d.epilogue != kEpiGeluGrad || !aligned16(d.colsum_partial)))
+    return hipErrorInvalidValue;
   if (d.dtype == kF32) return hipSuccess;
   if (d.dtype != kBF16) return hipErrorInvalidValue;
   // 16-byte vector accesses along the contiguous dimensions

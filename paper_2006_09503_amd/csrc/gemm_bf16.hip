@@ -37,6 +37,7 @@ struct BfParams {
   const bf16_t* A; const bf16_t* B; void* C;
   int M, N, K, lda, ldb, ldc;
   const bf16_t* bias; const bf16_t* aux; bf16_t* aux_out;
+  float* colsum;   // GELU' epilogue: partial[ceil(M/32)][N] column sums of the result, or null
   int accumulate;
   int tiles_m, tiles_n;
 };
@@ -313,6 +314,7 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[MI][NI], const BfPa
         }
       }
     } else {
+      float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int it = 0; it < WN / 16; ++it) {
         const int L = it * 64 + lane;
@@ -349,7 +351,22 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[MI][NI], const BfPa
 #pragma unroll
             for (int j = 0; j < 8; ++j) v[j] *= gelu_grad_fast(u[j]);
             *reinterpret_cast<uint4*>(out) = pack8(v);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) cs[j] += v[j];
           }
+        }
+      }
+      if (EPI == kEpiGeluGrad && p.colsum) {
+        // column sums of this 32-row strip: the lanes that share a column group are WN/8 apart
+#pragma unroll
+        for (int off = WN / 8; off < 64; off <<= 1)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) cs[j] += __shfl_xor(cs[j], off, 64);
+        const int col = col_base + lane * 8;
+        if (lane < WN / 8 && row_base < p.M && col < p.N) {
+          float* dst = p.colsum + (int64_t)(row_base >> 5) * p.N + col;
+          *reinterpret_cast<float4*>(dst) = make_float4(cs[0], cs[1], cs[2], cs[3]);
+          *reinterpret_cast<float4*>(dst + 4) = make_float4(cs[4], cs[5], cs[6], cs[7]);
         }
       }
     }
@@ -817,7 +834,8 @@ bool vector_ok(const GemmDesc& d) {
 BfParams to_params(const GemmDesc& d) {
   return BfParams{static_cast<const bf16_t*>(d.A), static_cast<const bf16_t*>(d.B), d.C,
                   d.M, d.N, d.K, d.lda, d.ldb, d.ldc, static_cast<const bf16_t*>(d.bias),
-                  static_cast<const bf16_t*>(d.aux), static_cast<bf16_t*>(d.aux_out), d.accumulate ? 1 : 0, 0, 0};
+                  static_cast<const bf16_t*>(d.aux), static_cast<bf16_t*>(d.aux_out),
+                  d.epilogue == kEpiGeluGrad ? d.colsum_partial : nullptr, d.accumulate ? 1 : 0, 0, 0};
 }
 
 }  // namespace

@@ -32,6 +32,10 @@ struct GemmDesc {
   const void* aux = nullptr;       // residual (kEpiStore) or pre-activation u (kEpiGeluGrad), ld = ldc
   void* aux_out = nullptr;         // GELU(u) (kEpiGelu), ld = ldc
   bool accumulate = false;         // kEpiAccum
+  // kEpiGeluGrad, bf16 only: if set, fp32 [ceil(M/32)][N] receives the column sums of every
+  // 32-row strip of the result (before rounding to bf16): the bias gradient of the projection
+  // whose output gradient C is, reduced afterwards with colsum_finalize
+  float* colsum_partial = nullptr;
   int dtype = kF32;
 };
 hipError_t gemm(const GemmDesc& d, hipStream_t stream);
@@ -48,9 +52,9 @@ hipError_t layernorm_fwd(const void* x, const void* gain, const void* shift, voi
                          float* mean, float* rstd, int rows, int h, float eps, int dtype,
                          hipStream_t stream);
 // dx = dres + rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)), dxhat = dy * gain;
-// dres may be null.  Column sums go to partial[parts][2h] (fp32; first h: sum_r dy*xhat, then sum_r dy);
+// dres may be null.  Column sums go to partial[parts][3h] (fp32: sum_r dy*xhat | sum_r dy | sum_r dx);
 // *parts_out receives the number of partial rows written.  partial must hold
-// 2 * ln_bwd_max_parts() * h floats.
+// 3 * ln_bwd_max_parts() * h floats.
 int ln_bwd_max_parts();
 hipError_t layernorm_bwd(const void* dy, const void* x, const float* mean, const float* rstd,
                          const void* gain, const void* dres, void* dx, float* partial,

@@ -30,6 +30,24 @@ int k2bw_gemm(int dtype, int trans_a, int trans_b, int epilogue, int M, int N, i
   return rc_of(gemm(d, static_cast<hipStream_t>(stream)));
 }
 
+int64_t k2bw_gemm_dgrad_gelu_bias_workspace(int M, int N) {
+  if (M <= 0 || N <= 0) return STAGE_ERR_INVALID_ARG;
+  return (int64_t)((M + 31) / 32) * N;
+}
+
+int k2bw_gemm_dgrad_gelu_bias(int M, int N, int K, const void* dy, int lda, const void* w, int ldb, void* du, int ldc,
+                              const void* u, float* dbias, int accumulate, float* workspace, void* stream) {
+  if (!dbias || !workspace) return STAGE_ERR_INVALID_ARG;
+  GemmDesc d;
+  d.dtype = kBF16; d.trans_b = true; d.epilogue = kEpiGeluGrad;
+  d.M = M; d.N = N; d.K = K; d.A = dy; d.lda = lda; d.B = w; d.ldb = ldb; d.C = du; d.ldc = ldc; d.aux = u;
+  d.colsum_partial = workspace;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = gemm(d, s);
+  if (e != hipSuccess) return rc_of(e);
+  return rc_of(colsum_finalize(workspace, (M + 31) / 32, N, dbias, accumulate != 0, s));
+}
+
 int k2bw_layernorm_fwd(int dtype, int rows, int h, float eps, const void* x, const void* gain, const void* shift,
                        void* y, float* mean, float* rstd, void* stream) {
   if (!dtype_ok(dtype)) return STAGE_ERR_INVALID_ARG;
@@ -38,18 +56,19 @@ int k2bw_layernorm_fwd(int dtype, int rows, int h, float eps, const void* x, con
 
 int64_t k2bw_layernorm_bwd_workspace(int h) {
   if (h <= 0) return STAGE_ERR_INVALID_ARG;
-  return (int64_t)ln_bwd_max_parts() * 2 * h;
+  return (int64_t)ln_bwd_max_parts() * 3 * h;
 }
 
 int k2bw_layernorm_bwd(int dtype, int rows, int h, const void* dy, const void* x, const float* mean,
                        const float* rstd, const void* gain, const void* dres, void* dx, float* dgain_dshift,
-                       int accumulate, float* workspace, void* stream) {
+                       float* dx_colsum, int accumulate, float* workspace, void* stream) {
   if (!dtype_ok(dtype) || !dgain_dshift || !workspace) return STAGE_ERR_INVALID_ARG;
   int parts = 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = layernorm_bwd(dy, x, mean, rstd, gain, dres, dx, workspace, &parts, rows, h, dtype, s);
   if (e != hipSuccess) return rc_of(e);
-  return rc_of(colsum_finalize(workspace, parts, 2 * h, dgain_dshift, accumulate != 0, s));
+  FinalizeItem fin[2] = {{workspace, parts, 3 * h, 2 * h, dgain_dshift}, {workspace + 2 * h, parts, 3 * h, h, dx_colsum}};
+  return rc_of(colsum_finalize_grouped(fin, dx_colsum ? 2 : 1, accumulate != 0, s));
 }
 
 int64_t k2bw_bias_grad_workspace(int n) {

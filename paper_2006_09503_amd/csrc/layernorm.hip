@@ -95,8 +95,10 @@ __global__ __launch_bounds__(kWg) void ln_fwd_kernel(const T* __restrict__ x, co
   if (sub == 0) { mean_out[row] = mean; rstd_out[row] = rstd; }
 }
 
-// Backward.  Workgroups stride over row groups and keep per-column sums of dy*xhat and dy in
-// registers; each workgroup writes one row of partial[parts][2h] (first h: dy*xhat, then dy).
+// Backward.  Workgroups stride over row groups and keep per-column sums of dy*xhat, dy and of the
+// result dx in registers; each workgroup writes one row of partial[parts][3h] (dy*xhat | dy | dx).
+// The third block is the bias gradient of the projection that produced this kernel's residual
+// operand (its output gradient is exactly dx), so no separate pass over dx is needed for it.
 template <typename T, int R, int CPT>
 __global__ __launch_bounds__(kWg) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                       const float* __restrict__ mean_in, const float* __restrict__ rstd_in,
@@ -107,13 +109,13 @@ __global__ __launch_bounds__(kWg) void ln_bwd_kernel(const T* __restrict__ dy, c
   __shared__ float comb[(ROWS > 1) ? (ROWS - 1) * R * CPT * 8 : 1];
   const int tid = threadIdx.x;
   const int sub = tid % R, rsub = tid / R;
-  float gsum[CPT][8], bsum[CPT][8], gn[CPT][8];
+  float gsum[CPT][8], bsum[CPT][8], osum[CPT][8], gn[CPT][8];
 #pragma unroll
   for (int c = 0; c < CPT; ++c) {
     const int col = (sub + c * R) * 8;
     if (col < h) load8(gain + col, gn[c]);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { gsum[c][i] = 0.f; bsum[c][i] = 0.f; if (col >= h) gn[c][i] = 0.f; }
+    for (int i = 0; i < 8; ++i) { gsum[c][i] = 0.f; bsum[c][i] = 0.f; osum[c][i] = 0.f; if (col >= h) gn[c][i] = 0.f; }
   }
   // Two row groups per trip, all loads of both issued before any arithmetic: the kernel is bound
   // by memory latency, not bandwidth, at the sizes a stage gives it.
@@ -177,6 +179,8 @@ __global__ __launch_bounds__(kWg) void ln_bwd_kernel(const T* __restrict__ dy, c
 #pragma unroll
               for (int i = 0; i < 8; ++i) o[i] += res[u][c][i];
             }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) osum[c][i] += o[i];
             store8(dx + (int64_t)row[u] * h + col, o);
           }
         }
@@ -185,7 +189,7 @@ __global__ __launch_bounds__(kWg) void ln_bwd_kernel(const T* __restrict__ dy, c
   }
   // combine the ROWS sub-rows of this workgroup, then one partial row per workgroup
 #pragma unroll
-  for (int which = 0; which < 2; ++which) {
+  for (int which = 0; which < 3; ++which) {
     if (ROWS > 1) {
       __syncthreads();
       if (rsub > 0) {
@@ -193,7 +197,7 @@ __global__ __launch_bounds__(kWg) void ln_bwd_kernel(const T* __restrict__ dy, c
         for (int c = 0; c < CPT; ++c)
 #pragma unroll
           for (int i = 0; i < 8; ++i)
-            comb[(((rsub - 1) * CPT + c) * 8 + i) * R + sub] = which ? bsum[c][i] : gsum[c][i];
+            comb[(((rsub - 1) * CPT + c) * 8 + i) * R + sub] = which == 0 ? gsum[c][i] : which == 1 ? bsum[c][i] : osum[c][i];
       }
       __syncthreads();
     }
@@ -205,10 +209,10 @@ __global__ __launch_bounds__(kWg) void ln_bwd_kernel(const T* __restrict__ dy, c
           float o[8];
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
-            o[i] = which ? bsum[c][i] : gsum[c][i];
+            o[i] = which == 0 ? gsum[c][i] : which == 1 ? bsum[c][i] : osum[c][i];
             for (int rr = 1; rr < ROWS; ++rr) o[i] += comb[(((rr - 1) * CPT + c) * 8 + i) * R + sub];
           }
-          store8(partial + (int64_t)blockIdx.x * 2 * h + which * h + col, o);
+          store8(partial + (int64_t)blockIdx.x * 3 * h + which * h + col, o);
         }
       }
     }

@@ -81,7 +81,7 @@ struct stage2bw {
   char* tmp_h = nullptr;
   std::vector<char*> dx1, dchain, du, dqkv;
   char* y_scratch = nullptr;  // recompute: output of the re-run forward
-  float *delta = nullptr, *ln_partial = nullptr, *ln_partial2 = nullptr, *cs_partial = nullptr;
+  float *delta = nullptr, *ln_partial = nullptr, *ln_partial2 = nullptr, *cs_partial = nullptr, *du_partial = nullptr;
 
   // timing
   bool timing = false;
@@ -335,13 +335,19 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
       w.M = M; w.N = N; w.K = T; w.epilogue = kEpiAccum; w.accumulate = acc;
       return hipSuccess;
     };
+    // Bias gradients are column sums of the four projection-output gradients.  Three of them come
+    // out of the kernels that produce those gradients: dx1 and this layer's result dx (= the next
+    // lower layer's dy) from the LayerNorm backward kernels, du (bf16 mode) from the epilogue of
+    // the GEMM that computes it; dqkv, the stage's incoming dy and du in fp32 mode are summed by
+    // the column-sum kernel.  One reduction launch per layer finishes all of them.
+    const bool fused_du = st->dtype == kBF16;
     auto dgrad = [&](const void* grad, int N, const char* w_, int K, void* out, const void* u) {
       // out[T,K] = grad[T,N] * W[K,N]^T
       GemmDesc d;
       d.dtype = st->dtype;
       d.A = grad; d.lda = N; d.B = w_; d.ldb = N; d.trans_b = true; d.C = out; d.ldc = K;
       d.M = T; d.N = K; d.K = N;
-      if (u) { d.epilogue = kEpiGeluGrad; d.aux = u; }
+      if (u) { d.epilogue = kEpiGeluGrad; d.aux = u; if (fused_du) d.colsum_partial = st->du_partial; }
       return run_gemm(st, STAGE_K_GEMM_DGRAD, d);
     };
     // y = x1 + GELU(u) W2 + b2
@@ -368,23 +374,33 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     // a = LN1(x); dx = dx1 + LN1'(da)
     e = run_ln_bwd(st, st->tmp_h, A.x, A.mean1, A.rstd1, wptr(st, buf, o.ln1_g), dx1, dx, st->ln_partial2, &ln1_parts);
     if (e != hipSuccess) return e;
-    // bias gradients (column sums of the four projection-output gradients) and the reduction of
-    // every partial of the layer: two launches
-    const ColsumItem cs[4] = {{dy, h, h}, {du, f, f}, {dx1, h, h}, {dqkv, 3 * h, 3 * h}};
+    ColsumItem cs[3];
+    int n_cs = 0, col_dqkv = 0, col_du = -1, col_dy = -1, cols = 0;
+    cs[n_cs++] = {dqkv, 3 * h, 3 * h}; cols += 3 * h;
+    if (!fused_du) { col_du = cols; cs[n_cs++] = {du, f, f}; cols += f; }
+    if (l == c.n_layers - 1) { col_dy = cols; cs[n_cs++] = {dy, h, h}; cols += h; }
     int cs_parts = 0, cs_cols = 0;
-    e = timed(st, STAGE_K_BIAS_GRAD, "colsum_partial_grouped_kernel", 0.0, (double)T * (5.0 * h + f) * st->esize, [&] {
-      return colsum_partial_grouped(cs, 4, T, st->cs_partial, &cs_parts, &cs_cols, st->dtype, st->stream);
+    e = timed(st, STAGE_K_BIAS_GRAD, "colsum_partial_grouped_kernel", 0.0, (double)T * cols * st->esize, [&] {
+      return colsum_partial_grouped(cs, n_cs, T, st->cs_partial, &cs_parts, &cs_cols, st->dtype, st->stream);
     });
     if (e != hipSuccess) return e;
-    const FinalizeItem fin[6] = {
-        {st->cs_partial, cs_parts, cs_cols, h, st->G + o.b2},
-        {st->cs_partial + h, cs_parts, cs_cols, f, st->G + o.b1},
-        {st->cs_partial + h + f, cs_parts, cs_cols, h, st->G + o.bo},
-        {st->cs_partial + 2 * h + f, cs_parts, cs_cols, 3 * h, st->G + o.bqkv},
-        {st->ln_partial, ln2_parts, 2 * h, 2 * h, st->G + o.ln2_g},
-        {st->ln_partial2, ln1_parts, 2 * h, 2 * h, st->G + o.ln1_g}};
-    e = timed(st, STAGE_K_BIAS_GRAD, "colsum_finalize_grouped_kernel", 0.0, 4.0 * (cs_parts * (double)cs_cols + (ln1_parts + ln2_parts) * 2.0 * h), [&] {
-      return colsum_finalize_grouped(fin, 6, acc, st->stream);
+    FinalizeItem fin[8];
+    int n_fin = 0;
+    double fin_elems = 0.0;
+    auto add_fin = [&](const float* partial, int parts, int ld, int n, float* out) {
+      fin[n_fin++] = {partial, parts, ld, n, out};
+      fin_elems += (double)parts * n;
+    };
+    add_fin(st->cs_partial + col_dqkv, cs_parts, cs_cols, 3 * h, st->G + o.bqkv);
+    if (fused_du) add_fin(st->du_partial, (T + 31) / 32, f, f, st->G + o.b1);
+    else add_fin(st->cs_partial + col_du, cs_parts, cs_cols, f, st->G + o.b1);
+    if (col_dy >= 0) add_fin(st->cs_partial + col_dy, cs_parts, cs_cols, h, st->G + o.b2);
+    add_fin(st->ln_partial, ln2_parts, 3 * h, 2 * h, st->G + o.ln2_g);
+    add_fin(st->ln_partial + 2 * h, ln2_parts, 3 * h, h, st->G + o.bo);
+    add_fin(st->ln_partial2, ln1_parts, 3 * h, 2 * h, st->G + o.ln1_g);
+    if (l > 0) add_fin(st->ln_partial2 + 2 * h, ln1_parts, 3 * h, h, st->G + st->off[l - 1].b2);
+    e = timed(st, STAGE_K_BIAS_GRAD, "colsum_finalize_grouped_kernel", 0.0, 4.0 * fin_elems, [&] {
+      return colsum_finalize_grouped(fin, n_fin, acc, st->stream);
     });
     if (e != hipSuccess) return e;
     dy = dx;
@@ -481,8 +497,9 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
   }
   if (cfg->recompute) ALLOC(st->y_scratch, T * h * E, nullptr);
   ALLOC(st->delta, (int64_t)cfg->microbatch * cfg->n_heads * cfg->seq * 4, nullptr);
-  ALLOC(st->ln_partial, (int64_t)ln_bwd_max_parts() * 2 * h * 4, nullptr);
-  ALLOC(st->ln_partial2, (int64_t)ln_bwd_max_parts() * 2 * h * 4, nullptr);
+  ALLOC(st->ln_partial, (int64_t)ln_bwd_max_parts() * 3 * h * 4, nullptr);
+  ALLOC(st->ln_partial2, (int64_t)ln_bwd_max_parts() * 3 * h * 4, nullptr);
+  ALLOC(st->du_partial, (int64_t)((T + 31) / 32) * f * 4, nullptr);
   ALLOC(st->cs_partial, (int64_t)colsum_max_parts() * (5 * h + f) * 4, nullptr);
 #undef ALLOC
 

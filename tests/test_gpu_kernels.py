@@ -155,6 +155,26 @@ def test_gemm_every_tile_variant(tile, M, N, K):
         assert L.k2bw_tune_gemm_tile(0) == 0
 
 
+@pytest.mark.parametrize("M,N,K", [(296, 264, 200), (4096, 1032, 136), (520, 4096, 64)])
+def test_gemm_gelu_gradient_with_fused_bias_gradient(M, N, K):
+    """du = (dy W^T) * GELU'(u) and db = colsum(du) from the same pass (bf16), overwrite then accumulate."""
+    rng = np.random.default_rng(M + N + K)
+    dy, w, u = rnd(rng, (M, K), BF16), rnd(rng, (N, K), BF16, 0.1), rnd(rng, (M, N), BF16)
+    want = (dy.astype(np.float64) @ w.astype(np.float64).T) * ob.gelu_grad(u.astype(np.float64))
+    L = B.lib()
+    DY, W, U = dev(dy, BF16), dev(w, BF16), dev(u, BF16)
+    DU = empty((M, N), BF16)
+    db = torch.full((N,), float("nan"), device="cuda")
+    ws = torch.empty(L.k2bw_gemm_dgrad_gelu_bias_workspace(M, N), device="cuda")
+    for acc in (0, 1):
+        assert L.k2bw_gemm_dgrad_gelu_bias(M, N, K, DY.data_ptr(), K, W.data_ptr(), K, DU.data_ptr(), N, U.data_ptr(),
+                                           db.data_ptr(), acc, ws.data_ptr(), None) == 0
+    sync()
+    assert rel(to_host(DU), want) < TIGHT[BF16]
+    scale = np.sqrt((want ** 2).sum(0)).max()
+    assert np.abs(to_host(db) - 2.0 * want.sum(0)).max() < 1e-5 * scale * np.sqrt(M)
+
+
 def test_gemm_rejects_shapes_it_cannot_take():
     L = B.lib()
     a = torch.zeros(64 * 64, device="cuda", dtype=torch.bfloat16)
@@ -198,15 +218,20 @@ def test_layernorm_forward_backward(dtype, rows, h):
 
     ws = torch.empty(L.k2bw_layernorm_bwd_workspace(h), device="cuda")
     dgs = torch.full((2 * h,), float("nan"), device="cuda")
+    dxs = torch.full((h,), float("nan"), device="cuda")
     assert L.k2bw_layernorm_bwd(dtype, rows, h, DY.data_ptr(), X.data_ptr(), mean.data_ptr(), rstd.data_ptr(),
-                                Gn.data_ptr(), DR.data_ptr(), DX.data_ptr(), dgs.data_ptr(), 0, ws.data_ptr(),
-                                None) == 0
+                                Gn.data_ptr(), DR.data_ptr(), DX.data_ptr(), dgs.data_ptr(), dxs.data_ptr(), 0,
+                                ws.data_ptr(), None) == 0
     sync()
     assert rel(to_host(DX), dx_want + dres) < TIGHT[dtype]
     assert rel(to_host(dgs)[:h], dg_want) < 1e-5 and rel(to_host(dgs)[h:], ds_want) < 1e-5
-    # accumulate on top, no residual
+    # column sums of the result (a bias gradient in the stage), taken before dx is rounded
+    cs_want = (dx_want + dres).sum(0)
+    assert np.abs(to_host(dxs) - cs_want).max() < 1e-5 * np.abs(dx_want + dres).sum(0).max() + 1e-4 * np.sqrt(rows)
+    # accumulate on top, no residual, no column sums
     assert L.k2bw_layernorm_bwd(dtype, rows, h, DY.data_ptr(), X.data_ptr(), mean.data_ptr(), rstd.data_ptr(),
-                                Gn.data_ptr(), None, DX.data_ptr(), dgs.data_ptr(), 1, ws.data_ptr(), None) == 0
+                                Gn.data_ptr(), None, DX.data_ptr(), dgs.data_ptr(), None, 1, ws.data_ptr(),
+                                None) == 0
     sync()
     assert rel(to_host(DX), dx_want) < TIGHT[dtype]
     assert rel(to_host(dgs)[:h], 2 * dg_want) < 1e-5 and rel(to_host(dgs)[h:], 2 * ds_want) < 1e-5
