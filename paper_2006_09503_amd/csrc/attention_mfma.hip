@@ -39,8 +39,12 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(3))) char lds_char_t;
 typedef __attribute__((address_space(1))) const void glob_void_t;
 
-constexpr int kThreads = 256;
-constexpr int kBlockRows = 128;   // rows (queries or keys) owned by a workgroup: 4 waves x 32
+// Waves per workgroup, 32 rows (queries or keys) each.  Measured on MI355X with 2 / 4 / 8 waves
+// (s = 512, dh = 64: forward 27.9 / 20.7 / 19.5 us, backward 66.7 / 58.8 / 57.1 us; s = 2048,
+// dh = 128 causal: forward 270 / 258 / 152 us): more waves share each K/V tile and each barrier.
+constexpr int kWaves = 8;
+constexpr int kThreads = kWaves * 64;
+constexpr int kBlockRows = kWaves * 32;
 constexpr int kTile = 64;         // rows streamed through LDS per step
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -52,10 +56,11 @@ struct Cfg {
   static constexpr int CH = DH / 8;                // 16-byte chunks per tile row
   static constexpr int kTileU4 = kTile * CH;       // uint4 per tile
   static constexpr int kPadU4 = 4;                 // transposing reads of the padded head columns run past a row
-  // Two waves per SIMD cap a lane at 256 registers; the compiler then keeps MFMA results in
-  // ordinary VGPRs.  With 512 available it parks them in the accumulator file and copies every
-  // score to a VGPR and back around the softmax arithmetic, which costs more than the MFMAs.
-  static constexpr int kMinWaves = DH <= 64 ? 2 : 1;
+  // Two waves per SIMD (which 8-wave workgroups imply) cap a lane at 256 registers; the compiler
+  // then keeps MFMA results in ordinary VGPRs.  With 512 available it parks them in the
+  // accumulator file and copies every score to a VGPR and back around the softmax arithmetic,
+  // which costs more than the MFMAs.
+  static constexpr int kMinWaves = 2;
 };
 
 // Chunk swizzle per head size (rows are 64 / 128 / 160 / 256 bytes; the LDS has 64 banks of 4 bytes).
@@ -79,14 +84,14 @@ template <int DH>
 struct TileLoader {
   static constexpr int CH = DH / 8;
   static constexpr int kInstr = kTile * CH / 64;            // wave-instructions per tile
-  static constexpr int NI = (kInstr + 3) / 4;               // per wave (4 waves)
+  static constexpr int NI = (kInstr + kWaves - 1) / kWaves;  // per wave
   int row[NI], coff[NI];
   int wave_;
   __device__ __forceinline__ void init(int wave, int lane) {
     wave_ = wave;
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const int L = (j * 4 + wave) * 64 + lane;
+      const int L = (j * kWaves + wave) * 64 + lane;
       const int r = L / CH, pc = L % CH;
       row[j] = r < kTile ? r : kTile - 1;
       coff[j] = (pc ^ swz<DH>(r)) * 8;
@@ -95,10 +100,10 @@ struct TileLoader {
   __device__ __forceinline__ void issue(const bf16_t* __restrict__ src, int64_t ld, int row0, int row_end, uint4* tile) const {
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      if ((j * 4 + wave_) < kInstr) {   // wave-uniform
+      if ((j * kWaves + wave_) < kInstr) {   // wave-uniform
         const int r = min(row0 + row[j], row_end - 1);
         __builtin_amdgcn_global_load_lds((glob_void_t*)(src + (int64_t)r * ld + coff[j]),
-                                         (lds_void_t*)(tile + (j * 4 + wave_) * 64), 16, 0, 0);
+                                         (lds_void_t*)(tile + (j * kWaves + wave_) * 64), 16, 0, 0);
       }
     }
   }
