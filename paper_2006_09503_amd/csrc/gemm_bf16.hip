@@ -631,6 +631,21 @@ __device__ __forceinline__ bf16x8 read_frag(const uint4* tile, int row0, int ks,
 // vmcnt = bits 3:0 and 15:14; expcnt and lgkmcnt fields left at their maxima = no wait)
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
+// Instruction order of one MFMA sub-step: the RD fragment reads of the next sub-step go between
+// the first half of the NM MFMAs of the current one, so that the second half covers their
+// latency.  Left to itself the scheduler sinks every read to just before its first use (fewer
+// live registers), and each group of MFMAs then waits out the full LDS latency.
+template <int I, int NM, int RD>
+__device__ __forceinline__ void interleave_reads_with_mfma() {
+  if constexpr (I < NM) {
+    constexpr int H = NM / 2 > 0 ? NM / 2 : 1;
+    constexpr int r = I < H ? (RD * (I + 1)) / H - (RD * I) / H : 0;
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA
+    if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);   // DS reads
+    interleave_reads_with_mfma<I + 1, NM, RD>();
+  }
+}
+
 template <int BM, int BN, int WM, int WN, int BKA, int NSTAGE, bool TA, bool TB, int EPI>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_async_kernel(GroupParams gp) {
   constexpr int NW = (BM / WM) * (BN / WN);
@@ -672,59 +687,75 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_async_ke
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
   const int nk = p.K / BKA;   // K is a multiple of 64
-  constexpr int kLoadsPerTile = AsyncLoader<BM, NW, BKA, !TA>::IPW + AsyncLoader<BN, NW, BKA, TB>::IPW;
-  static_assert((NSTAGE - 2) * kLoadsPerTile <= 63, "vmcnt range");
-  // prologue: tiles 0 .. NSTAGE-2 in flight (past the end: the last tile again, never read)
-#pragma unroll
-  for (int t = 0; t < NSTAGE - 1; ++t) {
-    const int kt_l = t < nk ? t : nk - 1;
-    ld_a.issue(kt_l * BKA, smem + t * kStage);
-    ld_b.issue(kt_l * BKA, smem + t * kStage + BM * CHK);
-  }
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * kLoadsPerTile));   // tile 0 has landed
+  static_assert(NSTAGE == 2 && KS % 2 == 0, "two LDS stages, even number of sub-steps");
+  constexpr int RD = MI * (TA ? 2 : 1) + NI * (TB ? 1 : 2);   // LDS reads per sub-step
+  // Pipeline (two stages).  At the top of K step kt the fragments of its sub-step 0 are in
+  // registers and tile kt+1 is on its way into the other stage.  Sub-steps 0..KS-2 run with the
+  // fragment reads of the following sub-step between their MFMAs; then the wave waits for its
+  // share of tile kt+1 and for its own LDS reads, and the barrier tells it that tile kt+1 is
+  // complete and that nobody reads stage kt&1 any more: the loads of tile kt+2 go there, and the
+  // last sub-step's MFMAs run with the reads of tile kt+1's first fragments between them.  Each
+  // load has a whole K step to land and no MFMA group waits for an LDS read issued just before it.
+  ld_a.issue(0, smem);
+  ld_b.issue(0, smem + BM * CHK);
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   __syncthreads();
+  {
+    const int k1 = (nk > 1 ? 1 : 0) * BKA;   // (a one-tile problem fetches tile 0 again: never read)
+    ld_a.issue(k1, smem + kStage);
+    ld_b.issue(k1, smem + kStage + BM * CHK);
+  }
+  bf16x8 af[2][MI], bfr[2][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) af[0][mi] = read_frag<BM, BKA, !TA>(smem, wm * WM + mi * 32, 0, lane);
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = read_frag<BN, BKA, TB>(smem + BM * CHK, wn * WN + ni * 32, 0, lane);
 
-  int rs = 0;             // stage being read
-  int ws = NSTAGE - 1;    // stage being filled
   for (int kt = 0; kt < nk; ++kt) {
-    const uint4* sA = smem + rs * kStage;
+    uint4* sCur = smem + (kt & 1) * kStage;
+    const uint4* sA = sCur;
     const uint4* sB = sA + BM * CHK;
-    uint4* dA = smem + ws * kStage;
-    // tile kt+NSTAGE-1 goes into the stage that was read in step kt-1 (all waves are past the
-    // barrier that ended it); past the end the last tile is fetched again: no branch, never read
-    const int k_next = (kt + NSTAGE - 1 < nk ? kt + NSTAGE - 1 : nk - 1) * BKA;
-    ld_a.issue(k_next, dA);
-    ld_b.issue(k_next, dA + BM * CHK);
-    bf16x8 af[2][MI], bfr[2][NI];
+    const uint4* nA = smem + ((kt + 1) & 1) * kStage;
+    const uint4* nB = nA + BM * CHK;
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) af[0][mi] = read_frag<BM, BKA, !TA>(sA, wm * WM + mi * 32, 0, lane);
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = read_frag<BN, BKA, TB>(sB, wn * WN + ni * 32, 0, lane);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
+    for (int ks = 0; ks + 1 < KS; ++ks) {
       const int cur = ks & 1, nxt = cur ^ 1;
-      if (ks + 1 < KS) {
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) af[nxt][mi] = read_frag<BM, BKA, !TA>(sA, wm * WM + mi * 32, ks + 1, lane);
+      for (int mi = 0; mi < MI; ++mi) af[nxt][mi] = read_frag<BM, BKA, !TA>(sA, wm * WM + mi * 32, ks + 1, lane);
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) bfr[nxt][ni] = read_frag<BN, BKA, TB>(sB, wn * WN + ni * 32, ks + 1, lane);
-      }
+      for (int ni = 0; ni < NI; ++ni) bfr[nxt][ni] = read_frag<BN, BKA, TB>(sB, wn * WN + ni * 32, ks + 1, lane);
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
     }
-    // this wave's share of tile kt+1 has landed once only the younger tiles' loads are outstanding
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * kLoadsPerTile));
+#pragma unroll
+    for (int ks = 0; ks + 1 < KS; ++ks) interleave_reads_with_mfma<0, MI * NI, RD>();
+    __builtin_amdgcn_sched_barrier(0);   // (MFMAs would otherwise sink below the barrier and leave the wait bare)
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0) & ~(15 << 8));   // vmcnt(0) and lgkmcnt(0)
     __syncthreads();
-    rs = rs + 1 == NSTAGE ? 0 : rs + 1;
-    ws = ws + 1 == NSTAGE ? 0 : ws + 1;
+    {
+      // tile kt+2 into the stage just released (past the end: the last tile again, never read)
+      const int k_next = (kt + 2 < nk ? kt + 2 : nk - 1) * BKA;
+      ld_a.issue(k_next, sCur);
+      ld_b.issue(k_next, sCur + BM * CHK);
+      constexpr int cur = (KS - 1) & 1, nxt = cur ^ 1;
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) af[nxt][mi] = read_frag<BM, BKA, !TA>(nA, wm * WM + mi * 32, 0, lane);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) bfr[nxt][ni] = read_frag<BN, BKA, TB>(nB, wn * WN + ni * 32, 0, lane);
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
+      interleave_reads_with_mfma<0, MI * NI, RD>();
+    }
   }
-  if (NSTAGE > 2) {   // prefetches past the end may still be landing in LDS
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-    __syncthreads();
-  }
+  // the last two prefetches may still be landing in LDS, which the epilogue re-uses
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+  __syncthreads();
   epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane, smem, wave, 0, MI);
 }
 
@@ -817,10 +848,6 @@ hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
     case 11: return launch_async<256, 256, 128, 128, 64, 2, TA, TB, EPI>(gp, s);
     case 12: return launch_async<128, 128, 64, 64, 64, 2, TA, TB, EPI>(gp, s);
     case 13: return launch_async<256, 256, 128, 64, 64, 2, TA, TB, EPI>(gp, s);
-    case 14: return launch_async<256, 256, 128, 64, 32, 4, TA, TB, EPI>(gp, s);    // 8 waves, 4 x 32 KB
-    case 15: return launch_async<256, 256, 128, 128, 32, 4, TA, TB, EPI>(gp, s);   // 4 waves, 4 x 32 KB
-    case 16: return launch_async<256, 256, 128, 64, 32, 3, TA, TB, EPI>(gp, s);
-    case 17: return launch_async<128, 128, 64, 64, 32, 4, TA, TB, EPI>(gp, s);     // 4 x 16 KB: 2 workgroups per CU
     default: return hipErrorInvalidValue;
   }
 }
