@@ -374,6 +374,21 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[MI][NI], const BfPa
   }
 }
 
+// Instruction order of one MFMA sub-step: the RD fragment reads of the next sub-step go between
+// the first half of the NM MFMAs of the current one, so that the second half covers their
+// latency.  Left to itself the scheduler sinks every read to just before its first use (fewer
+// live registers), and each group of MFMAs then waits out the full LDS latency.
+template <int I, int NM, int RD>
+__device__ __forceinline__ void interleave_reads_with_mfma() {
+  if constexpr (I < NM) {
+    constexpr int H = NM / 2 > 0 ? NM / 2 : 1;
+    constexpr int r = I < H ? (RD * (I + 1)) / H - (RD * I) / H : 0;
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA
+    if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);   // DS reads
+    interleave_reads_with_mfma<I + 1, NM, RD>();
+  }
+}
+
 // KSPLIT = 2: two groups of waves share the workgroup's tile and split its K range in halves, each
 // with its own pair of LDS stages; at the end the groups swap halves of their partial sums through
 // LDS and each finishes half of the tile's rows.  For launches with about one tile per CU this
@@ -387,7 +402,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KSPLIT) void gemm_bf16
   constexpr int MI = WM / 32, NI = WN / 32;
   constexpr int WAVES_N = BN / WN;
   constexpr int KS = BK / 16;
-  constexpr bool kFragDbuf = NT * KSPLIT <= 256;
+  // fragments of sub-step ks+1 are read while the MFMAs of sub-step ks run, where the registers
+  // allow it (up to 64 x 64 per wave)
+  constexpr bool kFragDbuf = MI * NI <= 4;
   static_assert(KSPLIT == 1 || (KSPLIT == 2 && MI % 2 == 0), "");
   extern __shared__ uint4 smem_all[];
 
@@ -501,6 +518,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KSPLIT) void gemm_bf16
       // sub-steps 0..KS/2-1 move slices of the A tile, the rest slices of the B tile
       if (ks < KS / 2) ld_a.step(ks, KS / 2, dA, (kt0 + kt + 2) * BK, k_hi);
       else ld_b.step(ks - KS / 2, KS / 2, dA + BM * CH, (kt0 + kt + 2) * BK, k_hi);
+      if (kFragDbuf) {
+        if (ks + 1 < KS) interleave_reads_with_mfma<0, MI * NI, MI + NI>();
+        else __builtin_amdgcn_sched_group_barrier(0x008, MI * NI, 0);
+      }
       // keep each slice's stores and loads inside its sub-step: left alone, the scheduler sinks
       // every global load to the end of the K step and hoists the selects that wait for them
       __builtin_amdgcn_sched_barrier(0);
@@ -630,21 +651,6 @@ __device__ __forceinline__ bf16x8 read_frag(const uint4* tile, int row0, int ks,
 // s_waitcnt immediate for "at most n vector-memory operations outstanding" (gfx9 encoding:
 // vmcnt = bits 3:0 and 15:14; expcnt and lgkmcnt fields left at their maxima = no wait)
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
-
-// Instruction order of one MFMA sub-step: the RD fragment reads of the next sub-step go between
-// the first half of the NM MFMAs of the current one, so that the second half covers their
-// latency.  Left to itself the scheduler sinks every read to just before its first use (fewer
-// live registers), and each group of MFMAs then waits out the full LDS latency.
-template <int I, int NM, int RD>
-__device__ __forceinline__ void interleave_reads_with_mfma() {
-  if constexpr (I < NM) {
-    constexpr int H = NM / 2 > 0 ? NM / 2 : 1;
-    constexpr int r = I < H ? (RD * (I + 1)) / H - (RD * I) / H : 0;
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA
-    if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);   // DS reads
-    interleave_reads_with_mfma<I + 1, NM, RD>();
-  }
-}
 
 template <int BM, int BN, int WM, int WN, int BKA, int NSTAGE, bool TA, bool TB, int EPI>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_async_kernel(GroupParams gp) {
