@@ -32,9 +32,10 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the same counters read for the
 # library's plain copy kernel of known size; see profiles/ for the runs.  None = not measured.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    # grouped weight-gradient GEMM of one layer (4 problems): FETCH_SIZE 125725.8 KiB x 1.995 (copy-kernel
-    # factor) + WRITE_SIZE 59105.7 KiB x 1.000; algorithmic minimum 2.349e8 (operands once + accumulator RMW)
-    "gemm_bf16_kernel<256, 256, 128, 64, 64, true, false, 3, 1>": 3.174e8,
+    # grouped weight-gradient GEMM (the 24 products of the stage's 6 layers in one launch): FETCH_SIZE
+    # 661607.1 KiB x 1.995 (copy-kernel factor) + WRITE_SIZE 294912.0 KiB x 1.000; algorithmic minimum
+    # 1.409e9 (operands once + fp32 accumulator read-modify-write)
+    "gemm_bf16_kernel<256, 256, 128, 64, 64, true, false, 3, 1>": 1.654e9,
 }
 
 
