@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C2", help="C1..C5 (see paper_2006_09503_amd/synth.py)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--flush", action="store_true", help="PipeDream-Flush (Section 3.2) instead of 2BW: one version, drain per batch")
+    ap.add_argument("--recompute", type=int, default=None, help="override the workload's activation recomputation (0/1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
@@ -103,6 +105,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     cfg = synth.PRESETS[args.workload]
+    if args.flush:
+        cfg = cfg.with_(flush=1)
+    if args.recompute is not None:
+        cfg = cfg.with_(recompute=args.recompute)
     p, m = cfg.max_inflight, cfg.m
     K, W = args.steps, args.warmup
     assert K >= 1 and W >= 2, "two warm-up batches are needed before the version rule leaves version 0"
@@ -138,11 +144,26 @@ def main():
             st.swap_versions()
         st.forward(k, X[(k - 1) % m], LEN[(k - 1) % m], Y[k % (p + 1)])
 
+    def flush_batch(b):
+        """One batch under the flush schedule: 1F1B inside the batch, drained before the update."""
+        first = b * m + 1
+        for k in range(first, first + m):
+            if k - p >= first:
+                st.backward(k - p, DY[(k - p - 1) % m], DX)
+            st.forward(k, X[(k - 1) % m], LEN[(k - 1) % m], Y[k % (p + 1)])
+        for k in range(first + m - p, first + m):
+            st.backward(k, DY[(k - 1) % m], DX)
+        st.coalesce_update()
+
     def run_steps(first_step, n_steps):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for k in range(first_step * m + 1, (first_step + n_steps) * m + 1):
-            iteration(k)
+        if cfg.flush:
+            for b in range(first_step, first_step + n_steps):
+                flush_batch(b)
+        else:
+            for k in range(first_step * m + 1, (first_step + n_steps) * m + 1):
+                iteration(k)
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
@@ -193,10 +214,11 @@ def main():
 
     # drain the microbatches still in flight so the stage ends at a batch boundary
     last = (W + K + (0 if args.no_kernel_timing else K)) * m
-    for kb in range(last - p + 1, last + 1):
-        st.backward(kb, DY[(kb - 1) % m], DX)
-        if kb % m == 0:
-            st.coalesce_update()
+    if not cfg.flush:
+        for kb in range(last - p + 1, last + 1):
+            st.backward(kb, DY[(kb - 1) % m], DX)
+            if kb % m == 0:
+                st.coalesce_update()
     torch.cuda.synchronize()
     finite = bool(torch.isfinite(DX.float()).all().item())
     alloc = st.query(B.Q_BYTES_ALLOCATED)
@@ -207,9 +229,10 @@ def main():
         "value": samples_per_s, "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.precision == synth.PREC_BF16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: one 2BW stage, L={cfg.n_layers} h={cfg.hidden} a={cfg.n_heads} "
+        "config": {"workload": f"{args.workload}: one pipeline stage, L={cfg.n_layers} h={cfg.hidden} a={cfg.n_heads} "
                                f"f={cfg.ffn} s={cfg.seq} b={cfg.microbatch} m={cfg.m} inflight={p} "
-                               f"mask={('none', 'causal', 'padding')[cfg.mask_mode]} recompute={cfg.recompute}",
+                               f"mask={('none', 'causal', 'padding')[cfg.mask_mode]} recompute={cfg.recompute} "
+                               f"schedule={'flush' if cfg.flush else '2bw'}",
                    "samples_per_step": cfg.microbatch * m, "model_flops_per_step": flops_step,
                    "stage_bytes_allocated": alloc},
         "model_tflops": tflops, "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS, "outputs_finite": finite,

@@ -14,7 +14,11 @@
  *     from that 1-stale gradient, and writes W(t+1) into the buffer that held the dead
  *     version W(t-1); no second copy of optimizer state               (Section 3.1, Semantics);
  *   - with activation recomputation only the stage input is stashed and the forward is
- *     re-run, on the stashed version, inside the backward               (Section 4.1).
+ *     re-run, on the stashed version, inside the backward               (Section 4.1);
+ *   - in flush mode (Section 3.2) the stage keeps ONE weight version: microbatch k runs on
+ *     version floor((k-1)/m), so batch t+1 cannot start before update t (the pipeline is
+ *     drained at every batch end), and the update is the vanilla W(t+1) = W(t) - nu *
+ *     step(grad f(W(t))) in place.
  *
  * All pointers named *_dev are device pointers owned by the caller, *_host are host pointers
  * owned by the caller.  Everything else is owned by the library and freed by stage_destroy.
@@ -64,6 +68,8 @@ typedef struct {
   int32_t recompute;    /* 0: stash every saved activation; 1: stash the stage input only   */
   float lr, beta1, beta2, adam_eps; /* Adam with bias correction, eps outside the root      */
   float ln_eps;                     /* added to the biased variance under the root           */
+  int32_t flush;        /* 0: 2BW (two versions, Section 3.1); 1: one version with a pipeline    */
+                        /* flush per batch (Section 3.2)                                      */
 } stage_config_t;
 
 /*
@@ -94,7 +100,8 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
  * activations (or just x, with recompute) are stashed with the version tag.
  * BAD_STATE if mb is already in flight, if no stash slot is free, or if the version the rule
  * assigns to mb is not the one new forwards currently read (call stage_swap_versions first,
- * or the needed version has not been generated yet).
+ * or the needed version has not been generated yet; in flush mode: the update of the previous
+ * batch has not been applied yet).
  */
 int stage_forward(stage_t* st, int64_t mb, const void* x_dev, const int32_t* seqlens_dev,
                   void* y_dev);
@@ -121,7 +128,8 @@ int stage_coalesce_update(stage_t* st);
 /*
  * Make the next-newer weight version the one new forward passes read; the version they read
  * so far stays available to microbatches already in flight until their backward passes are
- * done (the "shadow" version of Section 1).  BAD_STATE if no newer version exists.
+ * done (the "shadow" version of Section 1).  BAD_STATE if no newer version exists (always, in
+ * flush mode: there the update itself makes the new version current).
  */
 int stage_swap_versions(stage_t* st);
 
@@ -181,7 +189,7 @@ int stage_timing_collect_kernels(stage_t* st, int32_t capacity, char* names_out,
  * without a GPU.  Same preconditions and error codes as the stage calls.
  */
 typedef struct stage_sched stage_sched_t;
-int stage_sched_create(int32_t m, int32_t max_inflight, stage_sched_t** out);
+int stage_sched_create(int32_t m, int32_t max_inflight, int32_t flush, stage_sched_t** out);
 /* slot_out: stash slot taken; version_out: version tag; buffer_out: weight buffer to read. */
 int stage_sched_forward(stage_sched_t* s, int64_t mb, int32_t* slot_out, int64_t* version_out,
                         int32_t* buffer_out);

@@ -27,7 +27,8 @@ KERNEL_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd"
 class StageConfigC(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_heads", "ffn", "seq", "microbatch", "m",
                                          "max_inflight", "mask_mode", "precision", "recompute")] + \
-               [(n, C.c_float) for n in ("lr", "beta1", "beta2", "adam_eps", "ln_eps")]
+               [(n, C.c_float) for n in ("lr", "beta1", "beta2", "adam_eps", "ln_eps")] + \
+               [("flush", C.c_int32)]
 
 
 class StageError(RuntimeError):
@@ -63,7 +64,7 @@ def lib() -> C.CDLL:
             "stage_timing_enable": (C.c_int, [vp, C.c_int, i32]),
             "stage_timing_collect": (C.c_int, [vp, vp, vp, vp, vp]),
             "stage_timing_collect_kernels": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, C.POINTER(i32)]),
-            "stage_sched_create": (C.c_int, [i32, i32, C.POINTER(vp)]),
+            "stage_sched_create": (C.c_int, [i32, i32, i32, C.POINTER(vp)]),
             "stage_sched_forward": (C.c_int, [vp, i64, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32)]),
             "stage_sched_backward": (C.c_int, [vp, i64, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32),
                                                C.POINTER(i32)]),
@@ -225,9 +226,9 @@ def stage_timing_collect_kernels(st: int, capacity: int = 64):
 class Sched:
     """The library's 2BW bookkeeping without any device: each method returns (code, outputs...)."""
 
-    def __init__(self, m: int, max_inflight: int):
+    def __init__(self, m: int, max_inflight: int, flush: bool = False):
         h = C.c_void_p()
-        _check(lib().stage_sched_create(m, max_inflight, C.byref(h)), "stage_sched_create")
+        _check(lib().stage_sched_create(m, max_inflight, int(flush), C.byref(h)), "stage_sched_create")
         self.h = h.value
 
     def forward(self, mb):
@@ -303,7 +304,8 @@ class Stage:
         """Microbatches first_mb .. first_mb+count-1 (first_mb - 1 a multiple of m, nothing in flight).
 
         get_inputs(k) -> (x, seqlens, dy) device tensors; get_outputs(k) -> (y, dx) device tensors.
-        on_update(t) is called right after update number t has been enqueued.
+        on_update(t) is called right after update number t has been enqueued.  In flush mode the
+        in-flight microbatches are drained at every batch end before the update (Section 3.2).
         """
         m = self.cfg.m
         assert (first_mb - 1) % m == 0 and 1 <= inflight <= m
@@ -317,6 +319,19 @@ class Stage:
                 self.coalesce_update()
                 if on_update is not None:
                     on_update(k // m)
+
+        if getattr(self.cfg, "flush", 0):
+            for b0 in range(first_mb, last + 1, m):
+                b1 = min(b0 + m - 1, last)
+                for k in range(b0, b1 + 1):
+                    if k - inflight >= b0:
+                        back(k - inflight)
+                    x, lens, _ = get_inputs(k)
+                    y, _ = get_outputs(k)
+                    self.forward(k, x, lens, y)
+                for k in range(max(b1 - inflight + 1, b0), b1 + 1):
+                    back(k)
+            return
 
         for k in range(first_mb, last + 1):
             if k - inflight >= first_mb:

@@ -9,7 +9,13 @@
 //
 // At most two versions are alive: t and t-1.  Update t -> t+1 reads buffer t % 2 and writes
 // buffer (t+1) % 2, which held t-1; it is refused while an in-flight microbatch is tagged
-// t-1.  Pure host code: no device calls here.
+// t-1.
+//
+// Flush variant (Section 3.2): one weight version.  Microbatch k runs on version floor((k-1)/m),
+// i.e. no forward pass of batch t+1 is admitted before update t has been applied (the pipeline
+// is drained at every batch end), the update reads and writes the one buffer, and new forward
+// passes read the newest version at once (no swap).
+// Pure host code: no device calls here.
 #pragma once
 #include <cstdint>
 #include <vector>
@@ -25,18 +31,21 @@ class Schedule {
     int64_t version = 0;  // tag taken at the forward pass
   };
 
-  Schedule(int m, int max_inflight) : m_(m), slots_(max_inflight) {}
+  Schedule(int m, int max_inflight, bool flush = false) : m_(m), flush_(flush), slots_(max_inflight) {}
 
   static int64_t version_rule(int64_t k, int64_t m) {
     int64_t v = (k - 1) / m - 1;
     return v > 0 ? v : 0;
   }
-  static int buffer_of(int64_t version) { return static_cast<int>(version & 1); }
+  static int64_t version_rule_flush(int64_t k, int64_t m) { return (k - 1) / m; }
+  int64_t rule(int64_t k) const { return flush_ ? version_rule_flush(k, m_) : version_rule(k, m_); }
+  int buffer_of(int64_t version) const { return flush_ ? 0 : static_cast<int>(version & 1); }
+  bool flush() const { return flush_; }
 
   // Checks only; no state change.  slot: the free slot forward would take.
   int check_forward(int64_t mb, int* slot) const {
     if (mb < 1) return kInvalidArg;
-    if (version_rule(mb, m_) != r_) return kBadState;  // needs a swap, or runs ahead of the updates
+    if (rule(mb) != r_) return kBadState;              // needs a swap, or runs ahead of the updates
     if (r_ + 1 < t_) return kBadState;                 // version r is dead (buffer overwritten)
     int free_slot = -1;
     for (size_t i = 0; i < slots_.size(); ++i) {
@@ -96,6 +105,7 @@ class Schedule {
     *read_buffer = buffer_of(t_);
     *write_buffer = buffer_of(t_ + 1);
     ++t_;
+    if (flush_) r_ = t_;
     *step = t_;
     n_acc_ = 0;
     return kOk;
@@ -120,6 +130,7 @@ class Schedule {
 
  private:
   int m_;
+  bool flush_;
   std::vector<Slot> slots_;
   int64_t t_ = 0;
   int64_t r_ = 0;

@@ -88,7 +88,7 @@ struct stage2bw {
   std::vector<EventPair> events;
   size_t events_used = 0;
 
-  stage2bw(const stage_config_t& c) : cfg(c), sched(c.m, c.max_inflight) {}
+  stage2bw(const stage_config_t& c) : cfg(c), sched(c.m, c.max_inflight, c.flush != 0) {}
 };
 
 namespace {
@@ -116,6 +116,7 @@ int validate(const stage_config_t* c) {
   if (c->mask_mode < 0 || c->mask_mode > 2) return STAGE_ERR_INVALID_ARG;
   if (c->precision != STAGE_PREC_FP32 && c->precision != STAGE_PREC_BF16) return STAGE_ERR_INVALID_ARG;
   if (c->recompute != 0 && c->recompute != 1) return STAGE_ERR_INVALID_ARG;
+  if (c->flush != 0 && c->flush != 1) return STAGE_ERR_INVALID_ARG;
   if (!(c->lr >= 0.f) || !(c->beta1 >= 0.f && c->beta1 < 1.f) || !(c->beta2 >= 0.f && c->beta2 < 1.f) ||
       !(c->adam_eps >= 0.f) || !(c->ln_eps >= 0.f))
     return STAGE_ERR_INVALID_ARG;
@@ -466,7 +467,8 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
   } while (0)
 
   ALLOC(st->wbuf[0], P * E, &st->bytes_weights);
-  ALLOC(st->wbuf[1], P * E, &st->bytes_weights);
+  if (cfg->flush) st->wbuf[1] = st->wbuf[0];   // one weight version (Section 3.2)
+  else ALLOC(st->wbuf[1], P * E, &st->bytes_weights);
   if (st->dtype == kBF16) ALLOC(st->master, P * 4, &st->bytes_weights);
   ALLOC(st->G, P * 4, nullptr);
   ALLOC(st->adam_m, P * 4, nullptr);
@@ -510,9 +512,9 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
   if (e == hipSuccess) {
     if (st->dtype == kBF16) {
       e = convert_f32_to_bf16(st->master, reinterpret_cast<bf16_t*>(st->wbuf[0]), P, st->stream);
-      if (e == hipSuccess)
+      if (e == hipSuccess && !cfg->flush)
         e = hipMemcpyAsync(st->wbuf[1], st->wbuf[0], (size_t)P * 2, hipMemcpyDeviceToDevice, st->stream);
-    } else {
+    } else if (!cfg->flush) {
       e = hipMemcpyAsync(st->wbuf[1], st->wbuf[0], (size_t)P * 4, hipMemcpyDeviceToDevice, st->stream);
     }
   }
@@ -532,7 +534,7 @@ int stage_forward(stage_t* st, int64_t mb, const void* x_dev, const int32_t* seq
   int slot = -1;
   int rc = st->sched.check_forward(mb, &slot);
   if (rc != STAGE_OK) return rc;
-  const int buf = Schedule::buffer_of(st->sched.read_version());
+  const int buf = st->sched.buffer_of(st->sched.read_version());
   const int64_t in_bytes = (int64_t)st->T * st->cfg.hidden * st->esize;
   ActSet& acts = st->cfg.recompute ? st->slot_acts[0] : st->slot_acts[slot];
   // stash the stage input (with recompute it is the only thing kept)
@@ -635,7 +637,7 @@ int stage_read_weights(stage_t* st, int which, float* out_host) {
   if (!st || !out_host) return STAGE_ERR_INVALID_ARG;
   if (which == STAGE_WEIGHTS_MASTER) {
     if (st->dtype == kBF16) return read_f32(st, st->master, out_host);
-    which = Schedule::buffer_of(st->sched.updates());
+    which = st->sched.buffer_of(st->sched.updates());
   }
   if (which != 0 && which != 1) return STAGE_ERR_INVALID_ARG;
   if (st->dtype == kF32) return read_f32(st, reinterpret_cast<const float*>(st->wbuf[which]), out_host);
@@ -672,8 +674,8 @@ int stage_query(stage_t* st, int what, int64_t* out) {
     case STAGE_Q_BYTES_ALLOCATED: *out = st->bytes_total; break;
     case STAGE_Q_BYTES_WEIGHTS: *out = st->bytes_weights; break;
     case STAGE_Q_BYTES_STASH: *out = st->bytes_stash; break;
-    case STAGE_Q_BUFFER_OF_NEWEST: *out = Schedule::buffer_of(st->sched.updates()); break;
-    case STAGE_Q_BUFFER_OF_READ: *out = Schedule::buffer_of(st->sched.read_version()); break;
+    case STAGE_Q_BUFFER_OF_NEWEST: *out = st->sched.buffer_of(st->sched.updates()); break;
+    case STAGE_Q_BUFFER_OF_READ: *out = st->sched.buffer_of(st->sched.read_version()); break;
     default: return STAGE_ERR_INVALID_ARG;
   }
   return STAGE_OK;
@@ -759,12 +761,12 @@ int stage_timing_collect(stage_t* st, double* ms_out, int64_t* launches_out, dou
 
 struct stage_sched {
   Schedule s;
-  stage_sched(int m, int p) : s(m, p) {}
+  stage_sched(int m, int p, bool flush) : s(m, p, flush) {}
 };
 
-int stage_sched_create(int32_t m, int32_t max_inflight, stage_sched_t** out) {
-  if (!out || m < 1 || max_inflight < 1 || m < max_inflight) return STAGE_ERR_INVALID_ARG;
-  *out = new (std::nothrow) stage_sched(m, max_inflight);
+int stage_sched_create(int32_t m, int32_t max_inflight, int32_t flush, stage_sched_t** out) {
+  if (!out || m < 1 || max_inflight < 1 || m < max_inflight || (flush != 0 && flush != 1)) return STAGE_ERR_INVALID_ARG;
+  *out = new (std::nothrow) stage_sched(m, max_inflight, flush != 0);
   return *out ? STAGE_OK : STAGE_ERR_OOM;
 }
 int stage_sched_forward(stage_sched_t* s, int64_t mb, int32_t* slot_out, int64_t* version_out, int32_t* buffer_out) {
@@ -804,8 +806,8 @@ int stage_sched_query(stage_sched_t* s, int what, int64_t* out) {
     case STAGE_Q_READ_VERSION: *out = s->s.read_version(); break;
     case STAGE_Q_INFLIGHT: *out = s->s.inflight(); break;
     case STAGE_Q_ACCUMULATED: *out = s->s.accumulated(); break;
-    case STAGE_Q_BUFFER_OF_NEWEST: *out = Schedule::buffer_of(s->s.updates()); break;
-    case STAGE_Q_BUFFER_OF_READ: *out = Schedule::buffer_of(s->s.read_version()); break;
+    case STAGE_Q_BUFFER_OF_NEWEST: *out = s->s.buffer_of(s->s.updates()); break;
+    case STAGE_Q_BUFFER_OF_READ: *out = s->s.buffer_of(s->s.read_version()); break;
     default: return STAGE_ERR_INVALID_ARG;
   }
   return STAGE_OK;

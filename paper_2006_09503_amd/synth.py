@@ -46,6 +46,7 @@ class StageConfig:
     mask_mode: int = MASK_NONE
     precision: int = PREC_FP32
     recompute: int = 0          # Section 4.1: stash only the stage input
+    flush: int = 0              # Section 3.2: one weight version, pipeline flush per batch
     lr: float = 1e-3
     beta1: float = 0.9
     beta2: float = 0.999

@@ -72,8 +72,11 @@ def run_stage_oracle(cfg: synth.StageConfig, w0: np.ndarray, mbs, inflight: int 
     st = ob.Stage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.mask_mode, cfg.ln_eps)
     f32 = lambda z: float(np.float32(z))        # the C ABI carries the hyper-parameters as floats
     opt = tb.Adam(f32(cfg.lr), f32(cfg.beta1), f32(cfg.beta2), f32(cfg.adam_eps))
+    rule = tb.weight_version_flush if cfg.flush else tb.weight_version
+    if cfg.flush:
+        inflight = 1        # the oracle's generic order only drains at batch ends when nothing overlaps them
     return tb.replay(lambda w, x, dy, lens: st.vjp(w, x, dy, lens), w0.astype(np.float64), mbs, cfg.m, opt,
-                     inflight=inflight)
+                     inflight=inflight, version_rule=rule)
 
 
 def compare_stage(cfg, gpu, tr: tb.Trace, tol=None, check_dw=True, check_weights=True):
@@ -92,15 +95,18 @@ def compare_stage(cfg, gpu, tr: tb.Trace, tol=None, check_dw=True, check_weights
         chk("dX", gpu["dX"][k], tr.dX[k])
     for s in gpu["snaps"]:
         t = s["t"]
-        assert s["updates"] == t and s["newest"] == t % 2
+        assert s["updates"] == t and s["newest"] == (0 if cfg.flush else t % 2)
         chk("G", s["G"], tr.G[t - 1])
         chk("adam_m", s["m"], tr.opt_state[t - 1]["m"])
         chk("adam_v", s["v"], tr.opt_state[t - 1]["v"])
         if not check_weights:
             continue
-        new, old = (s["buf1"], s["buf0"]) if t % 2 else (s["buf0"], s["buf1"])
+        new, old = (s["buf1"], s["buf0"]) if (t % 2 and not cfg.flush) else (s["buf0"], s["buf1"])
         chk("W_new_buffer", new, tr.W[t])
-        chk("W_other_buffer", old, tr.W[t - 1])        # the shadow version is still intact
+        if cfg.flush:
+            assert np.array_equal(old, new)            # one version: both names read the same buffer
+        else:
+            chk("W_other_buffer", old, tr.W[t - 1])    # the shadow version is still intact
         chk("W_master", s["master"], tr.W[t])
         if check_dw:
             # the raw weights move by only ~lr/0.02 per step; the step itself is the sensitive quantity

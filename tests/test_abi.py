@@ -61,7 +61,7 @@ def test_invalid_configs_are_rejected(bad):
 
 def test_config_struct_layout_matches_header():
     # 11 int32 + 5 float, no padding
-    assert ctypes.sizeof(binding.StageConfigC) == 16 * 4
+    assert ctypes.sizeof(binding.StageConfigC) == 17 * 4
     text = open(os.path.join(ROOT, "include", "stage2bw.h")).read()
     body = text[text.index("typedef struct {"):text.index("} stage_config_t;")]
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
@@ -84,4 +84,4 @@ def test_null_arguments_return_invalid_arg():
     assert L.stage_destroy(None) == binding.ERR_INVALID_ARG
     assert L.stage_sched_swap_versions(None) == binding.ERR_INVALID_ARG
     h = ctypes.c_void_p()
-    assert L.stage_sched_create(2, 3, ctypes.byref(h)) == binding.ERR_INVALID_ARG      # m < in-flight depth
+    assert L.stage_sched_create(2, 3, 0, ctypes.byref(h)) == binding.ERR_INVALID_ARG   # m < in-flight depth

@@ -130,3 +130,37 @@ def test_memory_report_matches_the_papers_formula():
     stash = st.query(B.Q_BYTES_STASH)
     assert cfg.max_inflight * per_mb <= stash < cfg.max_inflight * per_mb * 1.2
     st.close()
+
+
+@pytest.mark.parametrize("precision", [synth.PREC_FP32, synth.PREC_BF16])
+def test_flush_mode_has_vanilla_semantics_and_one_version(precision):
+    """Section 3.2: W(t+1) = W(t) - nu * step(grad f(W(t))) with a single weight version; the stage is
+    driven in 1F1B order with a drain at every batch end."""
+    cfg = RAGGED.with_(precision=precision, mask_mode=synth.MASK_PADDING, flush=1)
+    gpu, tr = both(cfg, 3, 2, seed=5)
+    worst = compare_stage(cfg, gpu, tr)
+    print(f"flush prec={precision}:", {k: f"{v:.2e}" for k, v in worst.items()})
+    assert [tr.version_used[k] for k in (1, 3, 4, 6, 7)] == [0, 0, 1, 1, 2]
+    # one version buffer less than the 2BW stage with the same shapes
+    gen = synth.StageInputs(cfg, 5)
+    w0 = gen.weights()
+    a = B.Stage(cfg, w0); b2 = B.Stage(cfg.with_(flush=0), w0)
+    esize = 2 if precision == synth.PREC_BF16 else 4
+    saved = b2.query(B.Q_BYTES_WEIGHTS) - a.query(B.Q_BYTES_WEIGHTS)
+    assert a.n_params * esize <= saved < a.n_params * esize + 4096
+    # the 2BW calls that make no sense here are refused
+    with pytest.raises(B.StageError):
+        a.swap_versions()
+    a.close(); b2.close()
+
+
+def test_flush_and_2bw_differ_from_the_second_update_on():
+    """Batch 1 runs on W(1) under flush and on W(0) under 2BW: same first update, different second."""
+    cfg = RAGGED.with_(precision=synth.PREC_FP32, mask_mode=synth.MASK_NONE, lr=1e-2)
+    gen = synth.StageInputs(cfg, 6)
+    w0 = gen.weights()
+    mbs = gen.microbatches(2 * cfg.m)
+    two = run_stage_gpu(cfg, w0, mbs, 2)
+    fl = run_stage_gpu(cfg.with_(flush=1), w0, mbs, 2)
+    assert np.array_equal(two["snaps"][0]["master"], fl["snaps"][0]["master"])
+    assert rel(fl["snaps"][1]["G"], two["snaps"][1]["G"]) > 1e-3

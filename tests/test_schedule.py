@@ -124,3 +124,31 @@ def test_matches_oracle_replay_versions():
     used = {k: v for e, k, v, b in log if e == "F"}
     tr = tb.replay(lambda w, *_: (None, None, w * 0), np.zeros(1), [()] * (m * nb), m, tb.Sgd(0.1), inflight=p)
     assert used == tr.version_used
+
+
+@pytest.mark.parametrize("m,p", [(4, 4), (4, 2), (3, 1), (8, 4)])
+def test_flush_variant_keeps_one_version_and_drains_every_batch(m, p):
+    """Section 3.2: microbatch k runs on version floor((k-1)/m); the next batch cannot start before
+    the update; one buffer; no swap."""
+    s = B.Sched(m, p, flush=True)
+    for b in range(4):
+        first = b * m + 1
+        # the whole batch in 1F1B order, drained at its end
+        for k in range(first, first + m):
+            if k - p >= first:
+                rc, slot, ver, buf, is_first = s.backward(k - p)
+                assert rc == 0 and ver == b and buf == 0 and is_first == (1 if k - p == first else 0)
+            rc, slot, ver, buf = s.forward(k)
+            assert rc == 0 and ver == tb.weight_version_flush(k, m) == b and buf == 0
+        # a forward pass of the next batch is refused while this batch's update is outstanding
+        assert s.forward(first + m)[0] == B.ERR_BAD_STATE
+        assert s.coalesce_update()[0] == B.ERR_BAD_STATE          # backward passes still missing
+        for k in range(max(first + m - p, first), first + m):
+            rc, slot, ver, buf, _ = s.backward(k)
+            assert rc == 0 and ver == b and buf == 0
+        assert s.query(B.Q_INFLIGHT) == 0
+        rc, rb, wb, step = s.coalesce_update()
+        assert rc == 0 and rb == 0 and wb == 0 and step == b + 1   # in place
+        assert s.query(B.Q_READ_VERSION) == b + 1                  # current at once
+        assert s.swap_versions() == B.ERR_BAD_STATE
+    s.close()
