@@ -47,6 +47,7 @@ enum {
 
 enum { STAGE_MASK_NONE = 0, STAGE_MASK_CAUSAL = 1, STAGE_MASK_PADDING = 2 };
 enum { STAGE_PREC_FP32 = 0, STAGE_PREC_BF16 = 1 };
+enum { STAGE_OPT_ADAM = 0, STAGE_OPT_MOMENTUM = 1 };
 
 typedef struct stage2bw stage_t; /* opaque */
 
@@ -70,6 +71,9 @@ typedef struct {
   float ln_eps;                     /* added to the biased variance under the root           */
   int32_t flush;        /* 0: 2BW (two versions, Section 3.1); 1: one version with a pipeline    */
                         /* flush per batch (Section 3.2)                                      */
+  int32_t optimizer;    /* STAGE_OPT_ADAM, or STAGE_OPT_MOMENTUM: m <- beta1 m + (1-beta1) g,    */
+                        /* W(t+1) = W(t) - lr m, the form Section 3.1 prints (beta2, adam_eps    */
+                        /* unused; the second-moment array is not allocated)                  */
 } stage_config_t;
 
 /*
@@ -143,7 +147,8 @@ enum { STAGE_WEIGHTS_BUF0 = 0, STAGE_WEIGHTS_BUF1 = 1, STAGE_WEIGHTS_MASTER = 2 
 int stage_read_weights(stage_t* st, int which, float* out_host);
 /* The coalesced accumulator (sum over the backward passes since the last update). */
 int stage_read_grad_accum(stage_t* st, float* out_host);
-/* Adam first and second moments; either pointer may be NULL. */
+/* Adam first and second moments (momentum SGD: its one moment; v_out_host must then be NULL);
+ * either pointer may be NULL. */
 int stage_read_adam(stage_t* st, float* m_out_host, float* v_out_host);
 
 enum {

@@ -89,6 +89,12 @@ int k2bw_adam(int64_t n, const float* w_cur, float* w_next, void* w_next_bf16, f
  * 2: 128x128/4, 3: 256x256/8, 4: 256x128/4, 5: 128x256/4, 6: 256x128/8).  Process-wide. */
 int k2bw_tune_gemm_tile(int id);
 
+/* SGD with momentum as Section 3.1 prints it: g = G/m_micro, m <- beta m + (1-beta) g,
+ * w_next = w_cur - lr m (fp32; w_next may equal w_cur), and, if w_next_bf16 is not NULL, its bf16
+ * rounding.  n: multiple of 4. */
+int k2bw_momentum(int64_t n, const float* w_cur, float* w_next, void* w_next_bf16, float* m,
+                  const float* G, float lr, float beta, int m_micro, void* stream);
+
 /* Plain 16-byte copy (bytes multiple of 16): the reference kernel for scaling HBM counters. */
 int k2bw_copy(const void* in, void* out, int64_t bytes, void* stream);
 

@@ -28,7 +28,7 @@ class StageConfigC(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_heads", "ffn", "seq", "microbatch", "m",
                                          "max_inflight", "mask_mode", "precision", "recompute")] + \
                [(n, C.c_float) for n in ("lr", "beta1", "beta2", "adam_eps", "ln_eps")] + \
-               [("flush", C.c_int32)]
+               [("flush", C.c_int32), ("optimizer", C.c_int32)]
 
 
 class StageError(RuntimeError):
@@ -83,6 +83,7 @@ def lib() -> C.CDLL:
             "k2bw_attention_fwd": (C.c_int, [C.c_int] * 6 + [vp, vp, vp, vp, vp]),
             "k2bw_attention_bwd": (C.c_int, [C.c_int] * 6 + [vp, vp, vp, vp, vp, vp, vp, vp]),
             "k2bw_adam": (C.c_int, [i64, vp, vp, vp, vp, vp, vp, f32, f32, f32, f32, C.c_int, i64, vp]),
+            "k2bw_momentum": (C.c_int, [i64, vp, vp, vp, vp, vp, f32, f32, C.c_int, vp]),
             "k2bw_copy": (C.c_int, [vp, vp, i64, vp]),
             "k2bw_tune_gemm_tile": (C.c_int, [C.c_int]),
         }
@@ -184,10 +185,10 @@ def stage_read_grad_accum(st: int, n_params: int) -> np.ndarray:
     return out
 
 
-def stage_read_adam(st: int, n_params: int):
+def stage_read_adam(st: int, n_params: int, second_moment: bool = True):
     m = np.empty(n_params, dtype=np.float32)
-    v = np.empty(n_params, dtype=np.float32)
-    _check(lib().stage_read_adam(st, m.ctypes.data, v.ctypes.data), "stage_read_adam")
+    v = np.empty(n_params, dtype=np.float32) if second_moment else None
+    _check(lib().stage_read_adam(st, m.ctypes.data, v.ctypes.data if second_moment else None), "stage_read_adam")
     return m, v
 
 
@@ -284,7 +285,7 @@ class Stage:
     def query(self, what): return stage_query(self.h, what)
     def read_weights(self, which): return stage_read_weights(self.h, which, self.n_params)
     def read_grad_accum(self): return stage_read_grad_accum(self.h, self.n_params)
-    def read_adam(self): return stage_read_adam(self.h, self.n_params)
+    def read_adam(self): return stage_read_adam(self.h, self.n_params, getattr(self.cfg, "optimizer", 0) == 0)
     def timing_enable(self, enable, capacity=0): stage_timing_enable(self.h, enable, capacity)
     def timing_collect(self): return stage_timing_collect(self.h)
     def timing_collect_kernels(self, capacity=64): return stage_timing_collect_kernels(self.h, capacity)

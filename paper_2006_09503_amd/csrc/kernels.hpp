@@ -112,6 +112,8 @@ struct AdamDesc {
   float omb1 = 0, omb2 = 0;        // 1 - beta, rounded once from double
 };
 hipError_t adam_step(const AdamDesc& d, hipStream_t stream);
+// SGD with momentum (Section 3.1's printed form); uses w_*, m, G, n, lr, beta1, inv_m of the descriptor.
+hipError_t momentum_step(const AdamDesc& d, hipStream_t stream);
 
 // ---------------------------------------------------------------------------- conversions / copies
 hipError_t convert_f32_to_bf16(const float* in, bf16_t* out, int64_t n, hipStream_t stream);

@@ -114,6 +114,15 @@ int k2bw_adam(int64_t n, const float* w_cur, float* w_next, void* w_next_bf16, f
   return rc_of(adam_step(d, static_cast<hipStream_t>(stream)));
 }
 
+int k2bw_momentum(int64_t n, const float* w_cur, float* w_next, void* w_next_bf16, float* m, const float* G, float lr,
+                  float beta, int m_micro, void* stream) {
+  if (m_micro < 1 || !(beta >= 0.f && beta < 1.f)) return STAGE_ERR_INVALID_ARG;
+  AdamDesc d;
+  d.n = n; d.w_cur = w_cur; d.w_next = w_next; d.w_next_lp = static_cast<bf16_t*>(w_next_bf16);
+  d.m = m; d.G = G; d.lr = lr; d.beta1 = beta; d.inv_m = 1.0f / (float)m_micro;
+  return rc_of(momentum_step(d, static_cast<hipStream_t>(stream)));
+}
+
 int k2bw_copy(const void* in, void* out, int64_t bytes, void* stream) {
   return rc_of(copy_bytes(in, out, bytes, static_cast<hipStream_t>(stream)));
 }

@@ -49,6 +49,34 @@ __global__ __launch_bounds__(256) void adam_kernel(AdamDesc d) {
   }
 }
 
+// SGD with momentum in the form Section 3.1 prints: m <- beta m + (1 - beta) g, W(t+1) = W(t) - lr m,
+// with g = G / m_micro the coalesced 1-stale gradient; no bias correction, no second moment.
+// 12 B/param read, 8 (+2 bf16) written.
+template <bool LP>
+__global__ __launch_bounds__(256) void momentum_kernel(AdamDesc d) {
+  const int64_t n4 = d.n / 4;
+  const int64_t base = (int64_t)blockIdx.x * (256 * kAdamPerThread) + threadIdx.x;
+  const float omb1 = d.omb1;
+#pragma unroll
+  for (int u = 0; u < kAdamPerThread; ++u) {
+    const int64_t i = base + u * 256;
+    if (i >= n4) continue;
+    const float4 w = reinterpret_cast<const float4*>(d.w_cur)[i];
+    const float4 m = reinterpret_cast<const float4*>(d.m)[i];
+    const float4 gs = reinterpret_cast<const float4*>(d.G)[i];
+    float wv[4] = {w.x, w.y, w.z, w.w}, mv[4] = {m.x, m.y, m.z, m.w};
+    const float gv[4] = {gs.x, gs.y, gs.z, gs.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      mv[k] = d.beta1 * mv[k] + omb1 * (gv[k] * d.inv_m);
+      wv[k] = wv[k] - d.lr * mv[k];
+    }
+    reinterpret_cast<float4*>(d.m)[i] = make_float4(mv[0], mv[1], mv[2], mv[3]);
+    reinterpret_cast<float4*>(d.w_next)[i] = make_float4(wv[0], wv[1], wv[2], wv[3]);
+    if (LP) reinterpret_cast<uint2*>(d.w_next_lp)[i] = make_uint2(pack_bf16x2(wv[0], wv[1]), pack_bf16x2(wv[2], wv[3]));
+  }
+}
+
 __global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ in, bf16_t* __restrict__ out,
                                                            int64_t n4) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -100,6 +128,22 @@ hipError_t adam_step(const AdamDesc& d_in, hipStream_t stream) {
     hipLaunchKernelGGL(adam_kernel<true>, dim3(grid), dim3(256), 0, stream, d);
   else
     hipLaunchKernelGGL(adam_kernel<false>, dim3(grid), dim3(256), 0, stream, d);
+  return hipGetLastError();
+}
+
+hipError_t momentum_step(const AdamDesc& d_in, hipStream_t stream) {
+  AdamDesc d = d_in;
+  d.omb1 = (float)(1.0 - (double)d.beta1);
+  if (d.n <= 0 || d.n % 4 || !d.w_cur || !d.w_next || !d.m || !d.G) return hipErrorInvalidValue;
+  if (!aligned16(d.w_cur) || !aligned16(d.w_next) || !aligned16(d.m) || !aligned16(d.G) ||
+      (reinterpret_cast<uintptr_t>(d.w_next_lp) & 7))
+    return hipErrorInvalidValue;
+  const int64_t blocks = (d.n / 4 + 256 * kAdamPerThread - 1) / (256 * kAdamPerThread);
+  if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+  if (d.w_next_lp)
+    hipLaunchKernelGGL(momentum_kernel<true>, dim3((int)blocks), dim3(256), 0, stream, d);
+  else
+    hipLaunchKernelGGL(momentum_kernel<false>, dim3((int)blocks), dim3(256), 0, stream, d);
   return hipGetLastError();
 }
 

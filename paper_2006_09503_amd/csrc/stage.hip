@@ -117,6 +117,7 @@ int validate(const stage_config_t* c) {
   if (c->precision != STAGE_PREC_FP32 && c->precision != STAGE_PREC_BF16) return STAGE_ERR_INVALID_ARG;
   if (c->recompute != 0 && c->recompute != 1) return STAGE_ERR_INVALID_ARG;
   if (c->flush != 0 && c->flush != 1) return STAGE_ERR_INVALID_ARG;
+  if (c->optimizer != STAGE_OPT_ADAM && c->optimizer != STAGE_OPT_MOMENTUM) return STAGE_ERR_INVALID_ARG;
   if (!(c->lr >= 0.f) || !(c->beta1 >= 0.f && c->beta1 < 1.f) || !(c->beta2 >= 0.f && c->beta2 < 1.f) ||
       !(c->adam_eps >= 0.f) || !(c->ln_eps >= 0.f))
     return STAGE_ERR_INVALID_ARG;
@@ -472,7 +473,7 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
   if (st->dtype == kBF16) ALLOC(st->master, P * 4, &st->bytes_weights);
   ALLOC(st->G, P * 4, nullptr);
   ALLOC(st->adam_m, P * 4, nullptr);
-  ALLOC(st->adam_v, P * 4, nullptr);
+  if (cfg->optimizer == STAGE_OPT_ADAM) ALLOC(st->adam_v, P * 4, nullptr);
 
   const int n_sets = cfg->recompute ? 1 : cfg->max_inflight;
   st->slot_acts.resize(n_sets);
@@ -520,7 +521,7 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
   }
   if (e == hipSuccess) e = hipMemsetAsync(st->G, 0, (size_t)P * 4, st->stream);
   if (e == hipSuccess) e = hipMemsetAsync(st->adam_m, 0, (size_t)P * 4, st->stream);
-  if (e == hipSuccess) e = hipMemsetAsync(st->adam_v, 0, (size_t)P * 4, st->stream);
+  if (e == hipSuccess && st->adam_v) e = hipMemsetAsync(st->adam_v, 0, (size_t)P * 4, st->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(st->stream);
   if (e != hipSuccess) return fail(hip_rc(e));
   *out = st;
@@ -610,6 +611,11 @@ int stage_coalesce_update(stage_t* st) {
     d.w_cur = reinterpret_cast<const float*>(st->wbuf[rb]); d.w_next = reinterpret_cast<float*>(st->wbuf[wb]);
     bytes = 28.0 * st->P;
   }
+  if (st->cfg.optimizer == STAGE_OPT_MOMENTUM) {
+    bytes -= 8.0 * st->P;   // no second moment
+    HIP_TRY(timed(st, STAGE_K_ADAM, "momentum_kernel", 0.0, bytes, [&] { return momentum_step(d, st->stream); }));
+    return STAGE_OK;
+  }
   HIP_TRY(timed(st, STAGE_K_ADAM, "adam_kernel", 0.0, bytes, [&] { return adam_step(d, st->stream); }));
   return STAGE_OK;
 }
@@ -660,7 +666,10 @@ int stage_read_grad_accum(stage_t* st, float* out_host) {
 int stage_read_adam(stage_t* st, float* m_out_host, float* v_out_host) {
   if (!st) return STAGE_ERR_INVALID_ARG;
   if (m_out_host) { int rc = read_f32(st, st->adam_m, m_out_host); if (rc) return rc; }
-  if (v_out_host) { int rc = read_f32(st, st->adam_v, v_out_host); if (rc) return rc; }
+  if (v_out_host) {
+    if (!st->adam_v) return STAGE_ERR_INVALID_ARG;   // momentum SGD keeps no second moment
+    int rc = read_f32(st, st->adam_v, v_out_host); if (rc) return rc;
+  }
   return STAGE_OK;
 }
 

@@ -32,6 +32,9 @@ MASK_PADDING = 2
 PREC_FP32 = 0
 PREC_BF16 = 1
 
+OPT_ADAM = 0
+OPT_MOMENTUM = 1
+
 
 @dataclass(frozen=True)
 class StageConfig:
@@ -47,6 +50,7 @@ class StageConfig:
     precision: int = PREC_FP32
     recompute: int = 0          # Section 4.1: stash only the stage input
     flush: int = 0              # Section 3.2: one weight version, pipeline flush per batch
+    optimizer: int = 0          # 0 Adam, 1 SGD with momentum (Section 3.1's printed form, beta = beta1)
     lr: float = 1e-3
     beta1: float = 0.9
     beta2: float = 0.999

@@ -71,7 +71,10 @@ def run_stage_gpu(cfg: synth.StageConfig, w0: np.ndarray, mbs, inflight: int, sn
 def run_stage_oracle(cfg: synth.StageConfig, w0: np.ndarray, mbs, inflight: int = 1) -> tb.Trace:
     st = ob.Stage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.mask_mode, cfg.ln_eps)
     f32 = lambda z: float(np.float32(z))        # the C ABI carries the hyper-parameters as floats
-    opt = tb.Adam(f32(cfg.lr), f32(cfg.beta1), f32(cfg.beta2), f32(cfg.adam_eps))
+    if cfg.optimizer == synth.OPT_MOMENTUM:
+        opt = tb.Momentum(f32(cfg.lr), f32(cfg.beta1))
+    else:
+        opt = tb.Adam(f32(cfg.lr), f32(cfg.beta1), f32(cfg.beta2), f32(cfg.adam_eps))
     rule = tb.weight_version_flush if cfg.flush else tb.weight_version
     if cfg.flush:
         inflight = 1        # the oracle's generic order only drains at batch ends when nothing overlaps them
@@ -98,7 +101,8 @@ def compare_stage(cfg, gpu, tr: tb.Trace, tol=None, check_dw=True, check_weights
         assert s["updates"] == t and s["newest"] == (0 if cfg.flush else t % 2)
         chk("G", s["G"], tr.G[t - 1])
         chk("adam_m", s["m"], tr.opt_state[t - 1]["m"])
-        chk("adam_v", s["v"], tr.opt_state[t - 1]["v"])
+        if cfg.optimizer == synth.OPT_ADAM:
+            chk("adam_v", s["v"], tr.opt_state[t - 1]["v"])
         if not check_weights:
             continue
         new, old = (s["buf1"], s["buf0"]) if (t % 2 and not cfg.flush) else (s["buf0"], s["buf1"])

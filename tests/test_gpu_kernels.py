@@ -252,6 +252,23 @@ def test_bias_gradient_column_sums(dtype, rows, n):
     assert rel(to_host(out), 2 * y.astype(np.float64).sum(0)) < 1e-5
 
 
+def test_momentum_sgd_kernel():
+    rng = np.random.default_rng(11)
+    n, m_micro, lr, beta = 4096 * 5 + 8, 4, 0.05, 0.9
+    w = rng.standard_normal(n).astype(np.float32); mom = rng.standard_normal(n).astype(np.float32) * 0.1
+    G = rng.standard_normal(n).astype(np.float32)
+    W, M, Gd = (torch.from_numpy(a).cuda() for a in (w, mom, G))
+    Wn = torch.empty_like(W); Wlp = torch.empty(n, device="cuda", dtype=torch.bfloat16)
+    assert B.lib().k2bw_momentum(n, W.data_ptr(), Wn.data_ptr(), Wlp.data_ptr(), M.data_ptr(), Gd.data_ptr(), lr, beta,
+                                 m_micro, None) == 0
+    sync()
+    b = float(np.float32(beta)); l = float(np.float32(lr))
+    m_want = b * mom.astype(np.float64) + (1.0 - b) * G.astype(np.float64) / m_micro
+    w_want = w.astype(np.float64) - l * m_want
+    assert rel(to_host(M), m_want) < 1e-6 and rel(to_host(Wn), w_want) < 1e-6
+    assert np.array_equal(to_host(Wlp), round_to_bf16(to_host(Wn)))
+
+
 # ----------------------------------------------------------------------------- attention
 
 ATTN_SHAPES = [  # b, s, a, dh

@@ -164,3 +164,22 @@ def test_flush_and_2bw_differ_from_the_second_update_on():
     fl = run_stage_gpu(cfg.with_(flush=1), w0, mbs, 2)
     assert np.array_equal(two["snaps"][0]["master"], fl["snaps"][0]["master"])
     assert rel(fl["snaps"][1]["G"], two["snaps"][1]["G"]) > 1e-3
+
+
+@pytest.mark.parametrize("precision", [synth.PREC_FP32, synth.PREC_BF16])
+def test_momentum_sgd_under_2bw(precision):
+    """The update Section 3.1 prints: m_t = beta m_(t-1) + (1 - beta) grad f(W(t-1)), W(t+1) = W(t) - nu m_t,
+    with one moment array and no extra copy of it for the stale version."""
+    cfg = RAGGED.with_(precision=precision, mask_mode=synth.MASK_CAUSAL, optimizer=synth.OPT_MOMENTUM, lr=5e-2)
+    gpu, tr = both(cfg, 4, 2, seed=7)
+    # the step is lr * m (no sign-like normalisation), so dW carries the plain tolerance
+    worst = compare_stage(cfg, gpu, tr, check_dw=False)
+    print(f"momentum prec={precision}:", {k: f"{v:.2e}" for k, v in worst.items()})
+    for s in gpu["snaps"][1:]:
+        t = s["t"]
+        dw = s["master"].astype(np.float64) - gpu["snaps"][t - 2]["master"]
+        assert rel(dw, tr.W[t] - tr.W[t - 1]) <= (1e-4 if precision == synth.PREC_FP32 else 2e-2)
+    st = B.Stage(cfg, synth.StageInputs(cfg, 7).weights())
+    with pytest.raises(B.StageError):
+        B.stage_read_adam(st.h, st.n_params, second_moment=True)     # there is none
+    st.close()
