@@ -31,6 +31,20 @@ class StageConfigC(C.Structure):
                [("flush", C.c_int32), ("optimizer", C.c_int32)]
 
 
+class PlannerInputC(C.Structure):
+    _fields_ = [("n_blocks", C.c_int32), ("n_gpus", C.c_int32), ("gpus_per_server", C.c_int32), ("n_sizes", C.c_int32),
+                ("microbatch_sizes", C.POINTER(C.c_int32)), ("block_time_s", C.POINTER(C.c_double)),
+                ("weight_bytes", C.c_double), ("state_bytes", C.c_double), ("act_bytes_per_sample", C.c_double),
+                ("input_bytes_per_sample", C.c_double), ("boundary_bytes_per_sample", C.c_double),
+                ("bw_high", C.c_double), ("bw_low", C.c_double), ("memory_capacity", C.c_double),
+                ("global_batch", C.c_int64), ("c_extra", C.c_double)]
+
+
+class PlannerChoiceC(C.Structure):
+    _fields_ = [("w", C.c_int32), ("d", C.c_int32), ("b", C.c_int32), ("mode", C.c_int32), ("g", C.c_int64),
+                ("throughput", C.c_double), ("memory", C.c_double)]
+
+
 class StageError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -86,6 +100,10 @@ def lib() -> C.CDLL:
             "k2bw_momentum": (C.c_int, [i64, vp, vp, vp, vp, vp, f32, f32, C.c_int, vp]),
             "k2bw_copy": (C.c_int, [vp, vp, i64, vp]),
             "k2bw_tune_gemm_tile": (C.c_int, [C.c_int]),
+            "planner_throughput": (C.c_int, [C.POINTER(PlannerInputC), i32, i32, i32, i32, C.POINTER(C.c_double)]),
+            "planner_memory": (C.c_int, [C.POINTER(PlannerInputC), i32, i32, i32, i32, C.POINTER(C.c_double)]),
+            "planner_search": (C.c_int, [C.POINTER(PlannerInputC), i32, i32, C.POINTER(PlannerChoiceC)]),
+            "planner_partition": (C.c_int, [C.POINTER(PlannerInputC), C.POINTER(PlannerChoiceC)]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -344,3 +362,51 @@ class Stage:
             self.forward(k, x, lens, y)
         for k in range(max(last - inflight + 1, first_mb), last + 1):
             back(k)
+
+
+# ----------------------------------------------------------------------------- planner (host)
+
+PLANNER_NO_PIPELINE, PLANNER_PIPELINE, PLANNER_PIPELINE_RECOMPUTE = 0, 1, 2
+
+
+class Planner:
+    """The library's planner (Section 3.4 / appendix); `profile` is any object with the fields of
+    planner_input_t (microbatch_sizes and block_time_s as sequences)."""
+
+    def __init__(self, profile):
+        n = len(profile.microbatch_sizes)
+        self._sizes = (C.c_int32 * n)(*profile.microbatch_sizes)
+        self._times = (C.c_double * n)(*profile.block_time_s)
+        c = PlannerInputC()
+        for name, _ in PlannerInputC._fields_:
+            if name == "n_sizes":
+                c.n_sizes = n
+            elif name == "microbatch_sizes":
+                c.microbatch_sizes = self._sizes
+            elif name == "block_time_s":
+                c.block_time_s = self._times
+            else:
+                setattr(c, name, getattr(profile, name))
+        self._c = c
+
+    def throughput(self, w, d, b, mode):
+        out = C.c_double()
+        rc = lib().planner_throughput(C.byref(self._c), w, d, b, mode, C.byref(out))
+        return rc, out.value
+
+    def memory(self, w, d, b, mode):
+        out = C.c_double()
+        rc = lib().planner_memory(C.byref(self._c), w, d, b, mode, C.byref(out))
+        return rc, out.value
+
+    @staticmethod
+    def _choice(rc, c):
+        return rc, (None if rc else (c.w, c.d, c.b, c.mode, c.g, c.throughput, c.memory))
+
+    def search(self, w, d):
+        c = PlannerChoiceC()
+        return self._choice(lib().planner_search(C.byref(self._c), w, d, C.byref(c)), c)
+
+    def partition(self):
+        c = PlannerChoiceC()
+        return self._choice(lib().planner_partition(C.byref(self._c), C.byref(c)), c)

@@ -1,0 +1,113 @@
+"""The planner (host only): the library's cost functions and sweep against the brute-force oracle,
+and the oracle against hand-computed values of the appendix's closed forms."""
+import numpy as np
+import pytest
+
+from oracle import planner as op
+from paper_2006_09503_amd import binding as B
+
+
+def profile(**kw):
+    base = dict(n_blocks=24, n_gpus=8, gpus_per_server=8, microbatch_sizes=[1, 2, 4, 8],
+                block_time_s=[1.0e-3, 1.8e-3, 3.4e-3, 6.6e-3], weight_bytes=600e6, state_bytes=0.0,
+                act_bytes_per_sample=480e6, input_bytes_per_sample=1e6, boundary_bytes_per_sample=2e6,
+                bw_high=100e9, bw_low=10e9, memory_capacity=16e9, global_batch=64, c_extra=4.0 / 3.0)
+    base.update(kw)
+    return op.Profile(**base)
+
+
+def test_oracle_cost_functions_match_hand_computation():
+    """Appendix closed forms with the numbers plugged in by hand."""
+    p = profile()
+    # d=4, w=2, b=4, pipelined: 6 blocks/stage * 3.4 ms = 20.4 ms compute; boundary 2*2e6*4/100e9 = 0.16 ms;
+    # all-reduce 2*(1/2)*(600e6/4)/100e9 = 1.5 ms every m = 64/(2*4) = 8 microbatches -> 0.1875 ms.
+    t = 20.4e-3 + 0.16e-3
+    assert op.throughput(p, 2, 4, 4, op.PIPELINE) == pytest.approx(2 * 4 / t, rel=1e-12)
+    # without pipelining the 4 stages run one after the other
+    assert op.throughput(p, 2, 4, 4, op.NO_PIPELINE) == pytest.approx(2 * 4 / (4 * t), rel=1e-12)
+    # recomputation: compute * 4/3, communication unchanged
+    assert op.throughput(p, 2, 4, 4, op.PIPELINE_RECOMPUTE) == pytest.approx(8 / (20.4e-3 * 4 / 3 + 0.16e-3), rel=1e-12)
+    # MEMORY: 2|W|/d + d|A_total|/d + d|A_input|  and  2|W|/d + |A_total|/d + d|A_input|
+    assert op.memory(p, 2, 4, 4, op.PIPELINE) == pytest.approx(2 * 600e6 / 4 + 480e6 * 4 + 4 * 1e6 * 4)
+    assert op.memory(p, 2, 4, 4, op.PIPELINE_RECOMPUTE) == pytest.approx(2 * 600e6 / 4 + 480e6 * 4 / 4 + 4 * 1e6 * 4)
+    assert op.memory(p, 2, 4, 4, op.NO_PIPELINE) == pytest.approx(600e6 / 4 + 480e6 * 4 / 4)
+    # one GPU: no communication at all, throughput = b / (blocks * block time)
+    assert op.throughput(p, 1, 1, 8, op.PIPELINE) == pytest.approx(8 / (24 * 6.6e-3))
+
+
+def test_oracle_all_reduce_bound_and_server_boundary():
+    # communication-bound replica: tiny compute, big weights, one microbatch per update
+    p = profile(block_time_s=[1e-6, 2e-6, 4e-6, 8e-6], global_batch=8, weight_bytes=8e9)
+    t_ar = 2 * (7 / 8) * 8e9 / 100e9
+    assert op.throughput(p, 8, 1, 1, op.PIPELINE) == pytest.approx(8 * 1 / t_ar)       # m(b) = 1
+    # 16 GPUs in servers of 8: w=2, d=8 keeps each pipeline in a server (stage traffic fast, all-reduce slow) or
+    # the stage replicas together (all-reduce fast, stage traffic slow); the better orientation counts
+    q = profile(n_gpus=16, global_batch=64)
+    t_depth_inside = max(3 * 3.4e-3 + 2 * 2e6 * 4 / 100e9, (2 * 0.5 * 600e6 / 8 / 10e9) / 8)
+    t_width_inside = max(3 * 3.4e-3 + 2 * 2e6 * 4 / 10e9, (2 * 0.5 * 600e6 / 8 / 100e9) / 8)
+    assert op.throughput(q, 2, 8, 4, op.PIPELINE) == pytest.approx(8 / min(t_depth_inside, t_width_inside))
+
+
+def test_oracle_partition_prefers_what_fits():
+    # memory so small that only recomputation (or a deep pipeline) fits the larger microbatches
+    p = profile(memory_capacity=1.5e9)
+    w, d, b, mode, g, thr, mem = op.partition(p)
+    assert mem <= 1.5e9 and w * d <= 8 and 24 % d == 0 and g == 64 // (w * b)
+    # nothing can beat the sum of all GPUs' compute
+    assert thr <= 8 * max(bb / (24 * t) for bb, t in zip(p.microbatch_sizes, p.block_time_s)) * (1 + 1e-12)
+    # more memory never lowers the optimum
+    assert op.partition(profile(memory_capacity=64e9))[5] >= thr
+
+
+def rand_profile(rng):
+    sizes = sorted(rng.choice(np.arange(1, 33), size=int(rng.integers(1, 6)), replace=False).tolist())
+    t1 = float(rng.uniform(0.2e-3, 3e-3))
+    times = [t1 * s ** float(rng.uniform(0.7, 1.0)) for s in sizes]
+    gps = int(rng.choice([1, 2, 4, 8]))
+    n_gpus = gps * int(rng.choice([1, 2, 4]))
+    return profile(n_blocks=int(rng.choice([12, 24, 30, 48])), n_gpus=n_gpus, gpus_per_server=gps,
+                   microbatch_sizes=sizes, block_time_s=times, weight_bytes=float(rng.uniform(0.1e9, 20e9)),
+                   state_bytes=float(rng.choice([0.0, 1.0])) * float(rng.uniform(0.1e9, 40e9)),
+                   act_bytes_per_sample=float(rng.uniform(50e6, 2e9)), input_bytes_per_sample=float(rng.uniform(0.1e6, 20e6)),
+                   boundary_bytes_per_sample=float(rng.uniform(0.1e6, 40e6)), bw_high=float(rng.uniform(20e9, 900e9)),
+                   bw_low=float(rng.uniform(1e9, 20e9)), memory_capacity=float(rng.uniform(2e9, 288e9)),
+                   global_batch=int(rng.choice([32, 64, 96, 512, 2048])), c_extra=float(rng.uniform(1.0, 1.6)))
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_library_planner_matches_the_brute_force_oracle(seed):
+    rng = np.random.default_rng(seed)
+    p = rand_profile(rng)
+    pl = B.Planner(p)
+    # cost functions on every admissible point
+    for w in range(1, p.n_gpus + 1):
+        for d in range(1, p.n_gpus // w + 1):
+            if p.n_blocks % d:
+                assert pl.throughput(w, d, p.microbatch_sizes[0], 1)[0] == B.ERR_INVALID_ARG
+                continue
+            for b in p.microbatch_sizes:
+                if w * b > p.global_batch:
+                    continue
+                for mode in (0, 1, 2):
+                    rc, thr = pl.throughput(w, d, b, mode)
+                    assert rc == 0 and thr == pytest.approx(op.throughput(p, w, d, b, mode), rel=1e-12)
+                    rc, mem = pl.memory(w, d, b, mode)
+                    assert rc == 0 and mem == pytest.approx(op.memory(p, w, d, b, mode), rel=1e-12)
+    rc, got = pl.partition()
+    want = op.partition(p)
+    if want is None:
+        assert rc == -2
+    else:
+        assert rc == 0
+        assert got[5] == pytest.approx(want[5], rel=1e-12)           # same optimum (ties may pick another point)
+        assert got[6] <= p.memory_capacity and got[4] == p.global_batch // (got[0] * got[2])
+
+
+def test_library_planner_rejects_bad_input():
+    p = profile()
+    pl = B.Planner(p)
+    assert pl.throughput(3, 3, 4, 1)[0] == B.ERR_INVALID_ARG        # 9 GPUs > 8
+    assert pl.throughput(1, 5, 4, 1)[0] == B.ERR_INVALID_ARG        # 5 does not divide 24 blocks
+    assert pl.throughput(1, 4, 3, 1)[0] == B.ERR_INVALID_ARG        # 3 is not a candidate size
+    assert pl.memory(1, 4, 4, 7)[0] == B.ERR_INVALID_ARG
+    assert B.Planner(profile(memory_capacity=1e6)).partition()[0] == -2
