@@ -80,6 +80,50 @@ def cpu_baseline(cfg, seed):
                       f"all {P} parameters ({t_adam:.2f} s), extrapolated linearly to L={cfg.n_layers}, m={cfg.m}"}
 
 
+def pipeline_bench(args, cfg, w0):
+    """d stages of the workload's shape chained in one process (the whole model has d * L layers)."""
+    import torch
+    from paper_2006_09503_amd import synth
+    from paper_2006_09503_amd.pipeline import Pipeline
+    d, m, K, W = args.stages, cfg.m, args.steps, args.warmup
+    assert not cfg.flush and m >= d
+    pipe = Pipeline(cfg, [w0] * d)
+    dt = torch.bfloat16 if cfg.precision == synth.PREC_BF16 else torch.float32
+    g = torch.Generator(device="cuda").manual_seed(args.seed)
+    shape = (cfg.microbatch, cfg.seq, cfg.hidden)
+    X = [torch.randn(shape, generator=g, device="cuda", dtype=torch.float32).to(dt) for _ in range(m)]
+    TG = [torch.randn(shape, generator=g, device="cuda", dtype=torch.float32).to(dt) for _ in range(m)]
+    LEN = [None] * m
+    if cfg.mask_mode == synth.MASK_PADDING:
+        LEN = [torch.randint(cfg.min_len, cfg.seq + 1, (cfg.microbatch,), generator=g, device="cuda", dtype=torch.int32)
+               for _ in range(m)]
+    scale = 1.0 / (cfg.microbatch * cfg.seq * cfg.hidden)
+    torch.cuda.synchronize()
+
+    def run(first_batch, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        pipe.run(first_batch * m + 1, n * m, lambda k: (X[(k - 1) % m], LEN[(k - 1) % m]), lambda k: TG[(k - 1) % m], scale)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    run(0, W)
+    elapsed = run(W, K)
+    flops_step = model_flops_per_microbatch(cfg) * m * d
+    alloc = sum(st.query(4) for st in pipe.stages)
+    pipe.close()
+    print(json.dumps({
+        "metric": "pipeline samples/sec (d stages of the workload's shape on 1 MI355X, one stream per stage, 2BW)",
+        "value": cfg.microbatch * m * K / elapsed, "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.precision == synth.PREC_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload} x {d} stages: {d * cfg.n_layers} layers h={cfg.hidden} a={cfg.n_heads} "
+                               f"f={cfg.ffn} s={cfg.seq} b={cfg.microbatch} m={m}, in-process pipeline, squared-error loss",
+                   "samples_per_step": cfg.microbatch * m, "model_flops_per_step": flops_step, "bytes_allocated": alloc},
+        "model_tflops": flops_step * K / elapsed / 1e12,
+        "frac_of_bf16_mfma_peak": flops_step * K / elapsed / 1e12 / PEAK_BF16_TFLOPS}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -89,6 +133,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--flush", action="store_true", help="PipeDream-Flush (Section 3.2) instead of 2BW: one version, drain per batch")
     ap.add_argument("--recompute", type=int, default=None, help="override the workload's activation recomputation (0/1)")
+    ap.add_argument("--stages", type=int, default=1, help="d > 1: a d-stage 2BW pipeline of such stages in this process, one "
+                    "HIP stream per stage, squared-error loss behind the last (an extra measurement, not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
@@ -115,6 +161,9 @@ def main():
 
     gen = synth.StageInputs(cfg, args.seed)
     w0 = gen.weights()
+    if args.stages > 1:
+        pipeline_bench(args, cfg, w0)
+        return
     st = B.Stage(cfg, w0)
     del w0
     # a pool of m distinct microbatches, resident in HBM, reused batch after batch

@@ -89,6 +89,12 @@ int k2bw_adam(int64_t n, const float* w_cur, float* w_next, void* w_next_bf16, f
  * 2: 128x128/4, 3: 256x256/8, 4: 256x128/4, 5: 128x256/4, 6: 256x128/8).  Process-wide. */
 int k2bw_tune_gemm_tile(int id);
 
+/* dy = (y - target) * scale, element-wise over n elements (n a multiple of 8 in bf16, of 4 in
+ * fp32): the gradient of scale/2 * sum (y - target)^2, which a multi-stage run puts behind its
+ * last stage in place of the seeded boundary gradient. */
+int k2bw_squared_error_grad(int dtype, int64_t n, const void* y, const void* target, float scale,
+                            void* dy, void* stream);
+
 /* SGD with momentum as Section 3.1 prints it: g = G/m_micro, m <- beta m + (1-beta) g,
  * w_next = w_cur - lr m (fp32; w_next may equal w_cur), and, if w_next_bf16 is not NULL, its bf16
  * rounding.  n: multiple of 4. */

@@ -98,6 +98,7 @@ def lib() -> C.CDLL:
             "k2bw_attention_bwd": (C.c_int, [C.c_int] * 6 + [vp, vp, vp, vp, vp, vp, vp, vp]),
             "k2bw_adam": (C.c_int, [i64, vp, vp, vp, vp, vp, vp, f32, f32, f32, f32, C.c_int, i64, vp]),
             "k2bw_momentum": (C.c_int, [i64, vp, vp, vp, vp, vp, f32, f32, C.c_int, vp]),
+            "k2bw_squared_error_grad": (C.c_int, [C.c_int, i64, vp, vp, f32, vp, vp]),
             "k2bw_copy": (C.c_int, [vp, vp, i64, vp]),
             "k2bw_tune_gemm_tile": (C.c_int, [C.c_int]),
             "planner_throughput": (C.c_int, [C.POINTER(PlannerInputC), i32, i32, i32, i32, C.POINTER(C.c_double)]),
@@ -116,6 +117,9 @@ def strerror(code: int) -> str:
     return lib().stage_strerror(code).decode()
 
 
+DT_F32, DT_BF16 = 0, 1      # dtype codes of the k2bw_* kernel calls
+
+
 def _check(code: int, where: str):
     if code != STAGE_OK:
         raise StageError(code, where)
@@ -130,6 +134,9 @@ def _ptr(t) -> Optional[int]:
         return t.ctypes.data
     assert t.is_contiguous()
     return t.data_ptr()
+
+
+check = _check
 
 
 def _stream_ptr(stream) -> Optional[int]:

@@ -116,6 +116,9 @@ hipError_t adam_step(const AdamDesc& d, hipStream_t stream);
 hipError_t momentum_step(const AdamDesc& d, hipStream_t stream);
 
 // ---------------------------------------------------------------------------- conversions / copies
+// dy = (y - target) * scale over n elements (n a multiple of 8 in bf16, 4 in fp32)
+hipError_t squared_error_grad(const void* y, const void* target, void* dy, float scale, int64_t n, int dtype,
+                              hipStream_t stream);
 hipError_t convert_f32_to_bf16(const float* in, bf16_t* out, int64_t n, hipStream_t stream);
 hipError_t convert_bf16_to_f32(const bf16_t* in, float* out, int64_t n, hipStream_t stream);
 hipError_t copy_bytes(const void* in, void* out, int64_t bytes, hipStream_t stream);

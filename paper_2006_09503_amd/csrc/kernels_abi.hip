@@ -123,6 +123,11 @@ int k2bw_momentum(int64_t n, const float* w_cur, float* w_next, void* w_next_bf1
   return rc_of(momentum_step(d, static_cast<hipStream_t>(stream)));
 }
 
+int k2bw_squared_error_grad(int dtype, int64_t n, const void* y, const void* target, float scale, void* dy, void* stream) {
+  if (!dtype_ok(dtype)) return STAGE_ERR_INVALID_ARG;
+  return rc_of(squared_error_grad(y, target, dy, scale, n, dtype, static_cast<hipStream_t>(stream)));
+}
+
 int k2bw_copy(const void* in, void* out, int64_t bytes, void* stream) {
   return rc_of(copy_bytes(in, out, bytes, static_cast<hipStream_t>(stream)));
 }

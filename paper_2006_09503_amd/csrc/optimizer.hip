@@ -102,6 +102,29 @@ __global__ __launch_bounds__(256) void copy16_kernel(const uint4* __restrict__ i
   if (i < n16) out[i] = in[i];
 }
 
+// dy = (y - target) * scale: the gradient of scale/2 * sum (y - target)^2, the loss the last stage of a
+// multi-stage run applies to its output; 8 elements (bf16) or 4 (fp32) per thread.
+template <typename T>
+__global__ __launch_bounds__(256) void squared_error_grad_kernel(const T* __restrict__ y, const T* __restrict__ target,
+                                                                  T* __restrict__ dy, float scale, int64_t n) {
+  constexpr int V = Act<T>::kVec;
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * V;
+  if (i >= n) return;
+  float a[8], b[8], o[8];
+  if (V == 8) {
+    load8(reinterpret_cast<const bf16_t*>(y) + i, a);
+    load8(reinterpret_cast<const bf16_t*>(target) + i, b);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) o[k] = (a[k] - b[k]) * scale;
+    store8(reinterpret_cast<bf16_t*>(dy) + i, o);
+  } else {
+    const float4 ya = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(y) + i);
+    const float4 tb = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(target) + i);
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(dy) + i) =
+        make_float4((ya.x - tb.x) * scale, (ya.y - tb.y) * scale, (ya.z - tb.z) * scale, (ya.w - tb.w) * scale);
+  }
+}
+
 int stream_grid(int64_t items) {
   // enough workgroups to cover 256 CUs several times over, capped so the grid-stride loop does the rest
   int64_t g = (items + 255) / 256;
@@ -158,6 +181,22 @@ hipError_t convert_bf16_to_f32(const bf16_t* in, float* out, int64_t n, hipStrea
   if (n <= 0 || n % 4 || !in || !out || !aligned16(out) || (reinterpret_cast<uintptr_t>(in) & 7))
     return hipErrorInvalidValue;
   hipLaunchKernelGGL(bf16_to_f32_kernel, dim3(stream_grid(n / 4)), dim3(256), 0, stream, in, out, n / 4);
+  return hipGetLastError();
+}
+
+hipError_t squared_error_grad(const void* y, const void* target, void* dy, float scale, int64_t n, int dtype,
+                              hipStream_t stream) {
+  const int v = dtype == kBF16 ? 8 : 4;
+  if (n <= 0 || n % v || !y || !target || !dy || !aligned16(y) || !aligned16(target) || !aligned16(dy))
+    return hipErrorInvalidValue;
+  const int64_t blocks = (n / v + 255) / 256;
+  if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+  if (dtype == kBF16)
+    hipLaunchKernelGGL(squared_error_grad_kernel<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       static_cast<const bf16_t*>(y), static_cast<const bf16_t*>(target), static_cast<bf16_t*>(dy), scale, n);
+  else
+    hipLaunchKernelGGL(squared_error_grad_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       static_cast<const float*>(y), static_cast<const float*>(target), static_cast<float*>(dy), scale, n);
   return hipGetLastError();
 }
 
