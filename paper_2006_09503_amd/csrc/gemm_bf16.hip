@@ -283,10 +283,43 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[MI][NI], const BfPa
   float4* strip = reinterpret_cast<float4*>(smem) + wave * (32 * CPR);
   const int r = lane & 31, khalf = lane >> 5;
   const int col_base = n0 + wn * WN;
+  // What a strip reads from HBM besides the accumulators -- the fp32 tile it adds to (kEpiAccum),
+  // the residual (kEpiStore) or the pre-activation (kEpiGeluGrad) -- is fetched one strip ahead,
+  // so that its latency runs under the previous strip's LDS round trip and stores.
+  constexpr int NIT = EPI == kEpiAccum ? WN / 8 : WN / 16;   // row-major passes of 64 lanes over a strip
+  constexpr int LPR = EPI == kEpiAccum ? CPR : WN / 8;        // lanes per strip row
+  constexpr int CW = EPI == kEpiAccum ? 4 : 8;                // columns per lane
+  const bool want_pre = EPI == kEpiAccum ? p.accumulate != 0 : (EPI == kEpiGeluGrad || (EPI == kEpiStore && p.aux != nullptr));
+  uint4 pre[2][NIT];
+  auto prefetch = [&](int mi, int buf) {
+    const int row_base = m0 + wm * WM + mi * 32;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int L = it * 64 + lane;
+      const int row = row_base + L / LPR, col = col_base + (L % LPR) * CW;
+      if (row < p.M && col < p.N) {
+        const int64_t idx = (int64_t)row * p.ldc + col;
+        pre[buf][it] = EPI == kEpiAccum ? *reinterpret_cast<const uint4*>(static_cast<const float*>(p.C) + idx)
+                                        : *reinterpret_cast<const uint4*>(p.aux + idx);
+      }
+    }
+  };
+  if (want_pre) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+      if (mi == mi_begin) prefetch(mi, mi & 1);
+  }
+  // the bias columns of a lane are the same in every pass and strip
+  float bias8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if ((EPI == kEpiStore || EPI == kEpiGelu) && p.bias) {
+    const int col = col_base + (lane % (WN / 8)) * 8;
+    if (col < p.N) unpack8(*reinterpret_cast<const uint4*>(p.bias + col), bias8);
+  }
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
     if (mi < mi_begin || mi >= mi_begin + mi_count) continue;   // wave-uniform
     const int row_base = m0 + wm * WM + mi * 32;
+    if (want_pre && mi + 1 < MI && mi + 1 < mi_begin + mi_count) prefetch(mi + 1, (mi + 1) & 1);
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
@@ -298,7 +331,7 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[MI][NI], const BfPa
     wave_lds_sync();
     if (EPI == kEpiAccum) {
 #pragma unroll
-      for (int it = 0; it < WN / 8; ++it) {
+      for (int it = 0; it < NIT; ++it) {
         const int L = it * 64 + lane;
         const int rr = L / CPR, c = L % CPR;
         const float4 v = strip[rr * CPR + (c ^ (rr & 15))];
@@ -307,8 +340,9 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[MI][NI], const BfPa
           float4* dst = reinterpret_cast<float4*>(static_cast<float*>(p.C) + (int64_t)row * p.ldc + col);
           float4 o = v;
           if (p.accumulate) {
-            const float4 old = *dst;
-            o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
+            const uint4 old = pre[mi & 1][it];
+            o.x += __uint_as_float(old.x); o.y += __uint_as_float(old.y);
+            o.z += __uint_as_float(old.z); o.w += __uint_as_float(old.w);
           }
           *dst = o;
         }
@@ -316,7 +350,7 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[MI][NI], const BfPa
     } else {
       float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int it = 0; it < WN / 16; ++it) {
+      for (int it = 0; it < NIT; ++it) {
         const int L = it * 64 + lane;
         const int rr = L / (WN / 8), c8 = L % (WN / 8);
         const float4 lo = strip[rr * CPR + ((2 * c8) ^ (rr & 15))];
@@ -325,17 +359,15 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[MI][NI], const BfPa
         if (row < p.M && col < p.N) {   // N is a multiple of 8: a group of 8 columns is inside or outside as a whole
           const int64_t idx = (int64_t)row * p.ldc + col;
           float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-          if ((EPI == kEpiStore || EPI == kEpiGelu) && p.bias) {
-            float b[8];
-            unpack8(*reinterpret_cast<const uint4*>(p.bias + col), b);
+          if (EPI == kEpiStore || EPI == kEpiGelu) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] += b[j];
+            for (int j = 0; j < 8; ++j) v[j] += bias8[j];
           }
           bf16_t* out = static_cast<bf16_t*>(p.C) + idx;
           if (EPI == kEpiStore) {
             if (p.aux) {
               float res[8];
-              unpack8(*reinterpret_cast<const uint4*>(p.aux + idx), res);
+              unpack8(pre[mi & 1][it], res);
 #pragma unroll
               for (int j = 0; j < 8; ++j) v[j] += res[j];
             }
@@ -347,7 +379,7 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[MI][NI], const BfPa
             *reinterpret_cast<uint4*>(p.aux_out + idx) = pack8(v);
           } else {   // kEpiGeluGrad
             float u[8];
-            unpack8(*reinterpret_cast<const uint4*>(p.aux + idx), u);
+            unpack8(pre[mi & 1][it], u);
 #pragma unroll
             for (int j = 0; j < 8; ++j) v[j] *= gelu_grad_fast(u[j]);
             *reinterpret_cast<uint4*>(out) = pack8(v);
