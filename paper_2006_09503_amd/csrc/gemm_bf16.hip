@@ -852,8 +852,9 @@ int g_tile_override = 0;  // 0: heuristic; else force a tile shape (tuning aid)
 int choose_tile(const BfParams* p, int count, bool ta, bool tb) {
   int tile = g_tile_override;
   if (tile == 0) {
-    // Measured on MI355X (M = 4096..8192): once 256x256 tiles give at least 3/4 of the CUs a tile
-    // the 8-wave 256x256 kernels win (the asynchronous one is on par when both operands are
+    // Measured on MI355X (M = 2048..8192): once 256x256 tiles give about 5/8 of the CUs a tile
+    // (160 tiles: N = 2560 at M = 4096) the 8-wave 256x256 kernels win, by 15..30 % at 160..192
+    // tiles and more above (the asynchronous one is a little ahead when both operands are
     // K-contiguous; it needs K % 64 == 0 and falls back to the register-staged kernel otherwise).
     // Below that, 128x128 tiles: two workgroups per CU when there are enough tiles, and the
     // variant with two K groups per workgroup when there is about one tile per CU (+15..25 %).
@@ -862,7 +863,7 @@ int choose_tile(const BfParams* p, int count, bool ta, bool tb) {
       big += (int64_t)ceil_div(p[g].M, 256) * ceil_div(p[g].N, 256);
       small += (int64_t)ceil_div(p[g].M, 128) * ceil_div(p[g].N, 128);
     }
-    if (big >= 192) tile = (!ta && tb) ? 13 : 3;
+    if (big >= 144) tile = (!ta && tb) ? 13 : 3;
     else tile = small <= 256 ? 6 : 2;
   }
   if (tile > 10) {   // the asynchronous kernels need whole K tiles

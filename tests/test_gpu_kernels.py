@@ -41,7 +41,7 @@ def sync():
 # ----------------------------------------------------------------------------- GEMM
 
 GEMM_SHAPES = [
-    # (M, N, K)   small ragged; several 128-tiles; 256x256-tile path (>= 192 big tiles), ragged
+    # (M, N, K)   small ragged; several 128-tiles; 256x256-tile path (>= 144 big tiles), ragged
     (70, 40, 24), (300, 264, 200), (512, 384, 256), (4000, 3080, 136),
 ]
 
