@@ -85,8 +85,11 @@ int k2bw_adam(int64_t n, const float* w_cur, float* w_next, void* w_next_bf16, f
               const float* G, float lr, float beta1, float beta2, float eps, int m_micro, int64_t step,
               void* stream);
 
-/* Tuning aid: force the bf16 GEMM's workgroup tile (0 = built-in choice; 1: 256x256/4 waves,
- * 2: 128x128/4, 3: 256x256/8, 4: 256x128/4, 5: 128x256/4, 6: 256x128/8).  Process-wide. */
+/* Tuning aid: force the bf16 GEMM's kernel variant (0 = built-in choice).  Register-staged:
+ * 1: 256x256 tile / 4 waves, 2: 128x128 / 4 waves, 3: 256x256 / 8 waves, 6: 128x128 with two K
+ * groups of 4 waves.  Direct-to-LDS loads (K a multiple of 64, else the register-staged twin):
+ * 11: 256x256 / 4 waves, 12: 128x128 / 4 waves, 13: 256x256 / 8 waves.  Other ids: INVALID_ARG.
+ * Process-wide. */
 int k2bw_tune_gemm_tile(int id);
 
 /* dy = (y - target) * scale, element-wise over n elements (n a multiple of 8 in bf16, of 4 in

@@ -869,7 +869,6 @@ int choose_tile(const BfParams* p, int count, bool ta, bool tb) {
   if (tile > 10) {   // the asynchronous kernels need whole K tiles
     for (int g = 0; g < count; ++g)
       if (p[g].K % 64) { tile -= 10; break; }
-    if (tile == 4 || tile == 5 || tile == 7) tile = 2;   // no register-staged twin
   }
   return tile;
 }
@@ -881,8 +880,6 @@ hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
     case 1: return launch<256, 256, 128, 128, 64, TA, TB, EPI>(gp, s);
     case 2: return launch<128, 128, 64, 64, 64, TA, TB, EPI>(gp, s);
     case 3: return launch<256, 256, 128, 64, 64, TA, TB, EPI>(gp, s);   // 8 waves
-    case 4: return launch<128, 128, 64, 64, 128, TA, TB, EPI>(gp, s);   // deeper K step
-    case 5: return launch<256, 128, 128, 64, 64, TA, TB, EPI>(gp, s);
     case 6: return launch<128, 128, 64, 64, 64, TA, TB, EPI, 2>(gp, s);   // two K groups of 4 waves
     case 11: return launch_async<256, 256, 128, 128, 64, 2, TA, TB, EPI>(gp, s);
     case 12: return launch_async<128, 128, 64, 64, 64, 2, TA, TB, EPI>(gp, s);

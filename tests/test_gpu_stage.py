@@ -183,3 +183,20 @@ def test_momentum_sgd_under_2bw(precision):
     with pytest.raises(B.StageError):
         B.stage_read_adam(st.h, st.n_params, second_moment=True)     # there is none
     st.close()
+
+
+@pytest.mark.parametrize("precision", [synth.PREC_FP32, synth.PREC_BF16])
+@pytest.mark.parametrize("shape", [
+    dict(n_layers=1, hidden=8, n_heads=1, ffn=8, seq=1, microbatch=1, m=1, max_inflight=1),        # one token, one key
+    dict(n_layers=1, hidden=16, n_heads=2, ffn=24, seq=3, microbatch=2, m=2, max_inflight=1, mask_mode=synth.MASK_PADDING,
+         min_len=1),                                                                               # key lengths down to 1
+    dict(n_layers=3, hidden=128, n_heads=1, ffn=8, seq=65, microbatch=1, m=2, max_inflight=2, mask_mode=synth.MASK_CAUSAL),
+    dict(n_layers=1, hidden=256, n_heads=2, ffn=1032, seq=129, microbatch=2, m=1, max_inflight=1, mask_mode=synth.MASK_CAUSAL),
+])
+def test_degenerate_and_minimal_shapes(precision, shape):
+    """Smallest admissible dimensions, one key per query, a head as wide as the model (head size 128), tile
+    sizes plus one, m = 1 (an update after every microbatch)."""
+    cfg = synth.StageConfig(**shape).with_(precision=precision)
+    gpu, tr = both(cfg, 3, cfg.max_inflight, seed=9)
+    worst = compare_stage(cfg, gpu, tr, check_dw=False)
+    print(f"degenerate {shape} prec={precision}:", {k: f"{v:.2e}" for k, v in worst.items()})
