@@ -72,10 +72,14 @@ int k2bw_bias_grad(int dtype, int rows, int n, const void* y, float* out, int ac
  * mask_mode 0 none, 1 causal (key j <= query i), 2 key padding (key j < seqlens[n]). */
 int k2bw_attention_fwd(int dtype, int b, int s, int a, int dh, int mask_mode, const int32_t* seqlens,
                        const void* qkv, void* o, float* lse, void* stream);
-/* dqkv: [b*s, 3h]; delta: fp32 scratch [b,a,s]. */
+/* dqkv: [b*s, 3h]; delta: fp32 scratch [b,a,s].  dbias_qkv (bf16 with head size 32, 64, 80 or 128
+ * only; may be NULL): fp32 [3h] = (accumulate ? dbias_qkv : 0) + column sums of dqkv, taken from
+ * the fp32 values inside the kernels; workspace: k2bw_attention_bwd_workspace(b, s, a, dh) floats,
+ * needed iff dbias_qkv is given. */
+int64_t k2bw_attention_bwd_workspace(int b, int s, int a, int dh);
 int k2bw_attention_bwd(int dtype, int b, int s, int a, int dh, int mask_mode, const int32_t* seqlens,
                        const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
-                       float* delta, void* stream);
+                       float* delta, float* dbias_qkv, int accumulate, float* workspace, void* stream);
 
 /* One Adam step over n parameters (n multiple of 4) from the coalesced sum G, g = G/m_micro:
  * moments updated in place; w_next = w_cur - lr*mhat/(sqrt(vhat)+eps) with bias correction for

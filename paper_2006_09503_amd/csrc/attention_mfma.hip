@@ -24,6 +24,8 @@
 // ds_read_b64_tr_b16, columns as MFMA rows (the transposed operands K^T, V^T, Q^T, dO^T), so no
 // transposed copy is ever built.  16-byte chunks are XOR-swizzled by row so that both read
 // patterns are bank-conflict free.  Masked keys get probability exactly zero.
+#include <type_traits>
+
 #include "kernels.hpp"
 
 namespace k2bw {
@@ -171,6 +173,49 @@ __device__ __forceinline__ uint2 pack4f(float a, float b, float c, float d) {
   return make_uint2(pack_bf16x2(a, b), pack_bf16x2(c, d));
 }
 
+// Sum of v over the 16 lanes of a DPP row, left in every lane of the row: two quad permutes, then
+// the half-row and full-row mirrors (each step adds a lane that holds the other group's sum).
+__device__ __forceinline__ float row16_sum(float v) {
+  auto dpp_add = [](float x, auto ctrl) {
+    const int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value, 0xF, 0xF, false);
+    return x + __builtin_bit_cast(float, y);
+  };
+  v = dpp_add(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1,0,3,2]
+  v = dpp_add(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2,3,0,1]
+  v = dpp_add(v, std::integral_constant<int, 0x141>{});   // row_half_mirror
+  v = dpp_add(v, std::integral_constant<int, 0x140>{});   // row_mirror
+  return v;
+}
+
+// Column sums over the workgroup's rows of a result held as acc[db][r] (lane = row, registers =
+// head columns db*32 + 8*(r/4) + 4*hf + r%4), scaled by `scale`, written to out[0 .. DH).
+// red: 16 * DHP floats of LDS that no wave still reads (one partial row per 16 lanes).
+template <int DH>
+__device__ __forceinline__ void block_column_sums(const f32x16 (&acc)[Cfg<DH>::DB], float scale, float* red, float* out,
+                                                  int tid, int lane, int wave) {
+  using C = Cfg<DH>;
+  const int hf = lane >> 5;
+  float* mine = red + (wave * 2 + ((lane >> 4) & 1)) * C::DHP + 4 * hf;
+#pragma unroll
+  for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      float4 v;
+      v.x = row16_sum(acc[db][4 * g]);
+      v.y = row16_sum(acc[db][4 * g + 1]);
+      v.z = row16_sum(acc[db][4 * g + 2]);
+      v.w = row16_sum(acc[db][4 * g + 3]);
+      if ((lane & 15) == 0) *reinterpret_cast<float4*>(mine + db * 32 + 8 * g) = v;
+    }
+  __syncthreads();
+  for (int d = tid; d < DH; d += kThreads) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < 2 * kWaves; ++w) t += red[w * C::DHP + d];
+    out[d] = t * scale;
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // forward
 template <int DH>
@@ -293,7 +338,8 @@ template <int DH>
 __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
                                                                  const bf16_t* __restrict__ d_o, const float* __restrict__ lse,
                                                                  float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s,
-                                                                 int a, int mask_mode, const int32_t* __restrict__ seqlens) {
+                                                                 int a, int mask_mode, const int32_t* __restrict__ seqlens,
+                                                                 float* __restrict__ colsum) {
   using C = Cfg<DH>;
   extern __shared__ uint4 smem[];   // stage st: K tile at st * 2 * kTileU4, V tile behind it
 
@@ -386,6 +432,11 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dq_mfma_ker
       for (int kk = 0; kk < 4; ++kk)
         dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_cols<DH>(k_lds, db * 32, kk, lane), dsb[kk], dq[db], 0, 0, 0);
   }
+  if (colsum) {   // rows past the end of the sequence hold zeros
+    __syncthreads();   // every wave is done with the K / V tiles
+    float* row = colsum + ((int64_t)n * gridDim.x + blockIdx.x) * ld + head * DH;
+    block_column_sums<DH>(dq, scale, reinterpret_cast<float*>(smem), row, tid, lane, wave);
+  }
   if (!row_ok) return;
   bf16_t* out = dqkv + ((int64_t)n * s + i) * ld + head * DH;
 #pragma unroll
@@ -405,7 +456,7 @@ template <int DH>
 __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dkv_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
                                                                   const float* __restrict__ lse, const float* __restrict__ delta,
                                                                   bf16_t* __restrict__ dqkv, int s, int a, int mask_mode,
-                                                                  const int32_t* __restrict__ seqlens) {
+                                                                  const int32_t* __restrict__ seqlens, float* __restrict__ colsum) {
   using C = Cfg<DH>;
   extern __shared__ uint4 smem[];
   // stage st: Q tile, dO tile, 64 lse, 64 delta
@@ -502,6 +553,14 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dkv_mfma_ke
       }
     }
   }
+  if (colsum) {   // masked and non-existent keys hold zeros
+    float* row = colsum + ((int64_t)n * gridDim.x + blockIdx.x) * ld + head * DH;
+    float* red = reinterpret_cast<float*>(smem);
+    __syncthreads();
+    block_column_sums<DH>(dk, scale, red, row + h, tid, lane, wave);
+    __syncthreads();
+    block_column_sums<DH>(dv, 1.0f, red, row + 2 * h, tid, lane, wave);
+  }
   if (!row_ok) return;
   bf16_t* outk = dqkv + ((int64_t)n * s + j) * ld + h + head * DH;
   bf16_t* outv = outk + h;
@@ -554,14 +613,16 @@ hipError_t bwd_launch(const AttnDesc& d, const void* qkv, const void* o, const f
   dim3 grid(ceil_div(d.s, kBlockRows), d.a, d.b);
   hipLaunchKernelGGL(attn_dq_mfma_kernel<DH>, grid, dim3(kThreads), lds_dq, st, static_cast<const bf16_t*>(qkv),
                      static_cast<const bf16_t*>(o), static_cast<const bf16_t*>(d_o), lse, delta,
-                     static_cast<bf16_t*>(dqkv), d.s, d.a, d.mask_mode, d.seqlens);
+                     static_cast<bf16_t*>(dqkv), d.s, d.a, d.mask_mode, d.seqlens, d.colsum_partial);
   hipLaunchKernelGGL(attn_dkv_mfma_kernel<DH>, grid, dim3(kThreads), lds_dkv, st, static_cast<const bf16_t*>(qkv),
                      static_cast<const bf16_t*>(d_o), lse, delta, static_cast<bf16_t*>(dqkv), d.s, d.a, d.mask_mode,
-                     d.seqlens);
+                     d.seqlens, d.colsum_partial);
   return hipGetLastError();
 }
 
 }  // namespace
+
+int attention_colsum_rows(int b, int s) { return b * ceil_div(s, kBlockRows); }
 
 bool attention_mfma_supported(const AttnDesc& d) {
   return d.dtype == kBF16 && (d.dh == 32 || d.dh == 64 || d.dh == 80 || d.dh == 128);

@@ -12,7 +12,6 @@ void gemm_bf16_kernel_name(const GemmDesc* d, int count, char* out, size_t cap);
 hipError_t attention_fwd_simple(const AttnDesc& d, const void* qkv, void* o, float* lse, hipStream_t st);
 hipError_t attention_bwd_simple(const AttnDesc& d, const void* qkv, const void* o, const float* lse,
                                 const void* d_o, void* dqkv, float* delta, hipStream_t st);
-bool attention_mfma_supported(const AttnDesc& d);
 hipError_t attention_fwd_mfma(const AttnDesc& d, const void* qkv, void* o, float* lse, hipStream_t st);
 hipError_t attention_bwd_mfma(const AttnDesc& d, const void* qkv, const void* o, const float* lse,
                               const void* d_o, void* dqkv, float* delta, hipStream_t st);
@@ -93,6 +92,7 @@ hipError_t attention_bwd(const AttnDesc& d, const void* qkv, const void* o, cons
   if (!qkv || !o || !lse || !d_o || !dqkv || !delta) return hipErrorInvalidValue;
   if (!aligned16(qkv) || !aligned16(o) || !aligned16(d_o) || !aligned16(dqkv)) return hipErrorInvalidValue;
   if (attention_mfma_supported(d)) return attention_bwd_mfma(d, qkv, o, lse, d_o, dqkv, delta, stream);
+  if (d.colsum_partial) return hipErrorInvalidValue;   // only the MFMA kernels produce the column sums
   return attention_bwd_simple(d, qkv, o, lse, d_o, dqkv, delta, stream);
 }
 

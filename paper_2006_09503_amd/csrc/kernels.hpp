@@ -87,7 +87,13 @@ struct AttnDesc {
   int mask_mode = 0;
   const int32_t* seqlens = nullptr;
   int dtype = kF32;
+  // backward, bf16 only: if set, fp32 [attention_colsum_rows(b, s)][3h] receives per-workgroup column
+  // sums of dQ | dK | dV (before rounding to bf16): the bias gradient of the QKV projection,
+  // reduced afterwards with colsum_finalize
+  float* colsum_partial = nullptr;
 };
+int attention_colsum_rows(int b, int s);
+bool attention_mfma_supported(const AttnDesc& d);   // bf16 with head size 32, 64, 80 or 128
 hipError_t attention_fwd(const AttnDesc& d, const void* qkv, void* o, float* lse,
                          hipStream_t stream);
 // dqkv: [b*s, 3h]; delta: scratch [b, a, s] fp32 (rowsum(dO*O)).

@@ -95,10 +95,20 @@ int k2bw_attention_fwd(int dtype, int b, int s, int a, int dh, int mask_mode, co
 
 int k2bw_attention_bwd(int dtype, int b, int s, int a, int dh, int mask_mode, const int32_t* seqlens,
                        const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta,
-                       void* stream) {
+                       float* dbias_qkv, int accumulate, float* workspace, void* stream) {
   AttnDesc d;
   d.b = b; d.s = s; d.a = a; d.dh = dh; d.mask_mode = mask_mode; d.seqlens = seqlens; d.dtype = dtype;
-  return rc_of(attention_bwd(d, qkv, o, lse, d_o, dqkv, delta, static_cast<hipStream_t>(stream)));
+  if (dbias_qkv && (!workspace || !attention_mfma_supported(d))) return STAGE_ERR_INVALID_ARG;
+  d.colsum_partial = dbias_qkv ? workspace : nullptr;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = attention_bwd(d, qkv, o, lse, d_o, dqkv, delta, st);
+  if (e != hipSuccess || !dbias_qkv) return rc_of(e);
+  return rc_of(colsum_finalize(workspace, attention_colsum_rows(b, s), 3 * a * dh, dbias_qkv, accumulate != 0, st));
+}
+
+int64_t k2bw_attention_bwd_workspace(int b, int s, int a, int dh) {
+  if (b <= 0 || s <= 0 || a <= 0 || dh <= 0) return STAGE_ERR_INVALID_ARG;
+  return (int64_t)attention_colsum_rows(b, s) * 3 * a * dh;
 }
 
 int k2bw_adam(int64_t n, const float* w_cur, float* w_next, void* w_next_bf16, float* m, float* v, const float* G,

@@ -82,6 +82,7 @@ struct stage2bw {
   std::vector<char*> dx1, dchain, du, dqkv;
   char* y_scratch = nullptr;  // recompute: output of the re-run forward
   float *delta = nullptr, *ln_partial = nullptr, *ln_partial2 = nullptr, *cs_partial = nullptr, *du_partial = nullptr;
+  float* attn_partial = nullptr;
 
   // timing
   bool timing = false;
@@ -340,8 +341,8 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     // Bias gradients are column sums of the four projection-output gradients.  Three of them come
     // out of the kernels that produce those gradients: dx1 and this layer's result dx (= the next
     // lower layer's dy) from the LayerNorm backward kernels, du (bf16 mode) from the epilogue of
-    // the GEMM that computes it; dqkv, the stage's incoming dy and du in fp32 mode are summed by
-    // the column-sum kernel.  One reduction launch per layer finishes all of them.
+    // the GEMM that computes it, dqkv (bf16 mode) from the attention backward kernels; the stage's
+    // incoming dy, and du and dqkv in fp32 mode, are summed by the column-sum kernel.  One reduction launch per layer finishes all of them.
     const bool fused_du = st->dtype == kBF16;
     auto dgrad = [&](const void* grad, int N, const char* w_, int K, void* out, const void* u) {
       // out[T,K] = grad[T,N] * W[K,N]^T
@@ -366,8 +367,11 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     e = wgrad(A.o, h, dx1, h, st->G + o.wo);                             if (e != hipSuccess) return e;
     e = dgrad(dx1, h, wptr(st, buf, o.wo), h, st->tmp_h, nullptr);       if (e != hipSuccess) return e;
     // attention
+    AttnDesc ad = attn_desc(st, lens);
+    const bool fused_dqkv = attention_mfma_supported(ad);
+    if (fused_dqkv) ad.colsum_partial = st->attn_partial;
     e = timed(st, STAGE_K_ATTN_BWD, "attention backward (dq + dkv kernels)", attn_flops, 0.0, [&] {
-      return attention_bwd(attn_desc(st, lens), A.qkv, A.o, A.lse, st->tmp_h, dqkv, st->delta, st->stream);
+      return attention_bwd(ad, A.qkv, A.o, A.lse, st->tmp_h, dqkv, st->delta, st->stream);
     });
     if (e != hipSuccess) return e;
     // qkv = a Wqkv + bqkv
@@ -377,15 +381,17 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     e = run_ln_bwd(st, st->tmp_h, A.x, A.mean1, A.rstd1, wptr(st, buf, o.ln1_g), dx1, dx, st->ln_partial2, &ln1_parts);
     if (e != hipSuccess) return e;
     ColsumItem cs[3];
-    int n_cs = 0, col_dqkv = 0, col_du = -1, col_dy = -1, cols = 0;
-    cs[n_cs++] = {dqkv, 3 * h, 3 * h}; cols += 3 * h;
+    int n_cs = 0, col_dqkv = -1, col_du = -1, col_dy = -1, cols = 0;
+    if (!fused_dqkv) { col_dqkv = cols; cs[n_cs++] = {dqkv, 3 * h, 3 * h}; cols += 3 * h; }
     if (!fused_du) { col_du = cols; cs[n_cs++] = {du, f, f}; cols += f; }
     if (l == c.n_layers - 1) { col_dy = cols; cs[n_cs++] = {dy, h, h}; cols += h; }
     int cs_parts = 0, cs_cols = 0;
-    e = timed(st, STAGE_K_BIAS_GRAD, "colsum_partial_grouped_kernel", 0.0, (double)T * cols * st->esize, [&] {
-      return colsum_partial_grouped(cs, n_cs, T, st->cs_partial, &cs_parts, &cs_cols, st->dtype, st->stream);
-    });
-    if (e != hipSuccess) return e;
+    if (n_cs > 0) {
+      e = timed(st, STAGE_K_BIAS_GRAD, "colsum_partial_grouped_kernel", 0.0, (double)T * cols * st->esize, [&] {
+        return colsum_partial_grouped(cs, n_cs, T, st->cs_partial, &cs_parts, &cs_cols, st->dtype, st->stream);
+      });
+      if (e != hipSuccess) return e;
+    }
     FinalizeItem fin[8];
     int n_fin = 0;
     double fin_elems = 0.0;
@@ -393,7 +399,8 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
       fin[n_fin++] = {partial, parts, ld, n, out};
       fin_elems += (double)parts * n;
     };
-    add_fin(st->cs_partial + col_dqkv, cs_parts, cs_cols, 3 * h, st->G + o.bqkv);
+    if (fused_dqkv) add_fin(st->attn_partial, attention_colsum_rows(c.microbatch, c.seq), 3 * h, 3 * h, st->G + o.bqkv);
+    else add_fin(st->cs_partial + col_dqkv, cs_parts, cs_cols, 3 * h, st->G + o.bqkv);
     if (fused_du) add_fin(st->du_partial, (T + 31) / 32, f, f, st->G + o.b1);
     else add_fin(st->cs_partial + col_du, cs_parts, cs_cols, f, st->G + o.b1);
     if (col_dy >= 0) add_fin(st->cs_partial + col_dy, cs_parts, cs_cols, h, st->G + o.b2);
@@ -503,6 +510,7 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
   ALLOC(st->ln_partial, (int64_t)ln_bwd_max_parts() * 3 * h * 4, nullptr);
   ALLOC(st->ln_partial2, (int64_t)ln_bwd_max_parts() * 3 * h * 4, nullptr);
   ALLOC(st->du_partial, (int64_t)((T + 31) / 32) * f * 4, nullptr);
+  ALLOC(st->attn_partial, (int64_t)attention_colsum_rows(cfg->microbatch, cfg->seq) * 3 * h * 4, nullptr);
   ALLOC(st->cs_partial, (int64_t)colsum_max_parts() * (5 * h + f) * 4, nullptr);
 #undef ALLOC
 
