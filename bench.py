@@ -141,6 +141,10 @@ def main():
     ap.add_argument("--recompute", type=int, default=None, help="override the workload's activation recomputation (0/1)")
     ap.add_argument("--stages", type=int, default=1, help="d > 1: a d-stage 2BW pipeline of such stages in this process, one "
                     "HIP stream per stage, squared-error loss behind the last (an extra measurement, not the headline)")
+    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
+                    help="2: backward passes and updates on a stream of their own, so that the forward and backward "
+                         "passes of different microbatches overlap (the per-kernel timing region always runs on one "
+                         "stream: each kernel then has the GPU to itself)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
@@ -170,7 +174,11 @@ def main():
     if args.stages > 1:
         pipeline_bench(args, cfg, w0)
         return
-    st = B.Stage(cfg, w0)
+    fwd_stream = torch.cuda.Stream()
+    st = B.Stage(cfg, w0, fwd_stream)
+    if args.streams == 2:
+        bwd_stream = torch.cuda.Stream()
+        st.set_backward_stream(bwd_stream)
     del w0
     # a pool of m distinct microbatches, resident in HBM, reused batch after batch
     dt = torch.bfloat16 if cfg.precision == synth.PREC_BF16 else torch.float32
@@ -188,10 +196,12 @@ def main():
     Y = [torch.empty(shape, device="cuda", dtype=dt) for _ in range(p + 1)]
     DX = torch.empty(shape, device="cuda", dtype=dt)
 
+    drained = [0]   # microbatches up to this one have had their backward pass (see drain())
+
     def iteration(k):
         """One slot of the worker's 1F1B stream: backward of k-p, maybe update, maybe swap, forward of k."""
         kb = k - p
-        if kb >= 1:
+        if kb > drained[0]:
             st.backward(kb, DY[(kb - 1) % m], DX)
             if kb % m == 0:
                 st.coalesce_update()
@@ -209,6 +219,16 @@ def main():
         for k in range(first + m - p, first + m):
             st.backward(k, DY[(k - 1) % m], DX)
         st.coalesce_update()
+
+    def drain(last):
+        """Backward passes of the microbatches still in flight after forward pass `last` (a batch end)."""
+        if not cfg.flush:
+            for kb in range(max(last - p, drained[0]) + 1, last + 1):
+                st.backward(kb, DY[(kb - 1) % m], DX)
+                if kb % m == 0:
+                    st.coalesce_update()
+        drained[0] = last
+        torch.cuda.synchronize()
 
     def run_steps(first_step, n_steps):
         torch.cuda.synchronize()
@@ -230,10 +250,19 @@ def main():
     tflops = flops_step * K / elapsed / 1e12
 
     roofline, kernels = None, None
+    steps_done = W + K
     if not args.no_kernel_timing:
+        # Per-kernel durations (HIP events around every launch, on the stream it is launched on) come
+        # from a second region of K steps on ONE stream, where each kernel has the GPU to itself;
+        # one untimed batch refills the pipeline after the switch.
+        if args.streams == 2:
+            drain(steps_done * m)
+            st.set_backward_stream(fwd_stream)
+        run_steps(steps_done, 1)
         launches_per_step = m * cfg.n_layers * 64 + 16
         st.timing_enable(True, launches_per_step * K + 64)
-        run_steps(W + K, K)
+        run_steps(steps_done + 1, K)
+        steps_done += 1 + K
         per_kernel = st.timing_collect_kernels()
         tm = st.timing_collect()
         st.timing_enable(False)
@@ -268,13 +297,7 @@ def main():
                                    for n, v in per_kernel.items()}
 
     # drain the microbatches still in flight so the stage ends at a batch boundary
-    last = (W + K + (0 if args.no_kernel_timing else K)) * m
-    if not cfg.flush:
-        for kb in range(last - p + 1, last + 1):
-            st.backward(kb, DY[(kb - 1) % m], DX)
-            if kb % m == 0:
-                st.coalesce_update()
-    torch.cuda.synchronize()
+    drain(steps_done * m)
     finite = bool(torch.isfinite(DX.float()).all().item())
     alloc = st.query(B.Q_BYTES_ALLOCATED)
     st.close()
@@ -287,7 +310,7 @@ def main():
         "config": {"workload": f"{args.workload}: one pipeline stage, L={cfg.n_layers} h={cfg.hidden} a={cfg.n_heads} "
                                f"f={cfg.ffn} s={cfg.seq} b={cfg.microbatch} m={cfg.m} inflight={p} "
                                f"mask={('none', 'causal', 'padding')[cfg.mask_mode]} recompute={cfg.recompute} "
-                               f"schedule={'flush' if cfg.flush else '2bw'}",
+                               f"schedule={'flush' if cfg.flush else '2bw'} streams={args.streams}",
                    "samples_per_step": cfg.microbatch * m, "model_flops_per_step": flops_step,
                    "stage_bytes_allocated": alloc},
         "model_tflops": tflops, "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS, "outputs_finite": finite,

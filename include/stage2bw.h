@@ -137,9 +137,27 @@ int stage_coalesce_update(stage_t* st);
  */
 int stage_swap_versions(stage_t* st);
 
+/*
+ * Run backward passes and updates on a stream of their own, so that in 1F1B steady state
+ * (Section 3.1, Figure 2: a stage alternates forward and backward passes of different
+ * microbatches) the two passes overlap on the GPU instead of taking turns.  After this call
+ * stage_backward and stage_coalesce_update enqueue on hip_stream, stage_forward stays on the
+ * stream given to stage_create.  The stage orders its own state across the two streams: a
+ * backward pass after the forward pass of its microbatch, the reuse of a stash slot after the
+ * backward pass that read it, a forward pass after the update that wrote the version it
+ * reads.  The caller orders its own buffers: dy_dev must be complete on hip_stream when
+ * stage_backward is called, dx_dev is complete there; x_dev / y_dev likewise on the forward
+ * stream.  Results are the same as with one stream.  hip_stream equal to the creation stream
+ * returns to one stream.  With recompute this allocates one more activation set (the forward
+ * pass needs scratch of its own).  BAD_STATE while microbatches are in flight or gradients
+ * wait for an update; the call synchronises both streams.  Errors: INVALID_ARG, BAD_STATE, OOM,
+ * HIP.
+ */
+int stage_set_backward_stream(stage_t* st, void* hip_stream);
+
 int stage_destroy(stage_t* st);
 
-/* ---- inspection, for parity tests; each synchronises the stream ------------------------- */
+/* ---- inspection, for parity tests; each synchronises the stage's streams ---------------- */
 
 enum { STAGE_WEIGHTS_BUF0 = 0, STAGE_WEIGHTS_BUF1 = 1, STAGE_WEIGHTS_MASTER = 2 };
 /* which: one of the two version buffers (converted to fp32), or the fp32 master (in fp32 mode

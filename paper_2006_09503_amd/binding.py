@@ -69,6 +69,7 @@ def lib() -> C.CDLL:
             "stage_backward": (C.c_int, [vp, i64, vp, vp]),
             "stage_coalesce_update": (C.c_int, [vp]),
             "stage_swap_versions": (C.c_int, [vp]),
+            "stage_set_backward_stream": (C.c_int, [vp, vp]),
             "stage_destroy": (C.c_int, [vp]),
             "stage_read_weights": (C.c_int, [vp, C.c_int, vp]),
             "stage_read_grad_accum": (C.c_int, [vp, vp]),
@@ -187,6 +188,10 @@ def stage_coalesce_update(st: int):
 
 def stage_swap_versions(st: int):
     _check(lib().stage_swap_versions(st), "stage_swap_versions")
+
+
+def stage_set_backward_stream(st: int, stream):
+    _check(lib().stage_set_backward_stream(st, _stream_ptr(stream)), "stage_set_backward_stream")
 
 
 def stage_destroy(st: int):
@@ -308,6 +313,7 @@ class Stage:
     def backward(self, mb, dy, dx): stage_backward(self.h, mb, dy, dx)
     def coalesce_update(self): stage_coalesce_update(self.h)
     def swap_versions(self): stage_swap_versions(self.h)
+    def set_backward_stream(self, stream): stage_set_backward_stream(self.h, stream)
     def query(self, what): return stage_query(self.h, what)
     def read_weights(self, which): return stage_read_weights(self.h, which, self.n_params)
     def read_grad_accum(self): return stage_read_grad_accum(self.h, self.n_params)

@@ -53,7 +53,16 @@ struct EventPair {
 
 struct stage2bw {
   stage_config_t cfg;
-  hipStream_t stream = nullptr;
+  hipStream_t stream = nullptr;    // forward passes (and everything else until a backward stream is set)
+  hipStream_t bstream = nullptr;   // backward passes and updates
+  hipStream_t cur = nullptr;       // the stream the running call enqueues on
+  bool two_streams = false;
+  // two-stream ordering: per stash slot "forward written" / "backward has read"; per version
+  // buffer "update has written"
+  std::vector<hipEvent_t> fwd_done, bwd_done;
+  std::vector<char> bwd_pending;
+  hipEvent_t ver_ready[2] = {nullptr, nullptr};
+  bool ver_pending[2] = {false, false};
   Schedule sched;
   int64_t P = 0;
   int T = 0;
@@ -204,12 +213,12 @@ hipError_t timed(stage2bw* st, int cls, const char* name, double flops, double b
     ev = &st->events[st->events_used++];
     ev->cls = cls; ev->flops = flops; ev->bytes = bytes;
     std::snprintf(ev->name, sizeof(ev->name), "%s", name);
-    hipError_t e = hipEventRecord(ev->start, st->stream);
+    hipError_t e = hipEventRecord(ev->start, st->cur);
     if (e != hipSuccess) return e;
   }
   hipError_t e = launch();
   if (e != hipSuccess) return e;
-  if (ev) return hipEventRecord(ev->stop, st->stream);
+  if (ev) return hipEventRecord(ev->stop, st->cur);
   return hipSuccess;
 }
 
@@ -220,14 +229,14 @@ const char* wptr(const stage2bw* st, int buffer, int64_t elem_off) {
 hipError_t run_gemm(stage2bw* st, int cls, const GemmDesc& d) {
   char name[96] = "";
   if (st->timing) gemm_kernel_name(&d, 1, name, sizeof(name));
-  return timed(st, cls, name, 2.0 * d.M * d.N * d.K, 0.0, [&] { return gemm(d, st->stream); });
+  return timed(st, cls, name, 2.0 * d.M * d.N * d.K, 0.0, [&] { return gemm(d, st->cur); });
 }
 
 hipError_t run_ln_fwd(stage2bw* st, const void* x, const void* gain, const void* shift, void* y, float* mean,
                       float* rstd) {
   const double bytes = 2.0 * st->T * st->cfg.hidden * st->esize + 8.0 * st->T;
   return timed(st, STAGE_K_LN_FWD, "ln_fwd_kernel", 0.0, bytes, [&] {
-    return layernorm_fwd(x, gain, shift, y, mean, rstd, st->T, st->cfg.hidden, st->cfg.ln_eps, st->dtype, st->stream);
+    return layernorm_fwd(x, gain, shift, y, mean, rstd, st->T, st->cfg.hidden, st->cfg.ln_eps, st->dtype, st->cur);
   });
 }
 
@@ -238,7 +247,7 @@ hipError_t run_ln_bwd(stage2bw* st, const void* dy, const void* x, const float* 
   const int h = st->cfg.hidden;
   const double bytes = 4.0 * st->T * h * st->esize + 8.0 * st->T;
   return timed(st, STAGE_K_LN_BWD, "ln_bwd_kernel", 0.0, bytes, [&] {
-    return layernorm_bwd(dy, x, mean, rstd, gain, dres, dx, partial, parts, st->T, h, st->dtype, st->stream);
+    return layernorm_bwd(dy, x, mean, rstd, gain, dres, dx, partial, parts, st->T, h, st->dtype, st->cur);
   });
 }
 
@@ -268,7 +277,7 @@ hipError_t run_forward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens,
     e = run_gemm(st, STAGE_K_GEMM_FWD, g);
     if (e != hipSuccess) return e;
     e = timed(st, STAGE_K_ATTN_FWD, st->dtype == kBF16 ? "attn_fwd_mfma_kernel" : "attn_fwd_simple", attn_flops, 0.0, [&] {
-      return attention_fwd(attn_desc(st, lens), A.qkv, A.o, A.lse, st->stream);
+      return attention_fwd(attn_desc(st, lens), A.qkv, A.o, A.lse, st->cur);
     });
     if (e != hipSuccess) return e;
     g = GemmDesc();
@@ -318,7 +327,7 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
       for (int i = 0; i < n; ++i) flops += 2.0 * wg[i0 + i].M * (double)wg[i0 + i].N * wg[i0 + i].K;
       char wg_name[96] = "";
       if (st->timing) gemm_kernel_name(&wg[i0], n, wg_name, sizeof(wg_name));
-      hipError_t e = timed(st, STAGE_K_GEMM_WGRAD, wg_name, flops, 0.0, [&] { return gemm_grouped(&wg[i0], n, st->stream); });
+      hipError_t e = timed(st, STAGE_K_GEMM_WGRAD, wg_name, flops, 0.0, [&] { return gemm_grouped(&wg[i0], n, st->cur); });
       if (e != hipSuccess) return e;
     }
     wg.clear();
@@ -371,7 +380,7 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     const bool fused_dqkv = attention_mfma_supported(ad);
     if (fused_dqkv) ad.colsum_partial = st->attn_partial;
     e = timed(st, STAGE_K_ATTN_BWD, "attention backward (dq + dkv kernels)", attn_flops, 0.0, [&] {
-      return attention_bwd(ad, A.qkv, A.o, A.lse, st->tmp_h, dqkv, st->delta, st->stream);
+      return attention_bwd(ad, A.qkv, A.o, A.lse, st->tmp_h, dqkv, st->delta, st->cur);
     });
     if (e != hipSuccess) return e;
     // qkv = a Wqkv + bqkv
@@ -388,7 +397,7 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     int cs_parts = 0, cs_cols = 0;
     if (n_cs > 0) {
       e = timed(st, STAGE_K_BIAS_GRAD, "colsum_partial_grouped_kernel", 0.0, (double)T * cols * st->esize, [&] {
-        return colsum_partial_grouped(cs, n_cs, T, st->cs_partial, &cs_parts, &cs_cols, st->dtype, st->stream);
+        return colsum_partial_grouped(cs, n_cs, T, st->cs_partial, &cs_parts, &cs_cols, st->dtype, st->cur);
       });
       if (e != hipSuccess) return e;
     }
@@ -409,7 +418,7 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     add_fin(st->ln_partial2, ln1_parts, 3 * h, 2 * h, st->G + o.ln1_g);
     if (l > 0) add_fin(st->ln_partial2 + 2 * h, ln1_parts, 3 * h, h, st->G + st->off[l - 1].b2);
     e = timed(st, STAGE_K_BIAS_GRAD, "colsum_finalize_grouped_kernel", 0.0, 4.0 * fin_elems, [&] {
-      return colsum_finalize_grouped(fin, n_fin, acc, st->stream);
+      return colsum_finalize_grouped(fin, n_fin, acc, st->cur);
     });
     if (e != hipSuccess) return e;
     dy = dx;
@@ -427,7 +436,19 @@ int free_all(stage2bw* st) {
     (void)hipEventDestroy(e.stop);
   }
   st->events.clear();
+  for (hipEvent_t e : st->fwd_done) (void)hipEventDestroy(e);
+  for (hipEvent_t e : st->bwd_done) (void)hipEventDestroy(e);
+  st->fwd_done.clear();
+  st->bwd_done.clear();
+  for (hipEvent_t& e : st->ver_ready)
+    if (e) { (void)hipEventDestroy(e); e = nullptr; }
   return rc;
+}
+
+hipError_t sync_all(stage2bw* st) {
+  hipError_t e = hipStreamSynchronize(st->stream);
+  if (e == hipSuccess && st->two_streams) e = hipStreamSynchronize(st->bstream);
+  return e;
 }
 
 }  // namespace
@@ -455,7 +476,7 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
   }
   stage2bw* st = new (std::nothrow) stage2bw(*cfg);
   if (!st) return STAGE_ERR_OOM;
-  st->stream = static_cast<hipStream_t>(hip_stream);
+  st->stream = st->bstream = st->cur = static_cast<hipStream_t>(hip_stream);
   st->P = cfg->n_layers * layer_params(cfg->hidden, cfg->ffn);
   st->T = cfg->microbatch * cfg->seq;
   st->dtype = cfg->precision == STAGE_PREC_BF16 ? kBF16 : kF32;
@@ -545,7 +566,14 @@ int stage_forward(stage_t* st, int64_t mb, const void* x_dev, const int32_t* seq
   if (rc != STAGE_OK) return rc;
   const int buf = st->sched.buffer_of(st->sched.read_version());
   const int64_t in_bytes = (int64_t)st->T * st->cfg.hidden * st->esize;
-  ActSet& acts = st->cfg.recompute ? st->slot_acts[0] : st->slot_acts[slot];
+  st->cur = st->stream;
+  if (st->two_streams) {
+    // the slot's previous occupant has been read by its backward pass; the version has been written
+    if (st->bwd_pending[slot]) { HIP_TRY(hipStreamWaitEvent(st->stream, st->bwd_done[slot], 0)); st->bwd_pending[slot] = 0; }
+    if (st->ver_pending[buf]) { HIP_TRY(hipStreamWaitEvent(st->stream, st->ver_ready[buf], 0)); st->ver_pending[buf] = false; }
+  }
+  // with recomputation and two streams the forward pass has a scratch activation set of its own
+  ActSet& acts = st->cfg.recompute ? st->slot_acts[st->two_streams ? 1 : 0] : st->slot_acts[slot];
   // stash the stage input (with recompute it is the only thing kept)
   char* x_keep = st->cfg.recompute ? st->slot_x0[slot] : acts.layer[0].x;
   HIP_TRY(timed(st, STAGE_K_OTHER, "copy16_kernel", 0.0, 2.0 * in_bytes, [&] { return copy_bytes(x_dev, x_keep, in_bytes, st->stream); }));
@@ -565,6 +593,7 @@ int stage_forward(stage_t* st, int64_t mb, const void* x_dev, const int32_t* seq
   } else {
     HIP_TRY(run_forward(st, buf, acts, lens, y_dev));
   }
+  if (st->two_streams) HIP_TRY(hipEventRecord(st->fwd_done[slot], st->stream));
   int64_t version = 0;
   int b2 = 0;
   return st->sched.forward(mb, &slot, &version, &b2);
@@ -582,6 +611,8 @@ int stage_backward(stage_t* st, int64_t mb, const void* dy_dev, void* dx_dev) {
   rc = st->sched.backward(mb, &slot, &version, &buf, &first);
   if (rc != STAGE_OK) return rc;
   const int32_t* lens = st->cfg.mask_mode == STAGE_MASK_PADDING ? st->slot_lens[slot] : nullptr;
+  st->cur = st->bstream;
+  if (st->two_streams) HIP_TRY(hipStreamWaitEvent(st->bstream, st->fwd_done[slot], 0));
   if (st->cfg.recompute) {
     // re-run the forward on the version tagged at the forward pass (Section 4.1 with Section 3.1)
     ActSet& acts = st->slot_acts[0];
@@ -594,6 +625,10 @@ int stage_backward(stage_t* st, int64_t mb, const void* dy_dev, void* dx_dev) {
   } else {
     HIP_TRY(run_backward(st, buf, st->slot_acts[slot], lens, dy_dev, dx_dev, first != 0));
   }
+  if (st->two_streams) {
+    HIP_TRY(hipEventRecord(st->bwd_done[slot], st->bstream));
+    st->bwd_pending[slot] = 1;
+  }
   return STAGE_OK;
 }
 
@@ -605,6 +640,7 @@ int stage_coalesce_update(stage_t* st) {
   int64_t step = 0;
   rc = st->sched.coalesce_update(&rb, &wb, &step);
   if (rc != STAGE_OK) return rc;
+  st->cur = st->bstream;
   AdamDesc d;
   d.n = st->P; d.m = st->adam_m; d.v = st->adam_v; d.G = st->G;
   d.lr = st->cfg.lr; d.beta1 = st->cfg.beta1; d.beta2 = st->cfg.beta2; d.eps = st->cfg.adam_eps;
@@ -621,10 +657,53 @@ int stage_coalesce_update(stage_t* st) {
   }
   if (st->cfg.optimizer == STAGE_OPT_MOMENTUM) {
     bytes -= 8.0 * st->P;   // no second moment
-    HIP_TRY(timed(st, STAGE_K_ADAM, "momentum_kernel", 0.0, bytes, [&] { return momentum_step(d, st->stream); }));
+    HIP_TRY(timed(st, STAGE_K_ADAM, "momentum_kernel", 0.0, bytes, [&] { return momentum_step(d, st->cur); }));
+  } else {
+    HIP_TRY(timed(st, STAGE_K_ADAM, "adam_kernel", 0.0, bytes, [&] { return adam_step(d, st->cur); }));
+  }
+  if (st->two_streams) {
+    HIP_TRY(hipEventRecord(st->ver_ready[wb], st->bstream));
+    st->ver_pending[wb] = true;
+  }
+  return STAGE_OK;
+}
+
+int stage_set_backward_stream(stage_t* st, void* hip_stream) {
+  if (!st) return STAGE_ERR_INVALID_ARG;
+  if (st->sched.inflight() != 0 || st->sched.accumulated() != 0) return STAGE_ERR_BAD_STATE;
+  HIP_TRY(sync_all(st));
+  hipStream_t b = static_cast<hipStream_t>(hip_stream);
+  if (b == st->stream) {   // back to one stream
+    st->bstream = st->stream;
+    st->two_streams = false;
     return STAGE_OK;
   }
-  HIP_TRY(timed(st, STAGE_K_ADAM, "adam_kernel", 0.0, bytes, [&] { return adam_step(d, st->stream); }));
+  if (st->fwd_done.empty()) {
+    std::vector<hipEvent_t> ev;
+    const int want = 2 * st->cfg.max_inflight + 2;
+    for (int i = 0; i < want; ++i) {
+      hipEvent_t e = nullptr;
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+        for (hipEvent_t x : ev) (void)hipEventDestroy(x);
+        return STAGE_ERR_HIP;
+      }
+      ev.push_back(e);
+    }
+    st->fwd_done.assign(ev.begin(), ev.begin() + st->cfg.max_inflight);
+    st->bwd_done.assign(ev.begin() + st->cfg.max_inflight, ev.begin() + 2 * st->cfg.max_inflight);
+    st->ver_ready[0] = ev[want - 2];
+    st->ver_ready[1] = ev[want - 1];
+    st->bwd_pending.assign(st->cfg.max_inflight, 0);
+  }
+  if (st->cfg.recompute && st->slot_acts.size() < 2) {
+    st->slot_acts.resize(2);
+    int rc = alloc_actset(st, &st->slot_acts[1]);
+    if (rc != STAGE_OK) { st->slot_acts.resize(1); return rc; }
+  }
+  std::fill(st->bwd_pending.begin(), st->bwd_pending.end(), 0);
+  st->ver_pending[0] = st->ver_pending[1] = false;
+  st->bstream = b;
+  st->two_streams = true;
   return STAGE_OK;
 }
 
@@ -635,14 +714,14 @@ int stage_swap_versions(stage_t* st) {
 
 int stage_destroy(stage_t* st) {
   if (!st) return STAGE_ERR_INVALID_ARG;
-  (void)hipStreamSynchronize(st->stream);
+  (void)sync_all(st);
   int rc = free_all(st);
   delete st;
   return rc;
 }
 
 static int read_f32(stage_t* st, const float* dev, float* host) {
-  HIP_TRY(hipStreamSynchronize(st->stream));
+  HIP_TRY(sync_all(st));
   HIP_TRY(hipMemcpy(host, dev, (size_t)st->P * 4, hipMemcpyDeviceToHost));
   return STAGE_OK;
 }
@@ -657,7 +736,7 @@ int stage_read_weights(stage_t* st, int which, float* out_host) {
   if (st->dtype == kF32) return read_f32(st, reinterpret_cast<const float*>(st->wbuf[which]), out_host);
   std::vector<uint16_t> tmp;
   try { tmp.resize((size_t)st->P); } catch (...) { return STAGE_ERR_OOM; }
-  HIP_TRY(hipStreamSynchronize(st->stream));
+  HIP_TRY(sync_all(st));
   HIP_TRY(hipMemcpy(tmp.data(), st->wbuf[which], (size_t)st->P * 2, hipMemcpyDeviceToHost));
   for (int64_t i = 0; i < st->P; ++i) {
     const uint32_t u = (uint32_t)tmp[i] << 16;
@@ -711,7 +790,7 @@ const char* stage_strerror(int code) {
 
 int stage_timing_enable(stage_t* st, int enable, int32_t capacity) {
   if (!st) return STAGE_ERR_INVALID_ARG;
-  HIP_TRY(hipStreamSynchronize(st->stream));
+  HIP_TRY(sync_all(st));
   for (EventPair& e : st->events) {
     (void)hipEventDestroy(e.start);
     (void)hipEventDestroy(e.stop);
@@ -736,7 +815,7 @@ int stage_timing_collect_kernels(stage_t* st, int32_t capacity, char* names_out,
                                  int64_t* launches_out, double* flops_out, double* bytes_out, int32_t* count_out) {
   if (!st || capacity < 1 || !names_out || !ms_out || !launches_out || !flops_out || !bytes_out || !count_out)
     return STAGE_ERR_INVALID_ARG;
-  HIP_TRY(hipStreamSynchronize(st->stream));
+  HIP_TRY(sync_all(st));
   int n = 0;
   for (size_t i = 0; i < st->events_used; ++i) {
     const EventPair& e = st->events[i];
@@ -759,7 +838,7 @@ int stage_timing_collect_kernels(stage_t* st, int32_t capacity, char* names_out,
 
 int stage_timing_collect(stage_t* st, double* ms_out, int64_t* launches_out, double* flops_out, double* bytes_out) {
   if (!st || !ms_out || !launches_out || !flops_out || !bytes_out) return STAGE_ERR_INVALID_ARG;
-  HIP_TRY(hipStreamSynchronize(st->stream));
+  HIP_TRY(sync_all(st));
   for (int i = 0; i < STAGE_K_COUNT; ++i) { ms_out[i] = 0; launches_out[i] = 0; flops_out[i] = 0; bytes_out[i] = 0; }
   for (size_t i = 0; i < st->events_used; ++i) {
     const EventPair& e = st->events[i];

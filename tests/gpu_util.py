@@ -37,10 +37,17 @@ def to_host(t: torch.Tensor) -> np.ndarray:
     return t.detach().to(torch.float32).cpu().numpy()
 
 
-def run_stage_gpu(cfg: synth.StageConfig, w0: np.ndarray, mbs, inflight: int, snapshot: bool = True):
+def run_stage_gpu(cfg: synth.StageConfig, w0: np.ndarray, mbs, inflight: int, snapshot: bool = True,
+                  two_streams: bool = False):
     """Drive the HIP stage over the microbatches; returns per-microbatch Y, dX and, per update,
-    the accumulator, Adam moments, both buffers and the master as read right after the update."""
+    the accumulator, Adam moments, both buffers and the master as read right after the update.
+    two_streams: backward passes and updates on a stream of their own."""
     st = B.Stage(cfg, w0)
+    bstream = None
+    if two_streams:
+        bstream = torch.cuda.Stream()
+        torch.cuda.synchronize()          # the inputs below are made on the current stream
+        st.set_backward_stream(bstream)
     n = len(mbs)
     shape = (cfg.microbatch, cfg.seq, cfg.hidden)
     X = {k: to_dev(mbs[k - 1][0], cfg.precision) for k in range(1, n + 1)}
@@ -50,6 +57,7 @@ def run_stage_gpu(cfg: synth.StageConfig, w0: np.ndarray, mbs, inflight: int, sn
     Y = {k: torch.full(shape, float("nan"), device="cuda", dtype=tdtype(cfg.precision)) for k in X}
     DX = {k: torch.full(shape, float("nan"), device="cuda", dtype=tdtype(cfg.precision)) for k in X}
     snaps = []
+    torch.cuda.synchronize()
 
     def on_update(t):
         if not snapshot:
@@ -63,7 +71,8 @@ def run_stage_gpu(cfg: synth.StageConfig, w0: np.ndarray, mbs, inflight: int, sn
     st.run_1f1b(1, n, lambda k: (X[k], LEN[k], DY[k]), lambda k: (Y[k], DX[k]), inflight, on_update)
     torch.cuda.synchronize()
     out = dict(Y={k: to_host(v) for k, v in Y.items()}, dX={k: to_host(v) for k, v in DX.items()}, snaps=snaps,
-               bytes=st.query(B.Q_BYTES_ALLOCATED))
+               bytes=st.query(B.Q_BYTES_ALLOCATED), final_master=st.read_weights(B.WEIGHTS_MASTER),
+               final_G=st.read_grad_accum())
     st.close()
     return out
 

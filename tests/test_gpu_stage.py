@@ -77,6 +77,43 @@ def test_inflight_depth_and_recompute_do_not_change_results(precision):
     assert rec < full
 
 
+@pytest.mark.parametrize("precision", [synth.PREC_FP32, synth.PREC_BF16])
+@pytest.mark.parametrize("variant", [dict(), dict(recompute=1), dict(flush=1), dict(mask_mode=synth.MASK_PADDING)])
+def test_backward_stream_of_its_own_gives_the_same_results(precision, variant):
+    """Backward passes and updates on a second stream (forward and backward passes of different
+    microbatches then overlap, Section 3.1's steady state): the stage orders its state across the
+    two streams, so every output and weight equals the one-stream run bit for bit, and the run with
+    per-update snapshots matches the oracle."""
+    cfg = RAGGED.with_(precision=precision, mask_mode=synth.MASK_CAUSAL, m=4, max_inflight=3).with_(**variant)
+    gen = synth.StageInputs(cfg, 5)
+    w0 = gen.weights()
+    mbs = gen.microbatches(4 * cfg.m)
+    tr = run_stage_oracle(cfg, w0, mbs)
+    compare_stage(cfg, run_stage_gpu(cfg, w0, mbs, 3, two_streams=True), tr)
+    one = run_stage_gpu(cfg, w0, mbs, 3, snapshot=False)
+    for _ in range(2):       # no host synchronisation between the calls: the streams really run ahead
+        two = run_stage_gpu(cfg, w0, mbs, 3, snapshot=False, two_streams=True)
+        for k in one["Y"]:
+            assert np.array_equal(two["Y"][k], one["Y"][k]) and np.array_equal(two["dX"][k], one["dX"][k]), k
+        assert np.array_equal(two["final_master"], one["final_master"])
+        assert np.array_equal(two["final_G"], one["final_G"])
+
+
+def test_backward_stream_can_only_be_set_between_batches():
+    cfg = RAGGED.with_(precision=synth.PREC_BF16, m=3, max_inflight=2)
+    gen = synth.StageInputs(cfg, 6)
+    st = B.Stage(cfg, gen.weights())
+    x, dy, _ = gen.microbatch()
+    X = to_dev(x, cfg.precision); Y = torch.empty_like(X)
+    s2 = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    st.forward(1, X, None, Y)
+    with pytest.raises(B.StageError) as err:
+        st.set_backward_stream(s2)
+    assert err.value.code == B.ERR_BAD_STATE
+    st.close()
+
+
 def test_bf16_sees_the_weight_version():
     """With eps = 1 Adam's step is nearly linear in g (no sign sensitivity) and lr = 1 moves the
     weights by ~5% per update: running a batch on the wrong version then changes G by 15-20%,
