@@ -648,6 +648,19 @@ struct AsyncLoader {
       }
     }
   }
+  // Load instruction j of the tile at k0, written as assembly so that the compiler does not see a
+  // store to LDS: it would otherwise put s_waitcnt vmcnt(0) in front of every later LDS read (it
+  // cannot tell the ring's stages apart), and the loads of the tiles further ahead could not stay
+  // in flight.  The caller waits (vmcnt) and synchronises before anyone reads the stage.
+  // lds_stage: byte address of the stage's tile in LDS, wave-uniform.
+  __device__ __forceinline__ void issue_one_untracked(int j, int k0, uint32_t lds_tile) const {
+    const bf16_t* b = K_CONTIG ? base_ + k0 : base_ + (int64_t)k0 * ld_;
+    const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + (uint32_t)(first_slot_ + j * 64) * 16u);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(dst), "v"(b + voff[j])
+                 : "memory");   // (M0 is reserved: the compiler keeps nothing in it)
+  }
   // tile at k0 -> LDS tile starting at byte address tile_bytes (uniform)
   __device__ __forceinline__ void issue(int k0, uint4* tile) const {
     const bf16_t* b = K_CONTIG ? base_ + k0 : base_ + (int64_t)k0 * ld_;
@@ -797,6 +810,157 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_async_ke
   epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane, smem, wave, 0, MI);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Ring variant of the asynchronous kernel: K tiles of 32 in a ring of NS LDS stages (a power of 2).  A wave's
+// 16-byte global->LDS load occupies the CU's address unit for 16 cycles (64 bytes per clock), so
+// the loads of a 256x256x64 step are a thousand cycles of issue; behind a barrier, back to back,
+// every wave sits in that queue with no MFMA in flight (measured with s_memtime around the phases:
+// 1400 cycles for the 8 MFMAs that follow the loads, 840 for the other 24).  With more than two
+// stages the stage that tile kt+NS-1 goes to is already free during the whole of step kt, so its
+// loads are issued one at a time between the MFMAs of both sub-steps and the queue never fills.
+// NS also sets how long a load may take: NS-2 steps.  A 256x256 tile has 1024 MFMA cycles per step
+// and gets by with four stages; a 128x128 tile has 256, and with operands that come from HBM it
+// needs eight (measured with flushed caches: four stages lose 10..15 % to the two-stage kernels).
+template <int BM, int BN, int WM, int WN, int NS, bool TA, bool TB, int EPI>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_kernel(GroupParams gp) {
+  constexpr int BKA = 32, CHK = BKA / 8;
+  constexpr int NW = (BM / WM) * (BN / WN);
+  constexpr int MI = WM / 32, NI = WN / 32;
+  constexpr int WAVES_N = BN / WN;
+  extern __shared__ uint4 smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int n_tiles = gp.tile_start[gp.count];
+  int wg = blockIdx.x;
+  {
+    const int per_xcd = n_tiles / 8;
+    if (wg < per_xcd * 8) wg = (wg % 8) * per_xcd + wg / 8;
+  }
+  int g = 0;
+#pragma unroll
+  for (int q = 1; q < kMaxGroup; ++q)
+    if (q < gp.count && wg >= gp.tile_start[q]) g = q;
+  const BfParams& p = gp.p[g];
+  wg -= gp.tile_start[g];
+  int bm, bn;
+  tile_coords(wg, p.tiles_m, p.tiles_n, bm, bn);
+  const int m0 = bm * BM, n0 = bn * BN;
+
+  AsyncLoader<BM, NW, BKA, !TA> ld_a;
+  AsyncLoader<BN, NW, BKA, TB> ld_b;
+  ld_a.init(TA ? p.A + m0 : p.A + (int64_t)m0 * p.lda, p.lda, p.M - m0, wave, lane);
+  ld_b.init(TB ? p.B + (int64_t)n0 * p.ldb : p.B + n0, p.ldb, p.N - n0, wave, lane);
+  constexpr int IPA = decltype(ld_a)::IPW, IPB = decltype(ld_b)::IPW;
+  static_assert(IPA == IPB, "square tiles: both operands take the same number of loads");
+
+  constexpr int kStage = (BM + BN) * CHK;  // uint4 per stage
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+  const int nk = p.K / BKA;   // K is a multiple of 32
+  // tile t (clamped past the end: fetched again, never read) into stage t & (NS - 1)
+  static_assert((NS & (NS - 1)) == 0 && NS >= 4, "ring size");
+  auto tile_k = [&](int t) { return (t < nk ? t : nk - 1) * BKA; };
+  // (dynamic LDS starts at address 0: a stage's byte address is its offset in smem)
+  for (int t = 0; t < NS - 1; ++t) {
+#pragma unroll
+    for (int j = 0; j < IPA; ++j) ld_a.issue_one_untracked(j, tile_k(t), (uint32_t)(t * kStage) * 16u);
+#pragma unroll
+    for (int j = 0; j < IPB; ++j) ld_b.issue_one_untracked(j, tile_k(t), (uint32_t)(t * kStage + BM * CHK) * 16u);
+  }
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * (IPA + IPB)));
+  __syncthreads();
+  bf16x8 af[2][MI], bfr[2][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) af[0][mi] = read_frag<BM, BKA, !TA>(smem, wm * WM + mi * 32, 0, lane);
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = read_frag<BN, BKA, TB>(smem + BM * CHK, wn * WN + ni * 32, 0, lane);
+
+  constexpr int NM = MI * NI, H = NM / 2, NF = MI + NI;
+  static_assert(NM % IPA == 0, "one load every NM / IPA MFMAs");
+  for (int kt = 0; kt < nk; ++kt) {
+    const uint4* sA = smem + (kt & (NS - 1)) * kStage;
+    const uint4* sB = sA + BM * CHK;
+    const uint4* nA = smem + ((kt + 1) & (NS - 1)) * kStage;
+    const uint4* nB = nA + BM * CHK;
+    const uint32_t lA = (uint32_t)(((kt + NS - 1) & (NS - 1)) * kStage) * 16u;
+    const uint32_t lB = lA + (uint32_t)(BM * CHK) * 16u;
+    const int k_load = tile_k(kt + NS - 1);
+    // sub-step 0: the A half of tile kt+NS-1 and the fragments of sub-step 1 between the MFMAs
+#pragma unroll
+    for (int i = 0; i < NM; ++i) {
+      const int mi = i / NI, ni = i % NI;
+      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[0][ni], af[0][mi], acc[mi][ni], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (i % (NM / IPA) == 0) ld_a.issue_one_untracked(i / (NM / IPA), k_load, lA);
+      if (i < H) {
+#pragma unroll
+        for (int f = (NF * i) / H; f < (NF * (i + 1)) / H; ++f) {
+          if (f < MI) af[1][f] = read_frag<BM, BKA, !TA>(sA, wm * WM + f * 32, 1, lane);
+          else bfr[1][f - MI] = read_frag<BN, BKA, TB>(sB, wn * WN + (f - MI) * 32, 1, lane);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // tile kt+1 has landed once at most the loads issued after it are outstanding: all of tiles
+    // kt+2 .. kt+NS-2 and the A half of tile kt+NS-1
+    static_assert((NS - 3) * (IPA + IPB) + IPA <= 63, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 3) * (IPA + IPB) + IPA) & ~(15 << 8));   // and lgkmcnt(0)
+    __syncthreads();
+    // sub-step 1: the B half of tile kt+NS-1 and the first fragments of tile kt+1 between the MFMAs
+#pragma unroll
+    for (int i = 0; i < NM; ++i) {
+      const int mi = i / NI, ni = i % NI;
+      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[1][ni], af[1][mi], acc[mi][ni], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (i % (NM / IPB) == 0) ld_b.issue_one_untracked(i / (NM / IPB), k_load, lB);
+      if (i < H) {
+#pragma unroll
+        for (int f = (NF * i) / H; f < (NF * (i + 1)) / H; ++f) {
+          if (f < MI) af[0][f] = read_frag<BM, BKA, !TA>(nA, wm * WM + f * 32, 0, lane);
+          else bfr[0][f - MI] = read_frag<BN, BKA, TB>(nB, wn * WN + (f - MI) * 32, 0, lane);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  // the last prefetches may still be landing in LDS, which the epilogue re-uses
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+  __syncthreads();
+  epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane, smem, wave, 0, MI);
+}
+
+template <int BM, int BN, int WM, int WN, int NS, bool TA, bool TB, int EPI>
+hipError_t launch_ring(GroupParams gp, hipStream_t s) {
+  constexpr int NT = (BM / WM) * (BN / WN) * 64;
+  constexpr size_t lds = NS * (BM + BN) * 4 * sizeof(uint4);
+  static_assert(lds <= 160 * 1024, "LDS of a CU");
+  auto kern = gemm_bf16_ring_kernel<BM, BN, WM, WN, NS, TA, TB, EPI>;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  int total = 0;
+  for (int g = 0; g < gp.count; ++g) {
+    gp.p[g].tiles_m = ceil_div(gp.p[g].M, BM);
+    gp.p[g].tiles_n = ceil_div(gp.p[g].N, BN);
+    gp.tile_start[g] = total;
+    total += gp.p[g].tiles_m * gp.p[g].tiles_n;
+  }
+  for (int g = gp.count; g <= kMaxGroup; ++g) gp.tile_start[g] = total;
+  hipLaunchKernelGGL(kern, dim3(total), dim3(NT), lds, s, gp);
+  return hipGetLastError();
+}
+
 template <int BM, int BN, int WM, int WN, int BKA, int NSTAGE, bool TA, bool TB, int EPI>
 hipError_t launch_async(GroupParams gp, hipStream_t s) {
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
@@ -854,19 +1018,26 @@ int choose_tile(const BfParams* p, int count, bool ta, bool tb) {
   if (tile == 0) {
     // Measured on MI355X (M = 2048..8192): once 256x256 tiles give about 5/8 of the CUs a tile
     // (160 tiles: N = 2560 at M = 4096) the 8-wave 256x256 kernels win, by 15..30 % at 160..192
-    // tiles and more above (the asynchronous one is a little ahead when both operands are
-    // K-contiguous; it needs K % 64 == 0 and falls back to the register-staged kernel otherwise).
-    // Below that, 128x128 tiles: two workgroups per CU when there are enough tiles, and the
-    // variant with two K groups per workgroup when there is about one tile per CU (+15..25 %).
+    // tiles and more above, and among them the ring kernel by 10..25 % (it needs K % 32 == 0 and
+    // falls back to the register-staged kernel of the same tile otherwise).  Below that, 128x128
+    // tiles: with about one tile per CU the variant with two K groups per workgroup (eight waves
+    // per CU); the 128x128 ring kernel is ahead of it with operands in cache but behind by 10..15 %
+    // with operands from HBM, which is what a stage's GEMMs see.
     int64_t big = 0, small = 0;
     for (int g = 0; g < count; ++g) {
       big += (int64_t)ceil_div(p[g].M, 256) * ceil_div(p[g].N, 256);
       small += (int64_t)ceil_div(p[g].M, 128) * ceil_div(p[g].N, 128);
     }
-    if (big >= 144) tile = (!ta && tb) ? 13 : 3;
-    else tile = small <= 256 ? 6 : 2;
+#ifndef K2BW_T_SMALL2
+#define K2BW_T_SMALL2 2
+#endif
+    tile = big >= 144 ? 23 : small <= 256 ? 6 : K2BW_T_SMALL2;
+    (void)ta; (void)tb;
   }
-  if (tile > 10) {   // the asynchronous kernels need whole K tiles
+  if (tile > 20) {   // the asynchronous kernels need whole K tiles (32 for the ring, 64 otherwise)
+    for (int g = 0; g < count; ++g)
+      if (p[g].K % 32) { tile -= 20; break; }
+  } else if (tile > 10) {
     for (int g = 0; g < count; ++g)
       if (p[g].K % 64) { tile -= 10; break; }
   }
@@ -884,6 +1055,10 @@ hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
     case 11: return launch_async<256, 256, 128, 128, 64, 2, TA, TB, EPI>(gp, s);
     case 12: return launch_async<128, 128, 64, 64, 64, 2, TA, TB, EPI>(gp, s);
     case 13: return launch_async<256, 256, 128, 64, 64, 2, TA, TB, EPI>(gp, s);
+    case 21: return launch_ring<256, 256, 128, 128, 4, TA, TB, EPI>(gp, s);
+    case 22: return launch_ring<128, 128, 64, 64, 8, TA, TB, EPI>(gp, s);
+    case 23: return launch_ring<256, 256, 128, 64, 4, TA, TB, EPI>(gp, s);
+    case 24: return launch_ring<128, 128, 64, 64, 4, TA, TB, EPI>(gp, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -919,6 +1094,10 @@ void gemm_bf16_kernel_name(const GemmDesc* d, int count, char* out, size_t cap) 
     case 3: snprintf(out, cap, "gemm_bf16_kernel<256, 256, 128, 64, 64, %s, %s, %d, 1>", ta, tb, d[0].epilogue); break;
     case 6: snprintf(out, cap, "gemm_bf16_kernel<128, 128, 64, 64, 64, %s, %s, %d, 2>", ta, tb, d[0].epilogue); break;
     case 13: snprintf(out, cap, "gemm_bf16_async_kernel<256, 256, 128, 64, 64, 2, %s, %s, %d>", ta, tb, d[0].epilogue); break;
+    case 21: snprintf(out, cap, "gemm_bf16_ring_kernel<256, 256, 128, 128, 4, %s, %s, %d>", ta, tb, d[0].epilogue); break;
+    case 22: snprintf(out, cap, "gemm_bf16_ring_kernel<128, 128, 64, 64, 8, %s, %s, %d>", ta, tb, d[0].epilogue); break;
+    case 23: snprintf(out, cap, "gemm_bf16_ring_kernel<256, 256, 128, 64, 4, %s, %s, %d>", ta, tb, d[0].epilogue); break;
+    case 24: snprintf(out, cap, "gemm_bf16_ring_kernel<128, 128, 64, 64, 4, %s, %s, %d>", ta, tb, d[0].epilogue); break;
     default: snprintf(out, cap, "gemm_bf16 tile %d <%s, %s, %d>", tile, ta, tb, d[0].epilogue); break;
   }
 }
