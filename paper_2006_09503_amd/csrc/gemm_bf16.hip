@@ -23,6 +23,8 @@
 // global accesses 8-byte (bf16) or 16-byte (fp32 accumulator) vectors.
 #include <cstdio>
 
+#include <type_traits>
+
 #include "kernels.hpp"
 
 namespace k2bw {
@@ -811,22 +813,24 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_async_ke
 }
 
 // ------------------------------------------------------------------------------------------------
-// Ring variant of the asynchronous kernel: K tiles of 32 in a ring of NS LDS stages (a power of 2).  A wave's
-// 16-byte global->LDS load occupies the CU's address unit for 16 cycles (64 bytes per clock), so
-// the loads of a 256x256x64 step are a thousand cycles of issue; behind a barrier, back to back,
-// every wave sits in that queue with no MFMA in flight (measured with s_memtime around the phases:
-// 1400 cycles for the 8 MFMAs that follow the loads, 840 for the other 24).  With more than two
-// stages the stage that tile kt+NS-1 goes to is already free during the whole of step kt, so its
-// loads are issued one at a time between the MFMAs of both sub-steps and the queue never fills.
-// NS also sets how long a load may take: NS-2 steps.  A 256x256 tile has 1024 MFMA cycles per step
-// and gets by with four stages; a 128x128 tile has 256, and with operands that come from HBM it
-// needs eight (measured with flushed caches: four stages lose 10..15 % to the two-stage kernels).
-template <int BM, int BN, int WM, int WN, int NS, bool TA, bool TB, int EPI>
+// Ring variant of the asynchronous kernel: K tiles of BKA (32 or 64) in a ring of NS LDS stages (a
+// power of 2).  A wave's 16-byte global->LDS load occupies the CU's address unit for about 16
+// cycles, so the loads of a 256x256x64 step are a thousand cycles of issue; behind a barrier, back
+// to back, every wave sits in that queue with no MFMA in flight (measured with s_memtime around
+// the phases of the two-stage kernel: 1400 cycles for the 8 MFMAs that follow the loads, 840 for
+// the other 24).  With more than two stages the stage that tile kt+NS-1 goes to is already free
+// during the whole of step kt, so its loads are issued one at a time between the MFMAs of all
+// sub-steps and the queue never fills; a load has NS-2 steps to land.  256x256 tiles: four stages
+// of K = 32 (128 KB).  128x128 tiles: four stages of K = 64; with K = 32 (half a 128-byte line per
+// row and load) that tile is 10..15 % slower once the operands come from HBM, as they do inside
+// the stage, with four stages or with eight.
+template <int BM, int BN, int WM, int WN, int BKA, int NS, bool TA, bool TB, int EPI>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_kernel(GroupParams gp) {
-  constexpr int BKA = 32, CHK = BKA / 8;
+  constexpr int CHK = BKA / 8, KS = BKA / 16;
   constexpr int NW = (BM / WM) * (BN / WN);
   constexpr int MI = WM / 32, NI = WN / 32;
   constexpr int WAVES_N = BN / WN;
+  static_assert((NS & (NS - 1)) == 0 && NS >= 4 && KS % 2 == 0, "ring size, even number of sub-steps");
   extern __shared__ uint4 smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -851,8 +855,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
   AsyncLoader<BN, NW, BKA, TB> ld_b;
   ld_a.init(TA ? p.A + m0 : p.A + (int64_t)m0 * p.lda, p.lda, p.M - m0, wave, lane);
   ld_b.init(TB ? p.B + (int64_t)n0 * p.ldb : p.B + n0, p.ldb, p.N - n0, wave, lane);
-  constexpr int IPA = decltype(ld_a)::IPW, IPB = decltype(ld_b)::IPW;
-  static_assert(IPA == IPB, "square tiles: both operands take the same number of loads");
+  constexpr int IPA = decltype(ld_a)::IPW, NV = IPA + decltype(ld_b)::IPW;   // loads per wave and tile
 
   constexpr int kStage = (BM + BN) * CHK;  // uint4 per stage
   f32x16 acc[MI][NI];
@@ -863,18 +866,18 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-  const int nk = p.K / BKA;   // K is a multiple of 32
-  // tile t (clamped past the end: fetched again, never read) into stage t & (NS - 1)
-  static_assert((NS & (NS - 1)) == 0 && NS >= 4, "ring size");
+  const int nk = p.K / BKA;   // K is a multiple of BKA
+  // tile t (clamped past the end: fetched again, never read) goes to stage t & (NS - 1);
+  // dynamic LDS starts at address 0, so a stage's byte address is its offset in smem
   auto tile_k = [&](int t) { return (t < nk ? t : nk - 1) * BKA; };
-  // (dynamic LDS starts at address 0: a stage's byte address is its offset in smem)
-  for (int t = 0; t < NS - 1; ++t) {
+  auto issue = [&](int v, int k0, uint32_t stage_bytes) {
+    if (v < IPA) ld_a.issue_one_untracked(v, k0, stage_bytes);
+    else ld_b.issue_one_untracked(v - IPA, k0, stage_bytes + (uint32_t)(BM * CHK) * 16u);
+  };
+  for (int t = 0; t < NS - 1; ++t)
 #pragma unroll
-    for (int j = 0; j < IPA; ++j) ld_a.issue_one_untracked(j, tile_k(t), (uint32_t)(t * kStage) * 16u);
-#pragma unroll
-    for (int j = 0; j < IPB; ++j) ld_b.issue_one_untracked(j, tile_k(t), (uint32_t)(t * kStage + BM * CHK) * 16u);
-  }
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * (IPA + IPB)));
+    for (int v = 0; v < NV; ++v) issue(v, tile_k(t), (uint32_t)(t * kStage) * 16u);
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * NV));
   __syncthreads();
   bf16x8 af[2][MI], bfr[2][NI];
 #pragma unroll
@@ -882,52 +885,47 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = read_frag<BN, BKA, TB>(smem + BM * CHK, wn * WN + ni * 32, 0, lane);
 
+  // One step = KS sub-steps of NM MFMAs.  The NV loads of tile kt+NS-1 go out every EVERY-th MFMA
+  // of the step; the fragments of the following sub-step (after the last one: sub-step 0 of tile
+  // kt+1) are read behind the first half of each sub-step's MFMAs.
   constexpr int NM = MI * NI, H = NM / 2, NF = MI + NI;
-  static_assert(NM % IPA == 0, "one load every NM / IPA MFMAs");
+  static_assert((KS * NM) % NV == 0, "one load every (KS * NM / NV)-th MFMA");
+  constexpr int EVERY = KS * NM / NV;
+  constexpr int NV_PRE = ((KS - 1) * NM + EVERY - 1) / EVERY;   // loads issued before the barrier
+  static_assert((NS - 3) * NV + NV_PRE <= 63, "vmcnt range");
   for (int kt = 0; kt < nk; ++kt) {
     const uint4* sA = smem + (kt & (NS - 1)) * kStage;
     const uint4* sB = sA + BM * CHK;
     const uint4* nA = smem + ((kt + 1) & (NS - 1)) * kStage;
     const uint4* nB = nA + BM * CHK;
-    const uint32_t lA = (uint32_t)(((kt + NS - 1) & (NS - 1)) * kStage) * 16u;
-    const uint32_t lB = lA + (uint32_t)(BM * CHK) * 16u;
+    const uint32_t l_stage = (uint32_t)(((kt + NS - 1) & (NS - 1)) * kStage) * 16u;
     const int k_load = tile_k(kt + NS - 1);
-    // sub-step 0: the A half of tile kt+NS-1 and the fragments of sub-step 1 between the MFMAs
 #pragma unroll
-    for (int i = 0; i < NM; ++i) {
-      const int mi = i / NI, ni = i % NI;
-      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[0][ni], af[0][mi], acc[mi][ni], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (i % (NM / IPA) == 0) ld_a.issue_one_untracked(i / (NM / IPA), k_load, lA);
-      if (i < H) {
-#pragma unroll
-        for (int f = (NF * i) / H; f < (NF * (i + 1)) / H; ++f) {
-          if (f < MI) af[1][f] = read_frag<BM, BKA, !TA>(sA, wm * WM + f * 32, 1, lane);
-          else bfr[1][f - MI] = read_frag<BN, BKA, TB>(sB, wn * WN + (f - MI) * 32, 1, lane);
-        }
+    for (int ks = 0; ks < KS; ++ks) {
+      const int cur = ks & 1, nxt = cur ^ 1;
+      const bool last = ks == KS - 1;
+      if (last) {
+        // tile kt+1 has landed once at most the loads issued after it are outstanding: all of
+        // tiles kt+2 .. kt+NS-2 and what this step has issued of tile kt+NS-1 so far; the barrier
+        // also tells that nobody reads stage kt any more (its last fragments are in registers)
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 3) * NV + NV_PRE) & ~(15 << 8));   // and lgkmcnt(0)
+        __syncthreads();
       }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // tile kt+1 has landed once at most the loads issued after it are outstanding: all of tiles
-    // kt+2 .. kt+NS-2 and the A half of tile kt+NS-1
-    static_assert((NS - 3) * (IPA + IPB) + IPA <= 63, "vmcnt range");
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 3) * (IPA + IPB) + IPA) & ~(15 << 8));   // and lgkmcnt(0)
-    __syncthreads();
-    // sub-step 1: the B half of tile kt+NS-1 and the first fragments of tile kt+1 between the MFMAs
 #pragma unroll
-    for (int i = 0; i < NM; ++i) {
-      const int mi = i / NI, ni = i % NI;
-      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[1][ni], af[1][mi], acc[mi][ni], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (i % (NM / IPB) == 0) ld_b.issue_one_untracked(i / (NM / IPB), k_load, lB);
-      if (i < H) {
+      for (int i = 0; i < NM; ++i) {
+        const int mi = i / NI, ni = i % NI, q = ks * NM + i;
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (q % EVERY == 0) issue(q / EVERY, k_load, l_stage);
+        if (i < H) {
 #pragma unroll
-        for (int f = (NF * i) / H; f < (NF * (i + 1)) / H; ++f) {
-          if (f < MI) af[0][f] = read_frag<BM, BKA, !TA>(nA, wm * WM + f * 32, 0, lane);
-          else bfr[0][f - MI] = read_frag<BN, BKA, TB>(nB, wn * WN + (f - MI) * 32, 0, lane);
+          for (int f = (NF * i) / H; f < (NF * (i + 1)) / H; ++f) {
+            if (f < MI) af[nxt][f] = read_frag<BM, BKA, !TA>(last ? nA : sA, wm * WM + f * 32, last ? 0 : ks + 1, lane);
+            else bfr[nxt][f - MI] = read_frag<BN, BKA, TB>(last ? nB : sB, wn * WN + (f - MI) * 32, last ? 0 : ks + 1, lane);
+          }
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
     }
   }
   // the last prefetches may still be landing in LDS, which the epilogue re-uses
@@ -936,12 +934,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
   epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane, smem, wave, 0, MI);
 }
 
-template <int BM, int BN, int WM, int WN, int NS, bool TA, bool TB, int EPI>
+template <int BM, int BN, int WM, int WN, int BKA, int NS, bool TA, bool TB, int EPI>
 hipError_t launch_ring(GroupParams gp, hipStream_t s) {
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
-  constexpr size_t lds = NS * (BM + BN) * 4 * sizeof(uint4);
+  constexpr size_t lds = NS * (BM + BN) * (BKA / 8) * sizeof(uint4);
   static_assert(lds <= 160 * 1024, "LDS of a CU");
-  auto kern = gemm_bf16_ring_kernel<BM, BN, WM, WN, NS, TA, TB, EPI>;
+  auto kern = gemm_bf16_ring_kernel<BM, BN, WM, WN, BKA, NS, TA, TB, EPI>;
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1018,25 +1016,23 @@ int choose_tile(const BfParams* p, int count, bool ta, bool tb) {
   if (tile == 0) {
     // Measured on MI355X (M = 2048..8192): once 256x256 tiles give about 5/8 of the CUs a tile
     // (160 tiles: N = 2560 at M = 4096) the 8-wave 256x256 kernels win, by 15..30 % at 160..192
-    // tiles and more above, and among them the ring kernel by 10..25 % (it needs K % 32 == 0 and
-    // falls back to the register-staged kernel of the same tile otherwise).  Below that, 128x128
-    // tiles: with about one tile per CU the variant with two K groups per workgroup (eight waves
-    // per CU); the 128x128 ring kernel is ahead of it with operands in cache but behind by 10..15 %
-    // with operands from HBM, which is what a stage's GEMMs see.
+    // tiles and more above, and among them the ring kernel by 10..25 %.  Below that, 128x128
+    // tiles: with about one tile per CU the ring kernel with K tiles of 64 (a little ahead of the
+    // variant with two K groups per workgroup), with more tiles two register-staged workgroups per
+    // CU.  The ring kernels need K to be a multiple of their K tile and fall back to the
+    // register-staged kernel of the same tile otherwise.
     int64_t big = 0, small = 0;
     for (int g = 0; g < count; ++g) {
       big += (int64_t)ceil_div(p[g].M, 256) * ceil_div(p[g].N, 256);
       small += (int64_t)ceil_div(p[g].M, 128) * ceil_div(p[g].N, 128);
     }
-#ifndef K2BW_T_SMALL2
-#define K2BW_T_SMALL2 2
-#endif
-    tile = big >= 144 ? 23 : small <= 256 ? 6 : K2BW_T_SMALL2;
+    tile = big >= 144 ? 23 : small <= 256 ? 22 : 2;
     (void)ta; (void)tb;
   }
-  if (tile > 20) {   // the asynchronous kernels need whole K tiles (32 for the ring, 64 otherwise)
+  if (tile > 20) {   // the asynchronous kernels need whole K tiles
+    const int bk = tile == 22 ? 64 : 32;
     for (int g = 0; g < count; ++g)
-      if (p[g].K % 32) { tile -= 20; break; }
+      if (p[g].K % bk) { tile -= 20; break; }
   } else if (tile > 10) {
     for (int g = 0; g < count; ++g)
       if (p[g].K % 64) { tile -= 10; break; }
@@ -1055,10 +1051,8 @@ hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
     case 11: return launch_async<256, 256, 128, 128, 64, 2, TA, TB, EPI>(gp, s);
     case 12: return launch_async<128, 128, 64, 64, 64, 2, TA, TB, EPI>(gp, s);
     case 13: return launch_async<256, 256, 128, 64, 64, 2, TA, TB, EPI>(gp, s);
-    case 21: return launch_ring<256, 256, 128, 128, 4, TA, TB, EPI>(gp, s);
-    case 22: return launch_ring<128, 128, 64, 64, 8, TA, TB, EPI>(gp, s);
-    case 23: return launch_ring<256, 256, 128, 64, 4, TA, TB, EPI>(gp, s);
-    case 24: return launch_ring<128, 128, 64, 64, 4, TA, TB, EPI>(gp, s);
+    case 22: return launch_ring<128, 128, 64, 64, 64, 4, TA, TB, EPI>(gp, s);
+    case 23: return launch_ring<256, 256, 128, 64, 32, 4, TA, TB, EPI>(gp, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -1094,10 +1088,8 @@ void gemm_bf16_kernel_name(const GemmDesc* d, int count, char* out, size_t cap) 
     case 3: snprintf(out, cap, "gemm_bf16_kernel<256, 256, 128, 64, 64, %s, %s, %d, 1>", ta, tb, d[0].epilogue); break;
     case 6: snprintf(out, cap, "gemm_bf16_kernel<128, 128, 64, 64, 64, %s, %s, %d, 2>", ta, tb, d[0].epilogue); break;
     case 13: snprintf(out, cap, "gemm_bf16_async_kernel<256, 256, 128, 64, 64, 2, %s, %s, %d>", ta, tb, d[0].epilogue); break;
-    case 21: snprintf(out, cap, "gemm_bf16_ring_kernel<256, 256, 128, 128, 4, %s, %s, %d>", ta, tb, d[0].epilogue); break;
-    case 22: snprintf(out, cap, "gemm_bf16_ring_kernel<128, 128, 64, 64, 8, %s, %s, %d>", ta, tb, d[0].epilogue); break;
-    case 23: snprintf(out, cap, "gemm_bf16_ring_kernel<256, 256, 128, 64, 4, %s, %s, %d>", ta, tb, d[0].epilogue); break;
-    case 24: snprintf(out, cap, "gemm_bf16_ring_kernel<128, 128, 64, 64, 4, %s, %s, %d>", ta, tb, d[0].epilogue); break;
+    case 22: snprintf(out, cap, "gemm_bf16_ring_kernel<128, 128, 64, 64, 64, 4, %s, %s, %d>", ta, tb, d[0].epilogue); break;
+    case 23: snprintf(out, cap, "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, %s, %s, %d>", ta, tb, d[0].epilogue); break;
     default: snprintf(out, cap, "gemm_bf16 tile %d <%s, %s, %d>", tile, ta, tb, d[0].epilogue); break;
   }
 }
