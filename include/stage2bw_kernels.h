@@ -90,10 +90,10 @@ int k2bw_adam(int64_t n, const float* w_cur, float* w_next, void* w_next_bf16, f
               void* stream);
 
 /* Tuning aid: force the bf16 GEMM's kernel variant (0 = built-in choice).  Register-staged:
- * 1: 256x256 tile / 4 waves, 2: 128x128 / 4 waves, 3: 256x256 / 8 waves, 6: 128x128 with two K
- * groups of 4 waves.  Direct-to-LDS loads (K a multiple of 64, else the register-staged twin):
- * 11: 256x256 / 4 waves, 12: 128x128 / 4 waves, 13: 256x256 / 8 waves.  Other ids: INVALID_ARG.
- * Process-wide. */
+ * 2: 128x128 tile / 4 waves, 3: 256x256 / 8 waves, 6: 128x128 with two K groups of 4 waves.
+ * Direct-to-LDS loads through a ring of four LDS stages: 22: 128x128 / 4 waves, K tiles of 64;
+ * 23: 256x256 / 8 waves, K tiles of 32 (K not a multiple of the K tile: 6 and 3 instead).
+ * Other ids: INVALID_ARG.  Process-wide. */
 int k2bw_tune_gemm_tile(int id);
 
 /* dy = (y - target) * scale, element-wise over n elements (n a multiple of 8 in bf16, of 4 in

@@ -603,7 +603,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KSPLIT) void gemm_bf16
 }
 
 // ------------------------------------------------------------------------------------------------
-// Asynchronous variant (K a multiple of 64).  Tiles go from HBM straight into LDS with
+// Asynchronous kernels (K a multiple of the K tile).  Tiles go from HBM straight into LDS with
 // global_load_lds (16 bytes per lane, a wave fills 1 KB of consecutive LDS), so no registers and
 // no LDS store instructions are spent on staging:
 //   * K-contiguous operand: LDS [row][8 chunks], chunk XOR-swizzled as above; lane i of a load
@@ -614,7 +614,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KSPLIT) void gemm_bf16
 //     4a + j receives (k_0..k_3) of row 4a + j -- measured on gfx950 -- so two such reads give a
 //     lane the 8 k-values of its row in the same slot order as a 16-byte read of the other form.
 // Out-of-range rows are fetched from a clamped address (their products only reach outputs that
-// are never stored).  Two LDS stages; the loads of tile kt+1 are issued before the MFMAs of kt.
+// are never stored).
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) v4i16 lds_v4i16_t;
 typedef __attribute__((address_space(3))) void lds_void_t;
@@ -663,13 +663,6 @@ struct AsyncLoader {
                  : "s"(dst), "v"(b + voff[j])
                  : "memory");   // (M0 is reserved: the compiler keeps nothing in it)
   }
-  // tile at k0 -> LDS tile starting at byte address tile_bytes (uniform)
-  __device__ __forceinline__ void issue(int k0, uint4* tile) const {
-    const bf16_t* b = K_CONTIG ? base_ + k0 : base_ + (int64_t)k0 * ld_;
-#pragma unroll
-    for (int j = 0; j < IPW; ++j)
-      __builtin_amdgcn_global_load_lds((glob_void_t*)(b + voff[j]), (lds_void_t*)(tile + first_slot_ + j * 64), 16, 0, 0);
-  }
 };
 
 // fragment of 32 rows starting at row0 for sub-step ks
@@ -699,122 +692,8 @@ __device__ __forceinline__ bf16x8 read_frag(const uint4* tile, int row0, int ks,
 // vmcnt = bits 3:0 and 15:14; expcnt and lgkmcnt fields left at their maxima = no wait)
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
-template <int BM, int BN, int WM, int WN, int BKA, int NSTAGE, bool TA, bool TB, int EPI>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_async_kernel(GroupParams gp) {
-  constexpr int NW = (BM / WM) * (BN / WN);
-  constexpr int MI = WM / 32, NI = WN / 32;
-  constexpr int WAVES_N = BN / WN;
-  constexpr int KS = BKA / 16, CHK = BKA / 8;
-  extern __shared__ uint4 smem[];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  const int n_tiles = gp.tile_start[gp.count];
-  int wg = blockIdx.x;
-  {
-    const int per_xcd = n_tiles / 8;
-    if (wg < per_xcd * 8) wg = (wg % 8) * per_xcd + wg / 8;
-  }
-  int g = 0;
-#pragma unroll
-  for (int q = 1; q < kMaxGroup; ++q)
-    if (q < gp.count && wg >= gp.tile_start[q]) g = q;
-  const BfParams& p = gp.p[g];
-  wg -= gp.tile_start[g];
-  int bm, bn;
-  tile_coords(wg, p.tiles_m, p.tiles_n, bm, bn);
-  const int m0 = bm * BM, n0 = bn * BN;
-
-  AsyncLoader<BM, NW, BKA, !TA> ld_a;
-  AsyncLoader<BN, NW, BKA, TB> ld_b;
-  ld_a.init(TA ? p.A + m0 : p.A + (int64_t)m0 * p.lda, p.lda, p.M - m0, wave, lane);
-  ld_b.init(TB ? p.B + (int64_t)n0 * p.ldb : p.B + n0, p.ldb, p.N - n0, wave, lane);
-
-  constexpr int kStage = (BM + BN) * CHK;  // uint4 per stage
-  f32x16 acc[MI][NI];
-#pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-
-  const int nk = p.K / BKA;   // K is a multiple of 64
-  static_assert(NSTAGE == 2 && KS % 2 == 0, "two LDS stages, even number of sub-steps");
-  constexpr int RD = MI * (TA ? 2 : 1) + NI * (TB ? 1 : 2);   // LDS reads per sub-step
-  // Pipeline (two stages).  At the top of K step kt the fragments of its sub-step 0 are in
-  // registers and tile kt+1 is on its way into the other stage.  Sub-steps 0..KS-2 run with the
-  // fragment reads of the following sub-step between their MFMAs; then the wave waits for its
-  // share of tile kt+1 and for its own LDS reads, and the barrier tells it that tile kt+1 is
-  // complete and that nobody reads stage kt&1 any more: the loads of tile kt+2 go there, and the
-  // last sub-step's MFMAs run with the reads of tile kt+1's first fragments between them.  Each
-  // load has a whole K step to land and no MFMA group waits for an LDS read issued just before it.
-  ld_a.issue(0, smem);
-  ld_b.issue(0, smem + BM * CHK);
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-  __syncthreads();
-  {
-    const int k1 = (nk > 1 ? 1 : 0) * BKA;   // (a one-tile problem fetches tile 0 again: never read)
-    ld_a.issue(k1, smem + kStage);
-    ld_b.issue(k1, smem + kStage + BM * CHK);
-  }
-  bf16x8 af[2][MI], bfr[2][NI];
-#pragma unroll
-  for (int mi = 0; mi < MI; ++mi) af[0][mi] = read_frag<BM, BKA, !TA>(smem, wm * WM + mi * 32, 0, lane);
-#pragma unroll
-  for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = read_frag<BN, BKA, TB>(smem + BM * CHK, wn * WN + ni * 32, 0, lane);
-
-  for (int kt = 0; kt < nk; ++kt) {
-    uint4* sCur = smem + (kt & 1) * kStage;
-    const uint4* sA = sCur;
-    const uint4* sB = sA + BM * CHK;
-    const uint4* nA = smem + ((kt + 1) & 1) * kStage;
-    const uint4* nB = nA + BM * CHK;
-#pragma unroll
-    for (int ks = 0; ks + 1 < KS; ++ks) {
-      const int cur = ks & 1, nxt = cur ^ 1;
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi) af[nxt][mi] = read_frag<BM, BKA, !TA>(sA, wm * WM + mi * 32, ks + 1, lane);
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni) bfr[nxt][ni] = read_frag<BN, BKA, TB>(sB, wn * WN + ni * 32, ks + 1, lane);
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
-    }
-#pragma unroll
-    for (int ks = 0; ks + 1 < KS; ++ks) interleave_reads_with_mfma<0, MI * NI, RD>();
-    __builtin_amdgcn_sched_barrier(0);   // (MFMAs would otherwise sink below the barrier and leave the wait bare)
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0) & ~(15 << 8));   // vmcnt(0) and lgkmcnt(0)
-    __syncthreads();
-    {
-      // tile kt+2 into the stage just released (past the end: the last tile again, never read)
-      const int k_next = (kt + 2 < nk ? kt + 2 : nk - 1) * BKA;
-      ld_a.issue(k_next, sCur);
-      ld_b.issue(k_next, sCur + BM * CHK);
-      constexpr int cur = (KS - 1) & 1, nxt = cur ^ 1;
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi) af[nxt][mi] = read_frag<BM, BKA, !TA>(nA, wm * WM + mi * 32, 0, lane);
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni) bfr[nxt][ni] = read_frag<BN, BKA, TB>(nB, wn * WN + ni * 32, 0, lane);
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
-      interleave_reads_with_mfma<0, MI * NI, RD>();
-    }
-  }
-  // the last two prefetches may still be landing in LDS, which the epilogue re-uses
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-  __syncthreads();
-  epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane, smem, wave, 0, MI);
-}
-
 // ------------------------------------------------------------------------------------------------
-// Ring variant of the asynchronous kernel: K tiles of BKA (32 or 64) in a ring of NS LDS stages (a
-// power of 2).  A wave's 16-byte global->LDS load occupies the CU's address unit for about 16
+// The ring kernel: K tiles of BKA (32 or 64) in a ring of NS LDS stages (a power of 2).  A wave's 16-byte global->LDS load occupies the CU's address unit for about 16
 // cycles, so the loads of a 256x256x64 step are a thousand cycles of issue; behind a barrier, back
 // to back, every wave sits in that queue with no MFMA in flight (measured with s_memtime around
 // the phases of the two-stage kernel: 1400 cycles for the 8 MFMAs that follow the loads, 840 for
@@ -959,30 +838,6 @@ hipError_t launch_ring(GroupParams gp, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WM, int WN, int BKA, int NSTAGE, bool TA, bool TB, int EPI>
-hipError_t launch_async(GroupParams gp, hipStream_t s) {
-  constexpr int NT = (BM / WM) * (BN / WN) * 64;
-  constexpr size_t lds = NSTAGE * (BM + BN) * (BKA / 8) * sizeof(uint4);
-  auto kern = gemm_bf16_async_kernel<BM, BN, WM, WN, BKA, NSTAGE, TA, TB, EPI>;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
-  int total = 0;
-  for (int g = 0; g < gp.count; ++g) {
-    gp.p[g].tiles_m = ceil_div(gp.p[g].M, BM);
-    gp.p[g].tiles_n = ceil_div(gp.p[g].N, BN);
-    gp.tile_start[g] = total;
-    total += gp.p[g].tiles_m * gp.p[g].tiles_n;
-  }
-  for (int g = gp.count; g <= kMaxGroup; ++g) gp.tile_start[g] = total;
-  hipLaunchKernelGGL(kern, dim3(total), dim3(NT), lds, s, gp);
-  return hipGetLastError();
-}
-
 template <int BM, int BN, int WM, int WN, int BK, bool TA, bool TB, int EPI, int KSPLIT = 1>
 hipError_t launch(GroupParams gp, hipStream_t s) {
   constexpr int NT = (BM / WM) * (BN / WN) * 64 * KSPLIT;
@@ -1018,9 +873,9 @@ int choose_tile(const BfParams* p, int count, bool ta, bool tb) {
     // (160 tiles: N = 2560 at M = 4096) the 8-wave 256x256 kernels win, by 15..30 % at 160..192
     // tiles and more above, and among them the ring kernel by 10..25 %.  Below that, 128x128
     // tiles: with about one tile per CU the ring kernel with K tiles of 64 (a little ahead of the
-    // variant with two K groups per workgroup), with more tiles two register-staged workgroups per
-    // CU.  The ring kernels need K to be a multiple of their K tile and fall back to the
-    // register-staged kernel of the same tile otherwise.
+    // register-staged variant with two K groups per workgroup), with more tiles two register-staged
+    // workgroups per CU.  The ring kernels need K to be a multiple of their K tile and fall back to
+    // the register-staged kernel of the same tile otherwise.
     int64_t big = 0, small = 0;
     for (int g = 0; g < count; ++g) {
       big += (int64_t)ceil_div(p[g].M, 256) * ceil_div(p[g].N, 256);
@@ -1029,13 +884,10 @@ int choose_tile(const BfParams* p, int count, bool ta, bool tb) {
     tile = big >= 144 ? 23 : small <= 256 ? 22 : 2;
     (void)ta; (void)tb;
   }
-  if (tile > 20) {   // the asynchronous kernels need whole K tiles
+  if (tile > 20) {   // the ring kernels need whole K tiles
     const int bk = tile == 22 ? 64 : 32;
     for (int g = 0; g < count; ++g)
-      if (p[g].K % bk) { tile -= 20; break; }
-  } else if (tile > 10) {
-    for (int g = 0; g < count; ++g)
-      if (p[g].K % 64) { tile -= 10; break; }
+      if (p[g].K % bk) { tile = tile == 22 ? 6 : 3; break; }
   }
   return tile;
 }
@@ -1044,13 +896,9 @@ template <bool TA, bool TB, int EPI>
 hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
   const int tile = choose_tile(gp.p, gp.count, TA, TB);
   switch (tile) {
-    case 1: return launch<256, 256, 128, 128, 64, TA, TB, EPI>(gp, s);
     case 2: return launch<128, 128, 64, 64, 64, TA, TB, EPI>(gp, s);
     case 3: return launch<256, 256, 128, 64, 64, TA, TB, EPI>(gp, s);   // 8 waves
     case 6: return launch<128, 128, 64, 64, 64, TA, TB, EPI, 2>(gp, s);   // two K groups of 4 waves
-    case 11: return launch_async<256, 256, 128, 128, 64, 2, TA, TB, EPI>(gp, s);
-    case 12: return launch_async<128, 128, 64, 64, 64, 2, TA, TB, EPI>(gp, s);
-    case 13: return launch_async<256, 256, 128, 64, 64, 2, TA, TB, EPI>(gp, s);
     case 22: return launch_ring<128, 128, 64, 64, 64, 4, TA, TB, EPI>(gp, s);
     case 23: return launch_ring<256, 256, 128, 64, 32, 4, TA, TB, EPI>(gp, s);
     default: return hipErrorInvalidValue;
@@ -1083,11 +931,9 @@ void gemm_bf16_kernel_name(const GemmDesc* d, int count, char* out, size_t cap) 
   const char* ta = d[0].trans_a ? "true" : "false";
   const char* tb = d[0].trans_b ? "true" : "false";
   switch (tile) {
-    case 1: snprintf(out, cap, "gemm_bf16_kernel<256, 256, 128, 128, 64, %s, %s, %d, 1>", ta, tb, d[0].epilogue); break;
     case 2: snprintf(out, cap, "gemm_bf16_kernel<128, 128, 64, 64, 64, %s, %s, %d, 1>", ta, tb, d[0].epilogue); break;
     case 3: snprintf(out, cap, "gemm_bf16_kernel<256, 256, 128, 64, 64, %s, %s, %d, 1>", ta, tb, d[0].epilogue); break;
     case 6: snprintf(out, cap, "gemm_bf16_kernel<128, 128, 64, 64, 64, %s, %s, %d, 2>", ta, tb, d[0].epilogue); break;
-    case 13: snprintf(out, cap, "gemm_bf16_async_kernel<256, 256, 128, 64, 64, 2, %s, %s, %d>", ta, tb, d[0].epilogue); break;
     case 22: snprintf(out, cap, "gemm_bf16_ring_kernel<128, 128, 64, 64, 64, 4, %s, %s, %d>", ta, tb, d[0].epilogue); break;
     case 23: snprintf(out, cap, "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, %s, %s, %d>", ta, tb, d[0].epilogue); break;
     default: snprintf(out, cap, "gemm_bf16 tile %d <%s, %s, %d>", tile, ta, tb, d[0].epilogue); break;

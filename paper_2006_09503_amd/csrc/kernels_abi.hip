@@ -146,7 +146,7 @@ int k2bw_copy(const void* in, void* out, int64_t bytes, void* stream) {
 
 namespace k2bw { void gemm_bf16_set_tile(int id); }
 extern "C" int k2bw_tune_gemm_tile(int id) {
-  if (id != 0 && id != 1 && id != 2 && id != 3 && id != 6 && id != 11 && id != 12 && id != 13 && id != 22 && id != 23) return STAGE_ERR_INVALID_ARG;
+  if (id != 0 && id != 2 && id != 3 && id != 6 && id != 22 && id != 23) return STAGE_ERR_INVALID_ARG;
   k2bw::gemm_bf16_set_tile(id);
   return STAGE_OK;
 }

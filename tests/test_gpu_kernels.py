@@ -114,7 +114,7 @@ def test_gemm_weight_gradient_form_coalesces_in_place(dtype, M, N, K):
     assert rel(to_host(G), g1 + x2.astype(np.float64).T @ d2.astype(np.float64)) < 2e-6
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 6, 11, 12, 13, 22, 23])
+@pytest.mark.parametrize("tile", [2, 3, 6, 22, 23])
 @pytest.mark.parametrize("M,N,K", [(296, 264, 200), (328, 272, 192), (136, 520, 64), (264, 136, 96), (136, 264, 32)])
 def test_gemm_every_tile_variant(tile, M, N, K):
     """Each tile shape / staging variant of the bf16 kernel, forced, on ragged shapes in all three forms:
