@@ -91,7 +91,7 @@ int k2bw_adam(int64_t n, const float* w_cur, float* w_next, void* w_next_bf16, f
 
 /* Tuning aid: force the bf16 GEMM's kernel variant (0 = built-in choice).  Register-staged:
  * 2: 128x128 tile / 4 waves, 3: 256x256 / 8 waves, 6: 128x128 with two K groups of 4 waves.
- * Direct-to-LDS loads through a ring of four LDS stages: 22: 128x128 / 4 waves, K tiles of 64;
+ * Direct-to-LDS loads through a ring of four LDS stages: 22: 128x128 / 8 waves, K tiles of 64;
  * 23: 256x256 / 8 waves, K tiles of 32 (K not a multiple of the K tile: 6 and 3 instead).
  * Other ids: INVALID_ARG.  Process-wide. */
 int k2bw_tune_gemm_tile(int id);

@@ -899,7 +899,7 @@ hipError_t pick_tile(const GroupParams& gp, hipStream_t s) {
     case 2: return launch<128, 128, 64, 64, 64, TA, TB, EPI>(gp, s);
     case 3: return launch<256, 256, 128, 64, 64, TA, TB, EPI>(gp, s);   // 8 waves
     case 6: return launch<128, 128, 64, 64, 64, TA, TB, EPI, 2>(gp, s);   // two K groups of 4 waves
-    case 22: return launch_ring<128, 128, 64, 64, 64, 4, TA, TB, EPI>(gp, s);
+    case 22: return launch_ring<128, 128, 32, 64, 64, 4, TA, TB, EPI>(gp, s);   // 8 waves
     case 23: return launch_ring<256, 256, 128, 64, 32, 4, TA, TB, EPI>(gp, s);
     default: return hipErrorInvalidValue;
   }
@@ -934,7 +934,7 @@ void gemm_bf16_kernel_name(const GemmDesc* d, int count, char* out, size_t cap) 
     case 2: snprintf(out, cap, "gemm_bf16_kernel<128, 128, 64, 64, 64, %s, %s, %d, 1>", ta, tb, d[0].epilogue); break;
     case 3: snprintf(out, cap, "gemm_bf16_kernel<256, 256, 128, 64, 64, %s, %s, %d, 1>", ta, tb, d[0].epilogue); break;
     case 6: snprintf(out, cap, "gemm_bf16_kernel<128, 128, 64, 64, 64, %s, %s, %d, 2>", ta, tb, d[0].epilogue); break;
-    case 22: snprintf(out, cap, "gemm_bf16_ring_kernel<128, 128, 64, 64, 64, 4, %s, %s, %d>", ta, tb, d[0].epilogue); break;
+    case 22: snprintf(out, cap, "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, %s, %s, %d>", ta, tb, d[0].epilogue); break;
     case 23: snprintf(out, cap, "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, %s, %s, %d>", ta, tb, d[0].epilogue); break;
     default: snprintf(out, cap, "gemm_bf16 tile %d <%s, %s, %d>", tile, ta, tb, d[0].epilogue); break;
   }

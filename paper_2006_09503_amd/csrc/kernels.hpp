@@ -76,6 +76,7 @@ struct ColsumItem { const void* y; int n; int ld; };
 hipError_t colsum_partial_grouped(const ColsumItem* items, int count, int rows, float* partial, int* parts_out,
                                   int* total_cols_out, int dtype, hipStream_t stream);
 struct FinalizeItem { const float* partial; int parts; int ld; int n; float* out; };
+constexpr int kFinalizeMaxItems = 64;   // segments per launch (the launch's arguments stay under 4 KB)
 hipError_t colsum_finalize_grouped(const FinalizeItem* items, int count, bool accumulate, hipStream_t stream);
 
 // ---------------------------------------------------------------------------- attention

@@ -19,9 +19,9 @@ struct ColsumGroup {
   float* partial;
 };
 struct FinalizeGroup {
-  const float* partial[8];
-  float* out[8];
-  int parts[8], n[8], ld[8], block0[8];
+  const float* partial[kFinalizeMaxItems];
+  float* out[kFinalizeMaxItems];
+  int parts[kFinalizeMaxItems], n[kFinalizeMaxItems], ld[kFinalizeMaxItems], block0[kFinalizeMaxItems];
   int count, accumulate;
 };
 
@@ -320,13 +320,12 @@ __global__ __launch_bounds__(kWg) void colsum_partial_grouped_kernel(ColsumGroup
   }
 }
 
-// out_s[n_s] (+)= sum over parts_s rows of partial_s, for up to 8 segments in one launch
+// out_s[n_s] (+)= sum over parts_s rows of partial_s, for up to kFinalizeMaxItems segments in one launch
 __global__ __launch_bounds__(kWg) void colsum_finalize_grouped_kernel(FinalizeGroup g) {
   __shared__ float red[16][17];
   int sidx = 0;
-#pragma unroll
-  for (int q = 1; q < 8; ++q)
-    if (q < g.count && (int)blockIdx.x >= g.block0[q]) sidx = q;
+  for (int q = 1; q < g.count; ++q)
+    if ((int)blockIdx.x >= g.block0[q]) sidx = q;
   const float* partial = g.partial[sidx];
   const int parts = g.parts[sidx], n = g.n[sidx], ld = g.ld[sidx];
   const int c = threadIdx.x & 15, pl = threadIdx.x >> 4;
@@ -501,7 +500,7 @@ hipError_t colsum_partial_grouped(const ColsumItem* items, int count, int rows, 
 }
 
 hipError_t colsum_finalize_grouped(const FinalizeItem* items, int count, bool accumulate, hipStream_t stream) {
-  if (!items || count < 1 || count > 8) return hipErrorInvalidValue;
+  if (!items || count < 1 || count > kFinalizeMaxItems) return hipErrorInvalidValue;
   FinalizeGroup g{};
   g.count = count;
   g.accumulate = accumulate ? 1 : 0;

@@ -90,8 +90,9 @@ struct stage2bw {
   char* tmp_h = nullptr;
   std::vector<char*> dx1, dchain, du, dqkv;
   char* y_scratch = nullptr;  // recompute: output of the re-run forward
-  float *delta = nullptr, *ln_partial = nullptr, *ln_partial2 = nullptr, *cs_partial = nullptr, *du_partial = nullptr;
-  float* attn_partial = nullptr;
+  float* delta = nullptr;
+  // per layer: partial rows of the bias / gain / shift gradients, reduced by one launch per backward pass
+  std::vector<float*> ln_partial, ln_partial2, cs_partial, du_partial, attn_partial;
 
   // timing
   bool timing = false;
@@ -320,6 +321,9 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
   // every CU busy.  The chain's result dX is enqueued before them.
   std::vector<GemmDesc> wg;
   wg.reserve(4 * c.n_layers);
+  std::vector<FinalizeItem> fin;
+  fin.reserve(8 * c.n_layers);
+  double fin_elems = 0.0;
   auto flush_wgrad = [&]() -> hipError_t {
     for (size_t i0 = 0; i0 < wg.size(); i0 += kGemmMaxGroup) {
       const int n = (int)std::min<size_t>(kGemmMaxGroup, wg.size() - i0);
@@ -351,7 +355,7 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     // out of the kernels that produce those gradients: dx1 and this layer's result dx (= the next
     // lower layer's dy) from the LayerNorm backward kernels, du (bf16 mode) from the epilogue of
     // the GEMM that computes it, dqkv (bf16 mode) from the attention backward kernels; the stage's
-    // incoming dy, and du and dqkv in fp32 mode, are summed by the column-sum kernel.  One reduction launch per layer finishes all of them.
+    // incoming dy, and du and dqkv in fp32 mode, are summed by the column-sum kernel.
     const bool fused_du = st->dtype == kBF16;
     auto dgrad = [&](const void* grad, int N, const char* w_, int K, void* out, const void* u) {
       // out[T,K] = grad[T,N] * W[K,N]^T
@@ -359,7 +363,7 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
       d.dtype = st->dtype;
       d.A = grad; d.lda = N; d.B = w_; d.ldb = N; d.trans_b = true; d.C = out; d.ldc = K;
       d.M = T; d.N = K; d.K = N;
-      if (u) { d.epilogue = kEpiGeluGrad; d.aux = u; if (fused_du) d.colsum_partial = st->du_partial; }
+      if (u) { d.epilogue = kEpiGeluGrad; d.aux = u; if (fused_du) d.colsum_partial = st->du_partial[l]; }
       return run_gemm(st, STAGE_K_GEMM_DGRAD, d);
     };
     // y = x1 + GELU(u) W2 + b2
@@ -370,7 +374,7 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     e = dgrad(du, f, wptr(st, buf, o.w1), h, st->tmp_h, nullptr);        if (e != hipSuccess) return e;
     // c = LN2(x1); dx1 = dy + LN2'(dc)
     int ln2_parts = 0, ln1_parts = 0;
-    e = run_ln_bwd(st, st->tmp_h, A.x1, A.mean2, A.rstd2, wptr(st, buf, o.ln2_g), dy, dx1, st->ln_partial, &ln2_parts);
+    e = run_ln_bwd(st, st->tmp_h, A.x1, A.mean2, A.rstd2, wptr(st, buf, o.ln2_g), dy, dx1, st->ln_partial[l], &ln2_parts);
     if (e != hipSuccess) return e;
     // x1 = x + o Wo + bo
     e = wgrad(A.o, h, dx1, h, st->G + o.wo);                             if (e != hipSuccess) return e;
@@ -378,7 +382,7 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     // attention
     AttnDesc ad = attn_desc(st, lens);
     const bool fused_dqkv = attention_mfma_supported(ad);
-    if (fused_dqkv) ad.colsum_partial = st->attn_partial;
+    if (fused_dqkv) ad.colsum_partial = st->attn_partial[l];
     e = timed(st, STAGE_K_ATTN_BWD, "attention backward (dq + dkv kernels)", attn_flops, 0.0, [&] {
       return attention_bwd(ad, A.qkv, A.o, A.lse, st->tmp_h, dqkv, st->delta, st->cur);
     });
@@ -387,7 +391,7 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     e = wgrad(A.a, h, dqkv, 3 * h, st->G + o.wqkv);                      if (e != hipSuccess) return e;
     e = dgrad(dqkv, 3 * h, wptr(st, buf, o.wqkv), h, st->tmp_h, nullptr);  if (e != hipSuccess) return e;
     // a = LN1(x); dx = dx1 + LN1'(da)
-    e = run_ln_bwd(st, st->tmp_h, A.x, A.mean1, A.rstd1, wptr(st, buf, o.ln1_g), dx1, dx, st->ln_partial2, &ln1_parts);
+    e = run_ln_bwd(st, st->tmp_h, A.x, A.mean1, A.rstd1, wptr(st, buf, o.ln1_g), dx1, dx, st->ln_partial2[l], &ln1_parts);
     if (e != hipSuccess) return e;
     ColsumItem cs[3];
     int n_cs = 0, col_dqkv = -1, col_du = -1, col_dy = -1, cols = 0;
@@ -397,31 +401,33 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     int cs_parts = 0, cs_cols = 0;
     if (n_cs > 0) {
       e = timed(st, STAGE_K_BIAS_GRAD, "colsum_partial_grouped_kernel", 0.0, (double)T * cols * st->esize, [&] {
-        return colsum_partial_grouped(cs, n_cs, T, st->cs_partial, &cs_parts, &cs_cols, st->dtype, st->cur);
+        return colsum_partial_grouped(cs, n_cs, T, st->cs_partial[l], &cs_parts, &cs_cols, st->dtype, st->cur);
       });
       if (e != hipSuccess) return e;
     }
-    FinalizeItem fin[8];
-    int n_fin = 0;
-    double fin_elems = 0.0;
     auto add_fin = [&](const float* partial, int parts, int ld, int n, float* out) {
-      fin[n_fin++] = {partial, parts, ld, n, out};
+      fin.push_back({partial, parts, ld, n, out});
       fin_elems += (double)parts * n;
     };
-    if (fused_dqkv) add_fin(st->attn_partial, attention_colsum_rows(c.microbatch, c.seq), 3 * h, 3 * h, st->G + o.bqkv);
-    else add_fin(st->cs_partial + col_dqkv, cs_parts, cs_cols, 3 * h, st->G + o.bqkv);
-    if (fused_du) add_fin(st->du_partial, (T + 31) / 32, f, f, st->G + o.b1);
-    else add_fin(st->cs_partial + col_du, cs_parts, cs_cols, f, st->G + o.b1);
-    if (col_dy >= 0) add_fin(st->cs_partial + col_dy, cs_parts, cs_cols, h, st->G + o.b2);
-    add_fin(st->ln_partial, ln2_parts, 3 * h, 2 * h, st->G + o.ln2_g);
-    add_fin(st->ln_partial + 2 * h, ln2_parts, 3 * h, h, st->G + o.bo);
-    add_fin(st->ln_partial2, ln1_parts, 3 * h, 2 * h, st->G + o.ln1_g);
-    if (l > 0) add_fin(st->ln_partial2 + 2 * h, ln1_parts, 3 * h, h, st->G + st->off[l - 1].b2);
-    e = timed(st, STAGE_K_BIAS_GRAD, "colsum_finalize_grouped_kernel", 0.0, 4.0 * fin_elems, [&] {
-      return colsum_finalize_grouped(fin, n_fin, acc, st->cur);
+    if (fused_dqkv) add_fin(st->attn_partial[l], attention_colsum_rows(c.microbatch, c.seq), 3 * h, 3 * h, st->G + o.bqkv);
+    else add_fin(st->cs_partial[l] + col_dqkv, cs_parts, cs_cols, 3 * h, st->G + o.bqkv);
+    if (fused_du) add_fin(st->du_partial[l], (T + 31) / 32, f, f, st->G + o.b1);
+    else add_fin(st->cs_partial[l] + col_du, cs_parts, cs_cols, f, st->G + o.b1);
+    if (col_dy >= 0) add_fin(st->cs_partial[l] + col_dy, cs_parts, cs_cols, h, st->G + o.b2);
+    add_fin(st->ln_partial[l], ln2_parts, 3 * h, 2 * h, st->G + o.ln2_g);
+    add_fin(st->ln_partial[l] + 2 * h, ln2_parts, 3 * h, h, st->G + o.bo);
+    add_fin(st->ln_partial2[l], ln1_parts, 3 * h, 2 * h, st->G + o.ln1_g);
+    if (l > 0) add_fin(st->ln_partial2[l] + 2 * h, ln1_parts, 3 * h, h, st->G + st->off[l - 1].b2);
+    dy = dx;
+  }
+  // every layer left its partial rows in buffers of its own: one reduction launch finishes the
+  // bias, gain and shift gradients of the whole stage
+  for (size_t i0 = 0; i0 < fin.size(); i0 += kFinalizeMaxItems) {
+    const int n = (int)std::min<size_t>(kFinalizeMaxItems, fin.size() - i0);
+    hipError_t e = timed(st, STAGE_K_BIAS_GRAD, "colsum_finalize_grouped_kernel", 0.0, 4.0 * fin_elems * n / fin.size(), [&] {
+      return colsum_finalize_grouped(&fin[i0], n, acc, st->cur);
     });
     if (e != hipSuccess) return e;
-    dy = dx;
   }
   return flush_wgrad();
 }
@@ -528,11 +534,22 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
   }
   if (cfg->recompute) ALLOC(st->y_scratch, T * h * E, nullptr);
   ALLOC(st->delta, (int64_t)cfg->microbatch * cfg->n_heads * cfg->seq * 4, nullptr);
-  ALLOC(st->ln_partial, (int64_t)ln_bwd_max_parts() * 3 * h * 4, nullptr);
-  ALLOC(st->ln_partial2, (int64_t)ln_bwd_max_parts() * 3 * h * 4, nullptr);
-  ALLOC(st->du_partial, (int64_t)((T + 31) / 32) * f * 4, nullptr);
-  ALLOC(st->attn_partial, (int64_t)attention_colsum_rows(cfg->microbatch, cfg->seq) * 3 * h * 4, nullptr);
-  ALLOC(st->cs_partial, (int64_t)colsum_max_parts() * (5 * h + f) * 4, nullptr);
+  st->ln_partial.assign(cfg->n_layers, nullptr);
+  st->ln_partial2.assign(cfg->n_layers, nullptr);
+  st->cs_partial.assign(cfg->n_layers, nullptr);
+  st->du_partial.assign(cfg->n_layers, nullptr);
+  st->attn_partial.assign(cfg->n_layers, nullptr);
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    ALLOC(st->ln_partial[l], (int64_t)ln_bwd_max_parts() * 3 * h * 4, nullptr);
+    ALLOC(st->ln_partial2[l], (int64_t)ln_bwd_max_parts() * 3 * h * 4, nullptr);
+    if (st->dtype == kBF16) {
+      ALLOC(st->du_partial[l], (int64_t)((T + 31) / 32) * f * 4, nullptr);
+      ALLOC(st->attn_partial[l], (int64_t)attention_colsum_rows(cfg->microbatch, cfg->seq) * 3 * h * 4, nullptr);
+    }
+    // the column-sum kernel serves the stage's incoming dy (top layer) and, in fp32 mode or for
+    // head sizes without the fused attention kernels, du and dqkv of every layer
+    ALLOC(st->cs_partial[l], (int64_t)colsum_max_parts() * (5 * h + f) * 4, nullptr);
+  }
 #undef ALLOC
 
   // upload W(0): fp32 mode -> both buffers; bf16 mode -> master, then both bf16 buffers
