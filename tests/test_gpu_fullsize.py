@@ -14,11 +14,11 @@ from gpu_util import compare_stage, run_stage_gpu, run_stage_oracle
 pytestmark = pytest.mark.gpu
 
 
-def run(cfg, n_batches, inflight, seed=0):
+def run(cfg, n_batches, inflight, seed=0, two_streams=False):
     gen = synth.StageInputs(cfg, seed)
     w0 = gen.weights()
     mbs = gen.microbatches(n_batches * cfg.m)
-    gpu = run_stage_gpu(cfg, w0, mbs, inflight)
+    gpu = run_stage_gpu(cfg, w0, mbs, inflight, two_streams=two_streams)
     tr = run_stage_oracle(cfg, w0, mbs)
     worst = compare_stage(cfg, gpu, tr)
     print({k: f"{v:.2e}" for k, v in worst.items()})
@@ -32,9 +32,10 @@ def test_bert_large_shape_three_updates():
 
 
 def test_bert_large_full_stage_one_batch():
-    """The benchmark's configuration itself: 6 layers, m = 8, 4 microbatches in flight; one batch."""
+    """The benchmark's configuration itself: 6 layers, m = 8, 4 microbatches in flight, backward
+    passes on a stream of their own; one batch."""
     cfg = synth.PRESETS["C2"]
-    run(cfg, 1, cfg.max_inflight)
+    run(cfg, 1, cfg.max_inflight, two_streams=True)
 
 
 def test_gpt_2560_shape_head_size_80():
