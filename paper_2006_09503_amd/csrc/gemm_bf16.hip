@@ -260,6 +260,29 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
 // 8 lanes (bf16 outputs, 8 columns per lane) or 16 lanes (fp32 accumulator, 4 columns per lane)
 // cover 128 / 256 contiguous bytes of a row, and the residual / pre-activation operands are read
 // the same way.  The arithmetic and its order are those of a direct store: one rounding to bf16.
+// v + (v of lane ^ OFF) without the LDS crossbar (ds_bpermute, which __shfl_xor compiles to, costs
+// several times as much): a DPP rotation inside the 16-lane row, the row and half-wave swaps
+// (of two copies of v: swapping odd rows of one with even rows of the other leaves both partners
+// of every pair in the same lane of the two results) beyond it.
+template <int OFF>
+__device__ __forceinline__ float xor_lane_sum(float v) {
+  static_assert(OFF == 8 || OFF == 16 || OFF == 32, "supported lane distances");
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  if constexpr (OFF == 8) {
+    return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, (int)u, 0x128 /* row_ror:8 */, 0xF, 0xF, false));
+  } else if constexpr (OFF == 16) {
+    // (written as assembly: with the builtin the compiler adds the first result to itself; the
+    // s_nop covers the wait states the swap needs after a VALU write of its operands)
+    unsigned a = u, b = u;
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
+  } else {
+    unsigned a = u, b = u;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
+  }
+}
+
 __device__ __forceinline__ void unpack8(uint4 w, float (&v)[8]) {
   v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xffff0000u);
   v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
@@ -392,10 +415,13 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[MI][NI], const BfPa
       }
       if (EPI == kEpiGeluGrad && p.colsum) {
         // column sums of this 32-row strip: the lanes that share a column group are WN/8 apart
+        static_assert(WN / 8 == 8 || WN / 8 == 16, "lane distance of a column group");
 #pragma unroll
-        for (int off = WN / 8; off < 64; off <<= 1)
-#pragma unroll
-          for (int j = 0; j < 8; ++j) cs[j] += __shfl_xor(cs[j], off, 64);
+        for (int j = 0; j < 8; ++j) {
+          if (WN / 8 == 8) cs[j] = xor_lane_sum<8>(cs[j]);
+          cs[j] = xor_lane_sum<16>(cs[j]);
+          cs[j] = xor_lane_sum<32>(cs[j]);
+        }
         const int col = col_base + lane * 8;
         if (lane < WN / 8 && row_base < p.M && col < p.N) {
           float* dst = p.colsum + (int64_t)(row_base >> 5) * p.N + col;
