@@ -773,7 +773,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
 
   const int nk = p.K / BKA;   // K is a multiple of BKA
   // tile t (clamped past the end: fetched again, never read) goes to stage t & (NS - 1);
-  // dynamic LDS starts at address 0, so a stage's byte address is its offset in smem
+  // a stage's LDS byte address: the low half of a generic pointer into LDS is its LDS address
+  const uint32_t lds_base = (uint32_t)reinterpret_cast<uintptr_t>(smem);
   auto tile_k = [&](int t) { return (t < nk ? t : nk - 1) * BKA; };
   auto issue = [&](int v, int k0, uint32_t stage_bytes) {
     if (v < IPA) ld_a.issue_one_untracked(v, k0, stage_bytes);
@@ -781,7 +782,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
   };
   for (int t = 0; t < NS - 1; ++t)
 #pragma unroll
-    for (int v = 0; v < NV; ++v) issue(v, tile_k(t), (uint32_t)(t * kStage) * 16u);
+    for (int v = 0; v < NV; ++v) issue(v, tile_k(t), lds_base + (uint32_t)(t * kStage) * 16u);
   __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * NV));
   __syncthreads();
   bf16x8 af[2][MI], bfr[2][NI];
@@ -803,7 +804,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
     const uint4* sB = sA + BM * CHK;
     const uint4* nA = smem + ((kt + 1) & (NS - 1)) * kStage;
     const uint4* nB = nA + BM * CHK;
-    const uint32_t l_stage = (uint32_t)(((kt + NS - 1) & (NS - 1)) * kStage) * 16u;
+    const uint32_t l_stage = lds_base + (uint32_t)(((kt + NS - 1) & (NS - 1)) * kStage) * 16u;
     const int k_load = tile_k(kt + NS - 1);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
