@@ -1,19 +1,27 @@
 // bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
 //
-// One workgroup computes a BM x BN tile of C in K steps of 64.  Both operand tiles are staged
-// in LDS in one common form -- [row][64 k] bf16, 128-byte rows, 16-byte chunks XOR-swizzled by
-// row -- whatever the operand's layout in HBM:
-//   * K contiguous in HBM (activations as A, W read for the data gradient): 16-byte global
-//     loads go to LDS as they are;
-//   * K strided in HBM (W[K,N] read for the forward, both operands of the weight gradient):
-//     each thread loads a 4(k) x 8(row) patch with four 16-byte loads along the contiguous
-//     dimension, transposes it in registers and writes eight 8-byte pieces.
-// so the MFMA loop is the same for the forward (NN), data-gradient (NT) and weight-gradient
-// (TN) forms.  Two LDS stages.  Per K step a wave issues the global loads of the next tile
-// first, runs its MFMAs with the LDS fragment reads of sub-step ks+1 in flight behind the MFMAs
-// of sub-step ks, and writes the prefetched tile to the other LDS stage during the last two
-// sub-steps; one barrier per K step.  Out-of-range rows/chunks are loaded from a clamped
-// address and zeroed by select, so the loop has no divergent branches.
+// One workgroup computes a BM x BN tile of C.  Two kernel families share the tile order, the
+// fragment layout and the epilogue:
+//
+//   * the ring kernel (gemm_bf16_ring_kernel, further down): operand tiles go from HBM straight
+//     into LDS (global_load_lds) through a ring of four stages, K-strided operands stay in their
+//     HBM form and are transposed by the LDS read.  It serves every launch whose K is a multiple
+//     of its K tile, which is every GEMM of the workloads;
+//   * the register-staged kernel (gemm_bf16_kernel): K steps of 64 through two LDS stages, any K.
+//     Both operand tiles are staged in one common form -- [row][64 k] bf16, 128-byte rows, 16-byte
+//     chunks XOR-swizzled by row -- whatever the operand's layout in HBM:
+//       - K contiguous in HBM (activations as A, W read for the data gradient): 16-byte global
+//         loads go to LDS as they are;
+//       - K strided in HBM (W[K,N] read for the forward, both operands of the weight gradient):
+//         each thread loads a 4(k) x 8(row) patch with four 16-byte loads along the contiguous
+//         dimension, transposes it in registers and writes eight 8-byte pieces.
+//     Per K step a wave issues the global loads of the next tile first, runs its MFMAs with the
+//     LDS fragment reads of sub-step ks+1 in flight behind the MFMAs of sub-step ks, and writes
+//     the prefetched tile to the other LDS stage during the last two sub-steps; one barrier per K
+//     step.  Out-of-range rows/chunks are loaded from a clamped address and zeroed by select, so
+//     the loop has no divergent branches.
+// The MFMA loop is the same for the forward (NN), data-gradient (NT) and weight-gradient (TN)
+// forms in both families.
 //
 // Lane layout of v_mfma_f32_32x32x16_bf16: lane l supplies row (l % 32) of the first operand and
 // column (l % 32) of the second, k = 8*(l/32) .. +7; it receives column (l % 32) of D, rows
