@@ -157,6 +157,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--flush", action="store_true", help="PipeDream-Flush (Section 3.2) instead of 2BW: one version, drain per batch")
     ap.add_argument("--recompute", type=int, default=None, help="override the workload's activation recomputation (0/1)")
+    ap.add_argument("--microbatch", type=int, default=None, help="override the workload's microbatch size b (an extra "
+                    "measurement: recomputation frees the memory for a larger b, Section 4.1 and the appendix)")
     ap.add_argument("--stages", type=int, default=1, help="d > 1: a d-stage 2BW pipeline of such stages in this process, one "
                     "HIP stream per stage, squared-error loss behind the last (an extra measurement, not the headline)")
     ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
@@ -183,6 +185,8 @@ def main():
         cfg = cfg.with_(flush=1)
     if args.recompute is not None:
         cfg = cfg.with_(recompute=args.recompute)
+    if args.microbatch is not None:
+        cfg = cfg.with_(microbatch=args.microbatch)
     p, m = cfg.max_inflight, cfg.m
     K, W = args.steps, args.warmup
     assert K >= 1 and W >= 2, "two warm-up batches are needed before the version rule leaves version 0"
