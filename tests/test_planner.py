@@ -111,3 +111,18 @@ def test_library_planner_rejects_bad_input():
     assert pl.throughput(1, 4, 3, 1)[0] == B.ERR_INVALID_ARG        # 3 is not a candidate size
     assert pl.memory(1, 4, 4, 7)[0] == B.ERR_INVALID_ARG
     assert B.Planner(profile(memory_capacity=1e6)).partition()[0] == -2
+
+
+def test_plan_with_the_measured_mi355x_profile():
+    """The example profile (this build's measured block times and stage sizes, 288 GB per GPU): a model that
+    fits in one GPU is replicated, not pipelined; one that does not is split into the shallowest pipeline
+    that fits, exactly what the brute-force oracle picks."""
+    from paper_2006_09503_amd import plan_mi355x as pm
+    rc, (w, d, b, mode, g, thr, mem) = pm.plan(8, 24, 512)
+    assert rc == 0 and (w, d, mode) == (8, 1, B.PLANNER_NO_PIPELINE) and w * b * g == 512
+    for n_gpus, n_blocks, batch in ((64, 768, 2048), (16, 1536, 512)):
+        prof = pm.Mi355xProfile(n_blocks=n_blocks, n_gpus=n_gpus, global_batch=batch)
+        rc, got = pm.plan(n_gpus, n_blocks, batch)
+        want = op.partition(prof)
+        assert rc == 0 and got[1] > 1 and got[3] != B.PLANNER_NO_PIPELINE
+        assert got[5] == pytest.approx(want[5], rel=1e-12) and got[6] <= prof.memory_capacity
