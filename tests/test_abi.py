@@ -81,6 +81,7 @@ def test_null_arguments_return_invalid_arg():
     assert L.stage_backward(None, 1, None, None) == binding.ERR_INVALID_ARG
     assert L.stage_coalesce_update(None) == binding.ERR_INVALID_ARG
     assert L.stage_swap_versions(None) == binding.ERR_INVALID_ARG
+    assert L.stage_set_backward_stream(None, None) == binding.ERR_INVALID_ARG
     assert L.stage_destroy(None) == binding.ERR_INVALID_ARG
     assert L.stage_sched_swap_versions(None) == binding.ERR_INVALID_ARG
     h = ctypes.c_void_p()
