@@ -58,6 +58,7 @@ struct GroupParams {
   BfParams p[kMaxGroup];
   int tile_start[kMaxGroup + 1];
   int count;
+  int n_tiles;   // = tile_start[count] = the launch's workgroups
 };
 
 // Chunk swizzle.  Three LDS access patterns have to avoid bank conflicts at once: fragment
@@ -257,6 +258,33 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
   const int t_in = t - group * per_group;
   bm = first_m + t_in % gm;
   bn = t_in / gm;
+}
+
+// The problem and the tile of a workgroup.  Consecutive workgroup ids land on different XCDs
+// (round-robin over 8), so each XCD gets a contiguous run of tiles: they share A rows / B columns
+// in that XCD's L2.  Kernel arguments live in device memory and every dependent round of loads
+// from them costs the better part of a microsecond before the first tile can be requested: with
+// one problem in the launch (all but the grouped weight-gradient launches) everything here comes
+// from one round -- problem 0 is read unconditionally and replaced only in a grouped launch.
+// Returns a copy of the problem for the code in front of the K loop (only the fields used there
+// are kept); the epilogue reads its operands through gp.p[g], where their latency does not matter
+// and they occupy no registers during the loop.
+__device__ __forceinline__ BfParams select_problem(const GroupParams& gp, int& wg, int& g) {
+  wg = blockIdx.x;
+  const int per_xcd = gp.n_tiles / 8;
+  if (wg < per_xcd * 8) wg = (wg % 8) * per_xcd + wg / 8;
+  BfParams p = gp.p[0];
+  g = 0;
+  if (gp.count > 1) {
+#pragma unroll
+    for (int q = 1; q < kMaxGroup; ++q)
+      if (q < gp.count && wg >= gp.tile_start[q]) g = q;
+    if (g > 0) {
+      p = gp.p[g];
+      wg -= gp.tile_start[g];
+    }
+  }
+  return p;
 }
 
 // Epilogue shared by the GEMM kernels.  A lane's accumulators are one row m = .. + (lane % 32) and,
@@ -480,20 +508,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KSPLIT) void gemm_bf16
   const int tid = threadIdx.x - kg * NT, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
-  // Workgroup -> tile: consecutive workgroup ids land on different XCDs (round-robin over 8),
-  // so give each XCD a contiguous run of tiles: they share A rows / B columns in that XCD's L2.
-  const int n_tiles = gp.tile_start[gp.count];
-  int wg = blockIdx.x;
-  {
-    const int per_xcd = n_tiles / 8;
-    if (wg < per_xcd * 8) wg = (wg % 8) * per_xcd + wg / 8;
-  }
-  int g = 0;
-#pragma unroll
-  for (int q = 1; q < kMaxGroup; ++q)
-    if (q < gp.count && wg >= gp.tile_start[q]) g = q;
-  const BfParams& p = gp.p[g];
-  wg -= gp.tile_start[g];
+  int wg, g;
+  const BfParams p = select_problem(gp, wg, g);
   int bm, bn;
   tile_coords(wg, p.tiles_m, p.tiles_n, bm, bn);
   const int m0 = bm * BM, n0 = bn * BN;
@@ -630,9 +646,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KSPLIT) void gemm_bf16
     }
     // strips live behind the exchange buffer: no wave overwrites partial sums another still reads
     constexpr int kXchg = H * NI * 4 * 2 * NT;   // float4 = uint4 units
-    epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane, smem_all + kXchg, (int)threadIdx.x >> 6, kg * H, H);
+    epilogue<MI, NI, WM, WN, EPI>(acc, gp.p[g], m0, n0, wm, wn, lane, smem_all + kXchg, (int)threadIdx.x >> 6, kg * H, H);
   } else {
-    epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane, smem_all, wave, 0, MI);
+    epilogue<MI, NI, WM, WN, EPI>(acc, gp.p[g], m0, n0, wm, wn, lane, smem_all, wave, 0, MI);
   }
 }
 
@@ -748,18 +764,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  const int n_tiles = gp.tile_start[gp.count];
-  int wg = blockIdx.x;
-  {
-    const int per_xcd = n_tiles / 8;
-    if (wg < per_xcd * 8) wg = (wg % 8) * per_xcd + wg / 8;
-  }
-  int g = 0;
-#pragma unroll
-  for (int q = 1; q < kMaxGroup; ++q)
-    if (q < gp.count && wg >= gp.tile_start[q]) g = q;
-  const BfParams& p = gp.p[g];
-  wg -= gp.tile_start[g];
+  int wg, g;
+  const BfParams p = select_problem(gp, wg, g);
   int bm, bn;
   tile_coords(wg, p.tiles_m, p.tiles_n, bm, bn);
   const int m0 = bm * BM, n0 = bn * BN;
@@ -845,7 +851,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
   // the last prefetches may still be landing in LDS, which the epilogue re-uses
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   __syncthreads();
-  epilogue<MI, NI, WM, WN, EPI>(acc, p, m0, n0, wm, wn, lane, smem, wave, 0, MI);
+  epilogue<MI, NI, WM, WN, EPI>(acc, gp.p[g], m0, n0, wm, wn, lane, smem, wave, 0, MI);
 }
 
 template <int BM, int BN, int WM, int WN, int BKA, int NS, bool TA, bool TB, int EPI>
@@ -869,6 +875,7 @@ hipError_t launch_ring(GroupParams gp, hipStream_t s) {
     total += gp.p[g].tiles_m * gp.p[g].tiles_n;
   }
   for (int g = gp.count; g <= kMaxGroup; ++g) gp.tile_start[g] = total;
+  gp.n_tiles = total;
   hipLaunchKernelGGL(kern, dim3(total), dim3(NT), lds, s, gp);
   return hipGetLastError();
 }
@@ -894,6 +901,7 @@ hipError_t launch(GroupParams gp, hipStream_t s) {
     total += gp.p[g].tiles_m * gp.p[g].tiles_n;
   }
   for (int g = gp.count; g <= kMaxGroup; ++g) gp.tile_start[g] = total;
+  gp.n_tiles = total;
   hipLaunchKernelGGL(kern, dim3(total), dim3(NT), lds, s, gp);
   return hipGetLastError();
 }
