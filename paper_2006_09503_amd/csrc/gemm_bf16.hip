@@ -270,15 +270,16 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
 // are kept); the epilogue reads its operands through gp.p[g], where their latency does not matter
 // and they occupy no registers during the loop.
 __device__ __forceinline__ BfParams select_problem(const GroupParams& gp, int& wg, int& g) {
-  wg = blockIdx.x;
-  const int per_xcd = gp.n_tiles / 8;
-  if (wg < per_xcd * 8) wg = (wg % 8) * per_xcd + wg / 8;
   BfParams p = gp.p[0];
+  const int count = gp.count;
+  const int b = blockIdx.x, per_xcd = gp.n_tiles / 8;
+  const int in_run = -(int)(b < per_xcd * 8);   // (mask arithmetic, not a branch: all the loads above stay in one round)
+  wg = (((b % 8) * per_xcd + b / 8) & in_run) | (b & ~in_run);
   g = 0;
-  if (gp.count > 1) {
+  if (count > 1) {
 #pragma unroll
     for (int q = 1; q < kMaxGroup; ++q)
-      if (q < gp.count && wg >= gp.tile_start[q]) g = q;
+      if (q < count && wg >= gp.tile_start[q]) g = q;
     if (g > 0) {
       p = gp.p[g];
       wg -= gp.tile_start[g];
