@@ -248,3 +248,62 @@ def test_parity_metrics_see_planted_mistakes():
     dW_good = good.W[2] - good.W[1]
     assert rel(good.W[2] - good.W[0], dW_good) > 0.5
     assert rel(good.W[0] + dW_good, good.W[2]) < 2e-1
+
+
+# ----------------------------------------------------------------------------- the composition, against library routines
+
+@pytest.mark.parametrize("mask", [ob.MASK_CAUSAL, ob.MASK_PADDING])
+def test_whole_stage_under_2bw_against_autograd_and_torch_adam(mask):
+    """The composition itself -- a transformer stage trained under the version rule with coalescing and
+    Adam -- against an implementation that shares nothing with the oracle: the block written with torch
+    functions, gradients from autograd, the update from torch.optim.Adam, and the delay written out as in
+    Section 3.1: the gradient of batch t is taken at W(t-1) (W(0) for the first two batches), averaged over
+    the m microbatches, and applied to W(t)."""
+    import torch
+    from test_oracle_block import _torch_block, rand_params
+    rng = np.random.default_rng(21)
+    L, h, a, f, s, b, m, n_batches = 2, 32, 4, 64, 10, 2, 3, 5
+    lr = 1e-2
+    st = ob.Stage(L, h, a, f, mask)
+    w0 = rand_params(rng, L, h, f, scale=0.2)
+    mbs = []
+    for _ in range(m * n_batches):
+        x, dy = rng.standard_normal((b, s, h)), rng.standard_normal((b, s, h))
+        lens = rng.integers(3, s + 1, size=b) if mask == ob.MASK_PADDING else None
+        mbs.append((x, dy, lens))
+    tr = tb.replay(lambda w, x, dy, lens: st.vjp(w, x, dy, lens), w0, mbs, m, tb.Adam(lr), inflight=2)
+
+    def grad_at(w, x, dy, lens):
+        wt = torch.tensor(w, dtype=torch.float64, requires_grad=True)
+        z, off = torch.tensor(x, dtype=torch.float64), 0
+        for _ in range(L):
+            p = {}
+            for name, shape in ob.layer_shapes(h, f):
+                n = int(np.prod(shape))
+                p[name] = wt[off:off + n].reshape(shape)
+                off += n
+            z = _torch_block(p, z, lens, mask, a, 1e-5)
+        (z * torch.tensor(dy)).sum().backward()
+        return wt.grad.numpy()
+
+    W = [np.array(w0)]
+    newest = torch.nn.Parameter(torch.tensor(w0, dtype=torch.float64))
+    opt = torch.optim.Adam([newest], lr=lr, betas=(0.9, 0.999), eps=1e-8)
+    for t in range(n_batches):
+        stale = W[max(t - 1, 0)]
+        g = sum(grad_at(stale, *mbs[t * m + j]) for j in range(m)) / m
+        newest.grad = torch.tensor(g)
+        opt.step()
+        W.append(newest.detach().numpy().copy())
+    # Adam's quotient mhat / (sqrt(vhat) + eps) is +-1 on the first step wherever |g| >> eps, and entries with
+    # |g| near eps carry the gradients' rounding (1e-16 relative to the largest entry) at full size: 1e-8 is
+    # far above that and far below what any mistake in the rule would give (compared below).
+    for t in range(n_batches + 1):
+        assert rel(tr.W[t], W[t]) < 1e-8, t
+    # what the bar separates: one update more or less is five orders of magnitude away, and so is a replay
+    # with a mistake planted in the rule (no delay; the delay one batch too long)
+    assert rel(W[2], W[1]) > 1e-3
+    for wrong in (lambda k, m_: (k - 1) // m_, lambda k, m_: max((k - 1) // m_ - 2, 0)):
+        bad = tb.replay(lambda w, x, dy, lens: st.vjp(w, x, dy, lens), w0, mbs, m, tb.Adam(lr), inflight=1,
+                        version_rule=wrong)
+        assert max(rel(bad.W[t], W[t]) for t in range(n_batches + 1)) > 1e-4
