@@ -58,6 +58,8 @@ typedef struct {
   int32_t ffn;          /* f, multiple of 8                                                 */
   int32_t seq;          /* s                                                                */
   int32_t microbatch;   /* b sequences per microbatch; tokens T = b*s                       */
+                        /* T <= 2^24; T*max(f, 3h) and h*f below 2^30 elements (the kernels  */
+                        /* address an operand with 32-bit byte offsets); h <= 16384          */
   int32_t m;            /* microbatches per coalesced update; m >= max_inflight (Sec. 3.1:  */
                         /* a new version every m >= d microbatches)                         */
   int32_t max_inflight; /* activation stash slots = microbatches in flight at this stage    */

@@ -678,7 +678,7 @@ struct AsyncLoader {
   static constexpr int IPW = kSlots / 64 / NW;      // load instructions per wave
   static_assert(kSlots % (64 * NW) == 0, "tile/waves mismatch");
   const bf16_t* base_;
-  uint32_t voff[IPW];
+  uint32_t voff[IPW];   // byte offsets from the tile's base
   int ld_, first_slot_;
   __device__ __forceinline__ void init(const bf16_t* base, int ld, int rows_valid, int wave, int lane) {
     base_ = base; ld_ = ld;
@@ -690,14 +690,14 @@ struct AsyncLoader {
         const int row = L / CHK, pc = L % CHK;
         const int c = pc ^ swz<CHK>(row);
         const int rc = row < rows_valid ? row : rows_valid - 1;
-        voff[j] = (uint32_t)rc * (uint32_t)ld + c * 8;
+        voff[j] = ((uint32_t)rc * (uint32_t)ld + c * 8) * 2u;
       } else {
         constexpr int PPR = R / 8;                  // pieces per k row
         const int k = L / PPR, pp = L % PPR;
         const int piece = pp ^ ((k & 3) << 1);
         int col = piece * 8;
         if (col >= rows_valid) col = rows_valid - 8;
-        voff[j] = (uint32_t)k * (uint32_t)ld + col;
+        voff[j] = ((uint32_t)k * (uint32_t)ld + col) * 2u;
       }
     }
   }
@@ -705,13 +705,21 @@ struct AsyncLoader {
   // store to LDS: it would otherwise put s_waitcnt vmcnt(0) in front of every later LDS read (it
   // cannot tell the ring's stages apart), and the loads of the tiles further ahead could not stay
   // in flight.  The caller waits (vmcnt) and synchronises before anyone reads the stage.
-  // lds_stage: byte address of the stage's tile in LDS, wave-uniform.
+  // Addressing: the tile's base in a scalar register pair plus this lane's 32-bit byte offset
+  // (operands are smaller than 2 GiB, checked on the host): the per-tile address arithmetic stays
+  // on the scalar unit and a load sends half the address data of the 64-bit form (+2..5 % on the
+  // weight-gradient form).
+  // lds_tile: byte address of the stage's tile in LDS, wave-uniform.
   __device__ __forceinline__ void issue_one_untracked(int j, int k0, uint32_t lds_tile) const {
     const bf16_t* b = K_CONTIG ? base_ + k0 : base_ + (int64_t)k0 * ld_;
     const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + (uint32_t)(first_slot_ + j * 64) * 16u);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+    const uint64_t bb = reinterpret_cast<uint64_t>(b);   // wave-uniform
+    const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(bb >> 32));
+    const uint32_t b_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)bb);
+    const uint64_t sb = ((uint64_t)b_hi << 32) | (uint64_t)b_lo;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(dst), "v"(b + voff[j])
+                 : "s"(dst), "v"(voff[j]), "s"(sb)
                  : "memory");   // (M0 is reserved: the compiler keeps nothing in it)
   }
 };
@@ -991,6 +999,10 @@ hipError_t gemm_bf16_grouped(const GemmDesc* d, int count, hipStream_t stream) {
   gp.count = count;
   for (int g = 0; g < count; ++g) {
     if (!vector_ok(d[g])) return hipErrorInvalidValue;
+    // the kernels address an operand with 32-bit byte offsets from its first element
+    const int64_t a_rows = d[g].trans_a ? d[g].K : d[g].M, b_rows = d[g].trans_b ? d[g].N : d[g].K;
+    if (a_rows * (int64_t)d[g].lda * 2 >= (1ll << 31) || b_rows * (int64_t)d[g].ldb * 2 >= (1ll << 31))
+      return hipErrorInvalidValue;
     if (d[g].trans_a != d[0].trans_a || d[g].trans_b != d[0].trans_b || d[g].epilogue != d[0].epilogue)
       return hipErrorInvalidValue;
     gp.p[g] = to_params(d[g]);

@@ -133,6 +133,9 @@ int validate(const stage_config_t* c) {
       !(c->adam_eps >= 0.f) || !(c->ln_eps >= 0.f))
     return STAGE_ERR_INVALID_ARG;
   if ((int64_t)c->seq * c->microbatch > (1 << 24)) return STAGE_ERR_INVALID_ARG;
+  // every GEMM operand below 2 GiB in bf16 (32-bit byte offsets in the kernels)
+  const int64_t T = (int64_t)c->seq * c->microbatch, widest = c->ffn > 3 * c->hidden ? c->ffn : 3 * c->hidden;
+  if (T * widest >= (1ll << 30) || (int64_t)c->hidden * c->ffn >= (1ll << 30)) return STAGE_ERR_INVALID_ARG;
   return STAGE_OK;
 }
 

@@ -51,7 +51,9 @@ def test_param_counts_of_the_workload_shapes():
 
 @pytest.mark.parametrize("bad", [dict(hidden=100), dict(n_heads=3), dict(m=1, max_inflight=2), dict(mask_mode=5),
                                  dict(precision=7), dict(n_layers=0), dict(ffn=12), dict(hidden=16, n_heads=4),
-                                 dict(beta1=1.0), dict(recompute=2)])
+                                 dict(beta1=1.0), dict(recompute=2),
+                                 dict(hidden=16384, n_heads=128, ffn=65536),          # h*f = 2^30 elements
+                                 dict(seq=4096, microbatch=1024, ffn=256)])           # T*f = 2^30 elements
 def test_invalid_configs_are_rejected(bad):
     cfg = synth.PRESETS["C1"].with_(**bad)
     with pytest.raises(binding.StageError) as e:

@@ -186,6 +186,9 @@ def test_gemm_rejects_shapes_it_cannot_take():
     assert L.k2bw_gemm(F32, 0, 0, 0, 0, 8, 8, p, 8, p, 8, p, 8, None, None, None, 0, None) == B.ERR_INVALID_ARG     # empty
     assert L.k2bw_gemm(F32, 0, 0, 1, 8, 8, 8, p, 8, p, 8, p, 8, None, None, None, 0, None) == B.ERR_INVALID_ARG     # GELU without bias
     assert L.k2bw_gemm(3, 0, 0, 0, 8, 8, 8, p, 8, p, 8, p, 8, None, None, None, 0, None) == B.ERR_INVALID_ARG
+    big = 1 << 27   # 8 rows of 2^27 bf16 = 2 GiB: past the kernels' 32-bit byte offsets
+    assert L.k2bw_gemm(BF16, 0, 0, 0, 8, 8, 8, p, big, p, 8, p, 8, None, None, None, 0, None) == B.ERR_INVALID_ARG
+    assert L.k2bw_gemm(BF16, 0, 0, 0, 8, 8, 8, p, 8, p, big, p, 8, None, None, None, 0, None) == B.ERR_INVALID_ARG
 
 
 # ----------------------------------------------------------------------------- LayerNorm
