@@ -50,15 +50,18 @@ struct BfParams {
   float* colsum;   // GELU' epilogue: partial[ceil(M/32)][N] column sums of the result, or null
   int accumulate;
   int tiles_m, tiles_n;
+  int tile_m;      // rows of C per tile: the kernel's BM, or BM/2 in the balanced tail of a ring launch
 };
 
 // Up to kMaxGroup independent GEMMs of the same form in one launch: workgroup ids
 // [tile_start[g], tile_start[g+1]) belong to problem g.
+constexpr int kMaxProblems = kMaxGroup + 1;   // + one problem split in two for the balanced tail
 struct GroupParams {
-  BfParams p[kMaxGroup];
-  int tile_start[kMaxGroup + 1];
+  BfParams p[kMaxProblems];
+  int tile_start[kMaxProblems + 1];
   int count;
   int n_tiles;   // = tile_start[count] = the launch's workgroups
+  int seg1, seg2;   // multiples of 8: workgroups [0, seg1) and [seg1, seg1 + seg2) are each dealt to the XCDs in runs
 };
 
 // Chunk swizzle.  Three LDS access patterns have to avoid bank conflicts at once: fragment
@@ -272,13 +275,15 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
 __device__ __forceinline__ BfParams select_problem(const GroupParams& gp, int& wg, int& g) {
   BfParams p = gp.p[0];
   const int count = gp.count;
-  const int b = blockIdx.x, per_xcd = gp.n_tiles / 8;
-  const int in_run = -(int)(b < per_xcd * 8);   // (mask arithmetic, not a branch: all the loads above stay in one round)
-  wg = (((b % 8) * per_xcd + b / 8) & in_run) | (b & ~in_run);
+  // (mask arithmetic, not branches: all the loads above stay in one round)
+  const int b = blockIdx.x, seg1 = gp.seg1, seg2 = gp.seg2;
+  const int in1 = -(int)(b < seg1), in2 = -(int)(b >= seg1 && b < seg1 + seg2);
+  const int b2 = b - seg1;
+  wg = (((b % 8) * (seg1 / 8) + b / 8) & in1) | ((seg1 + (b2 % 8) * (seg2 / 8) + b2 / 8) & in2) | (b & ~(in1 | in2));
   g = 0;
   if (count > 1) {
 #pragma unroll
-    for (int q = 1; q < kMaxGroup; ++q)
+    for (int q = 1; q < kMaxProblems; ++q)
       if (q < count && wg >= gp.tile_start[q]) g = q;
     if (g > 0) {
       p = gp.p[g];
@@ -777,11 +782,16 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
   const BfParams p = select_problem(gp, wg, g);
   int bm, bn;
   tile_coords(wg, p.tiles_m, p.tiles_n, bm, bn);
-  const int m0 = bm * BM, n0 = bn * BN;
+  // A launch may end with tiles of BM/2 rows (see launch_ring): the waves of the lower half then only
+  // take part in the loads and barriers.
+  constexpr bool kCanHalve = BM == 2 * WM;
+  const int tile_m = kCanHalve ? p.tile_m : BM;
+  const bool active = !kCanHalve || wm * WM < tile_m;   // wave-uniform
+  const int m0 = bm * tile_m, n0 = bn * BN;
 
   AsyncLoader<BM, NW, BKA, !TA> ld_a;
   AsyncLoader<BN, NW, BKA, TB> ld_b;
-  ld_a.init(TA ? p.A + m0 : p.A + (int64_t)m0 * p.lda, p.lda, p.M - m0, wave, lane);
+  ld_a.init(TA ? p.A + m0 : p.A + (int64_t)m0 * p.lda, p.lda, min(p.M - m0, tile_m), wave, lane);
   ld_b.init(TB ? p.B + (int64_t)n0 * p.ldb : p.B + n0, p.ldb, p.N - n0, wave, lane);
   constexpr int IPA = decltype(ld_a)::IPW, NV = IPA + decltype(ld_b)::IPW;   // loads per wave and tile
 
@@ -822,6 +832,21 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
   constexpr int EVERY = KS * NM / NV;
   constexpr int NV_PRE = ((KS - 1) * NM + EVERY - 1) / EVERY;   // loads issued before the barrier
   static_assert((NS - 3) * NV + NV_PRE <= 63, "vmcnt range");
+  if (!active) {
+    // same loads, waits and barriers as below, no fragments and no MFMAs: the step's loads follow its
+    // barrier, so at the wait the tiles kt+2 .. kt+NS-2 may be outstanding
+    for (int kt = 0; kt < nk; ++kt) {
+      const uint32_t l_stage = lds_base + (uint32_t)(((kt + NS - 1) & (NS - 1)) * kStage) * 16u;
+      const int k_load = tile_k(kt + NS - 1);
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 3) * NV));
+      __syncthreads();
+#pragma unroll
+      for (int v = 0; v < NV; ++v) issue(v, k_load, l_stage);
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+    return;
+  }
   for (int kt = 0; kt < nk; ++kt) {
     const uint4* sA = smem + (kt & (NS - 1)) * kStage;
     const uint4* sB = sA + BM * CHK;
@@ -863,6 +888,43 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
   epilogue<MI, NI, WM, WN, EPI>(acc, gp.p[g], m0, n0, wm, wn, lane, smem, wave, 0, MI);
 }
 
+#ifndef K2BW_BALANCE_TAIL
+#define K2BW_BALANCE_TAIL 1
+#endif
+int g_balance_tail = K2BW_BALANCE_TAIL;   // build-time tuning aid: 0 switches the half-row tail of the ring launches off
+
+int compute_units() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    n = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+            ? prop.multiProcessorCount : 256;
+  }
+  return n;
+}
+
+// Rows [m_split, M) of problem q as a problem of its own (m_split a multiple of 32).
+template <bool TA, int EPI>
+BfParams lower_rows(const BfParams& q, int m_split) {
+  BfParams r = q;
+  r.M = q.M - m_split;
+  r.A = TA ? q.A + m_split : q.A + (int64_t)m_split * q.lda;
+  const int64_t c_off = (int64_t)m_split * q.ldc;
+  r.C = EPI == kEpiAccum ? static_cast<void*>(static_cast<float*>(q.C) + c_off)
+                         : static_cast<void*>(static_cast<bf16_t*>(q.C) + c_off);
+  if (q.aux) r.aux = q.aux + c_off;
+  if (q.aux_out) r.aux_out = q.aux_out + c_off;
+  if (q.colsum) r.colsum = q.colsum + (int64_t)(m_split / 32) * q.N;
+  return r;
+}
+
+// A launch of T tiles on n CUs takes ceil(T / n) rounds of one tile per CU.  When the last round
+// would fill at most half of the CUs (T mod n in 1..n/2, T > n) the rows of its tiles are given to
+// twice as many workgroups with tiles of BM/2 rows, in which half of the waves run the MFMAs: that
+// round then takes about 0.6 of a full one (the B tile is still loaded whole).  The halved tiles
+// are the launch's last problems, or the last tile rows of one that is split in two for this;
+// they are dispatched last because the XCD remap treats them as a segment of its own.
 template <int BM, int BN, int WM, int WN, int BKA, int NS, bool TA, bool TB, int EPI>
 hipError_t launch_ring(GroupParams gp, hipStream_t s) {
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
@@ -876,15 +938,51 @@ hipError_t launch_ring(GroupParams gp, hipStream_t s) {
     if (e != hipSuccess) return e;
     configured = true;
   }
-  int total = 0;
+  int64_t full = 0;
   for (int g = 0; g < gp.count; ++g) {
+    gp.p[g].tile_m = BM;
     gp.p[g].tiles_m = ceil_div(gp.p[g].M, BM);
     gp.p[g].tiles_n = ceil_div(gp.p[g].N, BN);
+    full += (int64_t)gp.p[g].tiles_m * gp.p[g].tiles_n;
+  }
+  int first_half = gp.count;   // problems [first_half, count) get tiles of BM/2 rows
+  if (BM == 2 * WM && g_balance_tail) {
+    const int n_cu = compute_units();
+    int64_t need = full % n_cu;
+    if (full > n_cu && need > 0 && need <= n_cu / 2) {
+      while (need > 0 && first_half > 0) {
+        BfParams& q = gp.p[first_half - 1];
+        const int64_t t = (int64_t)q.tiles_m * q.tiles_n;
+        const int rows = (int)ceil_div(need, (int64_t)q.tiles_n);   // tile rows of q still wanted
+        if (t <= need || rows >= q.tiles_m) {
+          --first_half;
+          need -= t;
+        } else {
+          // split q: its last `rows` tile rows become a problem of their own behind it
+          const int m_split = (q.tiles_m - rows) * BM;
+          for (int g = gp.count; g > first_half; --g) gp.p[g] = gp.p[g - 1];
+          gp.p[first_half] = lower_rows<TA, EPI>(q, m_split);
+          q.M = m_split;
+          q.tiles_m -= rows;
+          ++gp.count;
+          need = 0;
+        }
+      }
+      for (int g = first_half; g < gp.count; ++g) {
+        gp.p[g].tile_m = BM / 2;
+        gp.p[g].tiles_m = ceil_div(gp.p[g].M, BM / 2);
+      }
+    }
+  }
+  int total = 0;
+  for (int g = 0; g < gp.count; ++g) {
     gp.tile_start[g] = total;
     total += gp.p[g].tiles_m * gp.p[g].tiles_n;
   }
-  for (int g = gp.count; g <= kMaxGroup; ++g) gp.tile_start[g] = total;
+  for (int g = gp.count; g <= kMaxProblems; ++g) gp.tile_start[g] = total;
   gp.n_tiles = total;
+  gp.seg1 = (first_half < gp.count ? gp.tile_start[first_half] : total) / 8 * 8;
+  gp.seg2 = (total - gp.seg1) / 8 * 8;
   hipLaunchKernelGGL(kern, dim3(total), dim3(NT), lds, s, gp);
   return hipGetLastError();
 }
@@ -909,8 +1007,10 @@ hipError_t launch(GroupParams gp, hipStream_t s) {
     gp.tile_start[g] = total;
     total += gp.p[g].tiles_m * gp.p[g].tiles_n;
   }
-  for (int g = gp.count; g <= kMaxGroup; ++g) gp.tile_start[g] = total;
+  for (int g = gp.count; g <= kMaxProblems; ++g) gp.tile_start[g] = total;
   gp.n_tiles = total;
+  gp.seg1 = total / 8 * 8;
+  gp.seg2 = 0;
   hipLaunchKernelGGL(kern, dim3(total), dim3(NT), lds, s, gp);
   return hipGetLastError();
 }

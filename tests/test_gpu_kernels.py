@@ -156,9 +156,20 @@ def test_gemm_every_tile_variant(tile, M, N, K):
         assert L.k2bw_tune_gemm_tile(0) == 0
 
 
-@pytest.mark.parametrize("M,N,K", [(296, 264, 200), (4096, 1032, 136), (520, 4096, 64)])
+@pytest.mark.parametrize("M,N,K", [(4360, 4096, 64), (4096, 4360, 96)])
+def test_gemm_balanced_tail_of_a_256_tile_launch(M, N, K):
+    """A launch whose last round of 256x256 tiles would leave most CUs idle gives the rows of those tiles to
+    half-height tiles: 4360 x 4096 is 18 x 16 = 288 tiles (the last two tile rows, 264 rows, are split off and
+    halved: 128 + 128 + 8 rows); 4096 x 4360 is 16 x 18 (the last tile row halved).  All three forms, the
+    two-output epilogue and in-place accumulation."""
+    test_gemm_every_tile_variant(23, M, N, K)
+
+
+@pytest.mark.parametrize("M,N,K", [(296, 264, 200), (4096, 1032, 136), (520, 4096, 64), (4360, 4096, 64)])
 def test_gemm_gelu_gradient_with_fused_bias_gradient(M, N, K):
-    """du = (dy W^T) * GELU'(u) and db = colsum(du) from the same pass (bf16), overwrite then accumulate."""
+    """du = (dy W^T) * GELU'(u) and db = colsum(du) from the same pass (bf16), overwrite then accumulate.
+    The last shape is 288 tiles of 256x256: its last two tile rows (264 rows) run as five rows of
+    half-height tiles, split off as a problem of their own with its own partial-sum rows."""
     rng = np.random.default_rng(M + N + K)
     dy, w, u = rnd(rng, (M, K), BF16), rnd(rng, (N, K), BF16, 0.1), rnd(rng, (M, N), BF16)
     want = (dy.astype(np.float64) @ w.astype(np.float64).T) * ob.gelu_grad(u.astype(np.float64))
