@@ -807,7 +807,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
   const int nk = p.K / BKA;   // K is a multiple of BKA
   // tile t (clamped past the end: fetched again, never read) goes to stage t & (NS - 1);
   // a stage's LDS byte address: the low half of a generic pointer into LDS is its LDS address
-  const uint32_t lds_base = (uint32_t)reinterpret_cast<uintptr_t>(smem);
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)reinterpret_cast<uintptr_t>(smem));
   auto tile_k = [&](int t) { return (t < nk ? t : nk - 1) * BKA; };
   auto issue = [&](int v, int k0, uint32_t stage_bytes) {
     if (v < IPA) ld_a.issue_one_untracked(v, k0, stage_bytes);
@@ -847,12 +847,16 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
     __syncthreads();
     return;
   }
-  for (int kt = 0; kt < nk; ++kt) {
-    const uint4* sA = smem + (kt & (NS - 1)) * kStage;
+  // One step on the tile in stage st = kt & (NS - 1).  The loop below runs NS steps per trip with st a
+  // constant, so that every LDS address of a step is a register of the lane plus an immediate and the
+  // K loop has no vector address arithmetic left (vector ALU instructions take issue cycles from the
+  // MFMAs of the same SIMD); the steps of a remainder run with st computed.
+  auto step = [&](int kt, int st) __attribute__((always_inline)) {
+    const uint4* sA = smem + st * kStage;
     const uint4* sB = sA + BM * CHK;
-    const uint4* nA = smem + ((kt + 1) & (NS - 1)) * kStage;
+    const uint4* nA = smem + ((st + 1) & (NS - 1)) * kStage;
     const uint4* nB = nA + BM * CHK;
-    const uint32_t l_stage = lds_base + (uint32_t)(((kt + NS - 1) & (NS - 1)) * kStage) * 16u;
+    const uint32_t l_stage = lds_base + (uint32_t)(((st + NS - 1) & (NS - 1)) * kStage) * 16u;
     const int k_load = tile_k(kt + NS - 1);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -881,7 +885,13 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+  };
+  int kt = 0;
+  for (; kt + NS <= nk; kt += NS) {
+#pragma unroll
+    for (int u = 0; u < NS; ++u) step(kt + u, u);
   }
+  for (; kt < nk; ++kt) step(kt, kt & (NS - 1));
   // the last prefetches may still be landing in LDS, which the epilogue re-uses
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   __syncthreads();
