@@ -165,6 +165,51 @@ def test_gemm_balanced_tail_of_a_256_tile_launch(M, N, K):
     test_gemm_every_tile_variant(23, M, N, K)
 
 
+def _random_gemm_shapes():
+    """Seeded shapes (multiples of 8) across the regimes of the tile choice: a few 128-tiles, about one 128-tile
+    per CU, and 256-tile launches of one to two rounds, where the last round is or is not given to half-height
+    tiles; K from one K tile of the ring to a few, with and without a remainder for either K tile."""
+    rng = np.random.default_rng(2006)
+    shapes = []
+    for lo, hi in [(8, 400), (400, 1500), (1500, 2600), (3300, 4700), (3300, 4700), (3300, 4700)]:
+        for _ in range(3):
+            M, N = (int(rng.integers(lo, hi)) // 8 * 8 + 8 for _ in range(2))
+            K = int(rng.choice([32, 64, 96, 128, 136, 192, 256, 320]))
+            shapes.append((M, N, K))
+    return shapes
+
+
+@pytest.mark.parametrize("M,N,K", _random_gemm_shapes())
+def test_gemm_random_shapes_with_the_built_in_tile_choice(M, N, K):
+    """The bf16 GEMM as the stage calls it (tile chosen by the library), all three forms, against fp64."""
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    L = B.lib()
+    x, w, b = rnd(rng, (M, K), BF16), rnd(rng, (K, N), BF16, 0.1), rnd(rng, (N,), BF16)
+    r = rnd(rng, (M, N), BF16)
+    X, W, Bv, R = dev(x, BF16), dev(w, BF16), dev(b, BF16), dev(r, BF16)
+    Y = empty((M, N), BF16)
+    assert L.k2bw_gemm(BF16, 0, 0, 0, M, N, K, X.data_ptr(), K, W.data_ptr(), N, Y.data_ptr(), N, Bv.data_ptr(),
+                       R.data_ptr(), None, 0, None) == 0
+    sync()
+    assert rel(to_host(Y), x.astype(np.float64) @ w.astype(np.float64) + b + r) < TIGHT[BF16]
+
+    wt = rnd(rng, (N, K), BF16, 0.1)
+    Wt, D = dev(wt, BF16), empty((M, N), BF16)
+    assert L.k2bw_gemm(BF16, 0, 1, 0, M, N, K, X.data_ptr(), K, Wt.data_ptr(), K, D.data_ptr(), N, None, None, None,
+                       0, None) == 0
+    sync()
+    assert rel(to_host(D), x.astype(np.float64) @ wt.astype(np.float64).T) < TIGHT[BF16]
+
+    xt, dy = rnd(rng, (K, M), BF16), rnd(rng, (K, N), BF16)
+    G = torch.full((M, N), float("nan"), device="cuda", dtype=torch.float32)
+    Xt, DY = dev(xt, BF16), dev(dy, BF16)
+    for acc in (0, 1):
+        assert L.k2bw_gemm(BF16, 1, 0, 3, M, N, K, Xt.data_ptr(), M, DY.data_ptr(), N, G.data_ptr(), N, None, None,
+                           None, acc, None) == 0
+    sync()
+    assert rel(to_host(G), 2.0 * (xt.astype(np.float64).T @ dy.astype(np.float64))) < 2e-6
+
+
 @pytest.mark.parametrize("M,N,K", [(296, 264, 200), (4096, 1032, 136), (520, 4096, 64), (4360, 4096, 64)])
 def test_gemm_gelu_gradient_with_fused_bias_gradient(M, N, K):
     """du = (dy W^T) * GELU'(u) and db = colsum(du) from the same pass (bf16), overwrite then accumulate.
