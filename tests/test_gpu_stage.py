@@ -222,6 +222,18 @@ def test_momentum_sgd_under_2bw(precision):
     st.close()
 
 
+def test_grouped_weight_gradients_with_a_split_and_halved_tail():
+    """One wide layer (h = 1280, head size 128, f = 5120, 128 tokens): its four weight-gradient products are one
+    launch of 75 + 25 + 100 + 100 = 300 tiles of 256x256, 44 past a whole round of the 256 CUs, so the last
+    problem is split on the host and its lower tile rows run as half-height tiles.  G, the Adam state and the
+    weights after two updates against the oracle."""
+    cfg = synth.StageConfig(n_layers=1, hidden=1280, n_heads=10, ffn=5120, seq=64, microbatch=2, m=2, max_inflight=1,
+                            mask_mode=synth.MASK_CAUSAL, precision=synth.PREC_BF16, lr=1e-3)
+    gpu, tr = both(cfg, 2, 1, seed=5)
+    worst = compare_stage(cfg, gpu, tr)
+    print("split tail:", {k: f"{v:.2e}" for k, v in worst.items()})
+
+
 @pytest.mark.parametrize("precision", [synth.PREC_FP32, synth.PREC_BF16])
 @pytest.mark.parametrize("shape", [
     dict(n_layers=1, hidden=8, n_heads=1, ffn=8, seq=1, microbatch=1, m=1, max_inflight=1),        # one token, one key
