@@ -23,7 +23,9 @@
  * All pointers named *_dev are device pointers owned by the caller, *_host are host pointers
  * owned by the caller.  Everything else is owned by the library and freed by stage_destroy.
  * The five hot calls only enqueue work on the stream given to stage_create and return; the
- * stage_read_* calls synchronise that stream.  Calls on one stage must not overlap.
+ * stage_read_* calls synchronise that stream.  Calls on one stage must not overlap, and calls on
+ * different stages from several host threads must be serialised by the caller: the library sets
+ * up process-wide state on first use (kernel attributes, the device's CU count) without locks.
  *
  * Every function returns STAGE_OK (0) or a negative error code.  A call that returns an
  * error has enqueued nothing and changed no state.

@@ -4,6 +4,7 @@
  * unless its name ends in _host; `stream` is a hipStream_t (NULL = null stream).  Calls only
  * enqueue.  Return value: 0, or a negative STAGE_ERR_* code from stage2bw.h (INVALID_ARG when a
  * shape or alignment the kernel assumes does not hold; nothing is launched then).
+ * Not thread-safe: first calls set up process-wide state without locks.
  *
  * dtype: 0 = fp32, 1 = bf16 (2-byte elements, fp32 accumulation and statistics).
  * All row strides and contiguous extents must be multiples of 8 elements; base pointers 16-byte
