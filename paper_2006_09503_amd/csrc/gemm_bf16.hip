@@ -51,6 +51,8 @@ struct BfParams {
   int accumulate;
   int tiles_m, tiles_n;
   int tile_m;      // rows of C per tile: the kernel's BM, or BM/2 in the balanced tail of a ring launch
+  const void* prefetch;        // lines to touch for a later launch, or null (ring kernels)
+  uint32_t prefetch_bytes;     // multiple of 4, below 2^31
 };
 
 // Up to kMaxGroup independent GEMMs of the same form in one launch: workgroup ids
@@ -676,6 +678,14 @@ typedef __attribute__((address_space(3))) v4i16 lds_v4i16_t;
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void glob_void_t;
 
+// A wave-uniform pointer, moved to scalar registers.
+__device__ __forceinline__ uint64_t uniform_address(const void* ptr) {
+  const uint64_t bb = reinterpret_cast<uint64_t>(ptr);
+  const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(bb >> 32));
+  const uint32_t b_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)bb);
+  return ((uint64_t)b_hi << 32) | (uint64_t)b_lo;
+}
+
 template <int R, int NW, int BKA, bool K_CONTIG>
 struct AsyncLoader {
   static constexpr int CHK = BKA / 8;               // chunks per row of a K-contiguous tile
@@ -718,10 +728,7 @@ struct AsyncLoader {
   __device__ __forceinline__ void issue_one_untracked(int j, int k0, uint32_t lds_tile) const {
     const bf16_t* b = K_CONTIG ? base_ + k0 : base_ + (int64_t)k0 * ld_;
     const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + (uint32_t)(first_slot_ + j * 64) * 16u);
-    const uint64_t bb = reinterpret_cast<uint64_t>(b);   // wave-uniform
-    const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(bb >> 32));
-    const uint32_t b_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)bb);
-    const uint64_t sb = ((uint64_t)b_hi << 32) | (uint64_t)b_lo;
+    const uint64_t sb = uniform_address(b);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(dst), "v"(voff[j]), "s"(sb)
@@ -813,6 +820,17 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
     if (v < IPA) ld_a.issue_one_untracked(v, k0, stage_bytes);
     else ld_b.issue_one_untracked(v - IPA, k0, stage_bytes + (uint32_t)(BM * CHK) * 16u);
   };
+  // Lines of the operand a later launch will read (GemmDesc::prefetch): every wave of the launch
+  // touches 64 of them, 128 bytes apart, with one 4-byte load in front of its own first loads.  The
+  // load is older than every tile load, so the waits below (which count the newest operations that
+  // may still be outstanding) stay sufficient whenever it returns; its destination register is kept
+  // out of other use until the kernel ends (the compiler does not know that the value arrives late).
+  uint32_t touched = 0;
+  if (p.prefetch != nullptr) {
+    const uint32_t line = ((uint32_t)blockIdx.x * NW + (uint32_t)wave) * 64u + (uint32_t)lane;
+    const uint32_t off = min(line * 128u, p.prefetch_bytes - 4u);
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(touched) : "v"(off), "s"(uniform_address(p.prefetch)) : "memory");
+  }
   for (int t = 0; t < NS - 1; ++t)
 #pragma unroll
     for (int v = 0; v < NV; ++v) issue(v, tile_k(t), lds_base + (uint32_t)(t * kStage) * 16u);
@@ -845,6 +863,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
+    asm volatile("" : : "v"(touched));
     return;
   }
   // One step on the tile in stage st = kt & (NS - 1).  The loop below runs NS steps per trip with st a
@@ -896,6 +915,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   __syncthreads();
   epilogue<MI, NI, WM, WN, EPI>(acc, gp.p[g], m0, n0, wm, wn, lane, smem, wave, 0, MI);
+  asm volatile("" : : "v"(touched));
 }
 
 #ifndef K2BW_BALANCE_TAIL
@@ -1077,7 +1097,10 @@ BfParams to_params(const GemmDesc& d) {
   return BfParams{static_cast<const bf16_t*>(d.A), static_cast<const bf16_t*>(d.B), d.C,
                   d.M, d.N, d.K, d.lda, d.ldb, d.ldc, static_cast<const bf16_t*>(d.bias),
                   static_cast<const bf16_t*>(d.aux), static_cast<bf16_t*>(d.aux_out),
-                  d.epilogue == kEpiGeluGrad ? d.colsum_partial : nullptr, d.accumulate ? 1 : 0, 0, 0};
+                  d.epilogue == kEpiGeluGrad ? d.colsum_partial : nullptr, d.accumulate ? 1 : 0, 0, 0, 0,
+                  // (matrices beyond the reach of one launch's touches, or of the cache, are left alone)
+                  d.prefetch_bytes >= 4 && d.prefetch_bytes <= (32ll << 20) ? d.prefetch : nullptr,
+                  (uint32_t)(d.prefetch_bytes >= 4 && d.prefetch_bytes <= (32ll << 20) ? d.prefetch_bytes & ~3ll : 0)};
 }
 
 }  // namespace

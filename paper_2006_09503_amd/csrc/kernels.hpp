@@ -36,6 +36,11 @@ struct GemmDesc {
   // 32-row strip of the result (before rounding to bf16): the bias gradient of the projection
   // whose output gradient C is, reduced afterwards with colsum_finalize
   float* colsum_partial = nullptr;
+  // bf16 only, optional: `prefetch_bytes` bytes at `prefetch` that a later launch on the stream reads
+  // (the stage passes the next GEMM's weights); this launch touches their cache lines on its way in,
+  // so that they come from the memory-side cache and not from HBM when they are needed.  Never written.
+  const void* prefetch = nullptr;
+  int64_t prefetch_bytes = 0;
   int dtype = kF32;
 };
 hipError_t gemm(const GemmDesc& d, hipStream_t stream);

@@ -278,6 +278,7 @@ hipError_t run_forward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens,
     g.dtype = st->dtype;
     g.A = A.a; g.lda = h; g.B = wptr(st, buf, o.wqkv); g.ldb = 3 * h; g.C = A.qkv; g.ldc = 3 * h;
     g.M = T; g.N = 3 * h; g.K = h; g.bias = wptr(st, buf, o.bqkv);
+    g.prefetch = wptr(st, buf, o.wo); g.prefetch_bytes = (int64_t)h * h * st->esize;   // the next GEMM's weights
     e = run_gemm(st, STAGE_K_GEMM_FWD, g);
     if (e != hipSuccess) return e;
     e = timed(st, STAGE_K_ATTN_FWD, st->dtype == kBF16 ? "attn_fwd_mfma_kernel" : "attn_fwd_simple", attn_flops, 0.0, [&] {
@@ -288,6 +289,7 @@ hipError_t run_forward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens,
     g.dtype = st->dtype;
     g.A = A.o; g.lda = h; g.B = wptr(st, buf, o.wo); g.ldb = h; g.C = A.x1; g.ldc = h;
     g.M = T; g.N = h; g.K = h; g.bias = wptr(st, buf, o.bo); g.aux = A.x;
+    g.prefetch = wptr(st, buf, o.w1); g.prefetch_bytes = (int64_t)h * f * st->esize;
     e = run_gemm(st, STAGE_K_GEMM_FWD, g);
     if (e != hipSuccess) return e;
     e = run_ln_fwd(st, A.x1, wptr(st, buf, o.ln2_g), wptr(st, buf, o.ln2_b), A.c, A.mean2, A.rstd2);
@@ -296,12 +298,14 @@ hipError_t run_forward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens,
     g.dtype = st->dtype;
     g.A = A.c; g.lda = h; g.B = wptr(st, buf, o.w1); g.ldb = f; g.C = A.u; g.ldc = f;
     g.M = T; g.N = f; g.K = h; g.bias = wptr(st, buf, o.b1); g.epilogue = kEpiGelu; g.aux_out = A.g;
+    g.prefetch = wptr(st, buf, o.w2); g.prefetch_bytes = (int64_t)h * f * st->esize;
     e = run_gemm(st, STAGE_K_GEMM_FWD, g);
     if (e != hipSuccess) return e;
     g = GemmDesc();
     g.dtype = st->dtype;
     g.A = A.g; g.lda = f; g.B = wptr(st, buf, o.w2); g.ldb = h; g.C = y; g.ldc = h;
     g.M = T; g.N = h; g.K = f; g.bias = wptr(st, buf, o.b2); g.aux = A.x1;
+    if (l + 1 < c.n_layers) { g.prefetch = wptr(st, buf, st->off[l + 1].wqkv); g.prefetch_bytes = (int64_t)3 * h * h * st->esize; }
     e = run_gemm(st, STAGE_K_GEMM_FWD, g);
     if (e != hipSuccess) return e;
   }
@@ -360,28 +364,30 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     // the GEMM that computes it, dqkv (bf16 mode) from the attention backward kernels; the stage's
     // incoming dy, and du and dqkv in fp32 mode, are summed by the column-sum kernel.
     const bool fused_du = st->dtype == kBF16;
-    auto dgrad = [&](const void* grad, int N, const char* w_, int K, void* out, const void* u) {
-      // out[T,K] = grad[T,N] * W[K,N]^T
+    auto dgrad = [&](const void* grad, int N, const char* w_, int K, void* out, const void* u, const char* next_w,
+                     int64_t next_elems) {
+      // out[T,K] = grad[T,N] * W[K,N]^T; next_w: the weights of the chain's next data-gradient GEMM
       GemmDesc d;
       d.dtype = st->dtype;
       d.A = grad; d.lda = N; d.B = w_; d.ldb = N; d.trans_b = true; d.C = out; d.ldc = K;
       d.M = T; d.N = K; d.K = N;
+      d.prefetch = next_w; d.prefetch_bytes = next_w ? next_elems * st->esize : 0;
       if (u) { d.epilogue = kEpiGeluGrad; d.aux = u; if (fused_du) d.colsum_partial = st->du_partial[l]; }
       return run_gemm(st, STAGE_K_GEMM_DGRAD, d);
     };
     // y = x1 + GELU(u) W2 + b2
     e = wgrad(A.g, f, dy, h, st->G + o.w2);                              if (e != hipSuccess) return e;
-    e = dgrad(dy, h, wptr(st, buf, o.w2), f, du, A.u);                   if (e != hipSuccess) return e;
+    e = dgrad(dy, h, wptr(st, buf, o.w2), f, du, A.u, wptr(st, buf, o.w1), (int64_t)h * f);   if (e != hipSuccess) return e;
     // u = c W1 + b1
     e = wgrad(A.c, h, du, f, st->G + o.w1);                              if (e != hipSuccess) return e;
-    e = dgrad(du, f, wptr(st, buf, o.w1), h, st->tmp_h, nullptr);        if (e != hipSuccess) return e;
+    e = dgrad(du, f, wptr(st, buf, o.w1), h, st->tmp_h, nullptr, wptr(st, buf, o.wo), (int64_t)h * h);   if (e != hipSuccess) return e;
     // c = LN2(x1); dx1 = dy + LN2'(dc)
     int ln2_parts = 0, ln1_parts = 0;
     e = run_ln_bwd(st, st->tmp_h, A.x1, A.mean2, A.rstd2, wptr(st, buf, o.ln2_g), dy, dx1, st->ln_partial[l], &ln2_parts);
     if (e != hipSuccess) return e;
     // x1 = x + o Wo + bo
     e = wgrad(A.o, h, dx1, h, st->G + o.wo);                             if (e != hipSuccess) return e;
-    e = dgrad(dx1, h, wptr(st, buf, o.wo), h, st->tmp_h, nullptr);       if (e != hipSuccess) return e;
+    e = dgrad(dx1, h, wptr(st, buf, o.wo), h, st->tmp_h, nullptr, wptr(st, buf, o.wqkv), (int64_t)3 * h * h);   if (e != hipSuccess) return e;
     // attention
     AttnDesc ad = attn_desc(st, lens);
     const bool fused_dqkv = attention_mfma_supported(ad);
@@ -392,7 +398,9 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     if (e != hipSuccess) return e;
     // qkv = a Wqkv + bqkv
     e = wgrad(A.a, h, dqkv, 3 * h, st->G + o.wqkv);                      if (e != hipSuccess) return e;
-    e = dgrad(dqkv, 3 * h, wptr(st, buf, o.wqkv), h, st->tmp_h, nullptr);  if (e != hipSuccess) return e;
+    e = dgrad(dqkv, 3 * h, wptr(st, buf, o.wqkv), h, st->tmp_h, nullptr, l > 0 ? wptr(st, buf, st->off[l - 1].w2) : nullptr,
+              (int64_t)h * f);
+    if (e != hipSuccess) return e;
     // a = LN1(x); dx = dx1 + LN1'(da)
     e = run_ln_bwd(st, st->tmp_h, A.x, A.mean1, A.rstd1, wptr(st, buf, o.ln1_g), dx1, dx, st->ln_partial2[l], &ln1_parts);
     if (e != hipSuccess) return e;
