@@ -35,13 +35,13 @@ TRAFFIC_BYTES_PER_LAUNCH = {
     # grouped weight-gradient GEMM (the 24 products of the stage's 6 layers in one launch): FETCH_SIZE
     # x 1.995 (copy-kernel factor) + WRITE_SIZE x 1.000; algorithmic minimum 1.409e9 (operands once +
     # fp32 accumulator read-modify-write)
-    "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 1.5450e+09,
+    "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 1.5451e+09,
     # the other GEMM instances (averages over the shapes each serves)
-    "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 2>": 1.1982e+08,
-    "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.1773e+08,
-    "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, false, 0>": 7.9666e+07,
-    "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, true, 0>": 7.5468e+07,
-    "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 7.1431e+07,
+    "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 2>": 1.2820e+08,
+    "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.2610e+08,
+    "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, false, 0>": 8.6462e+07,
+    "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, true, 0>": 8.0600e+07,
+    "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 7.3529e+07,
 }
 
 
