@@ -12,9 +12,15 @@
  *     d > 1, and (2 (w-1)/w) * weight_bytes/d / bw_width of all-reduce traffic every
  *     m(b) = B / (w b) microbatches when w > 1;
  *   - a group of GPUs talks at bw_high when it fits inside one server (size <= gpus_per_server),
- *     at bw_low otherwise; the pipelines are oriented whichever way (replicas of a stage inside a
+ *     at bw_low otherwise.  This departs from the appendix's printed case expression, which is
+ *     strict (w < number of GPUs in a server): a group that fills a server exactly still stays
+ *     inside it.  The pipelines are oriented whichever way (replicas of a stage inside a
  *     server, or the stages of a pipeline inside a server) gives the higher throughput;
  *   - the throughput returned is that of the whole job, w * b / t samples per second;
+ *   - degree of gradient accumulation g = B / (w d b): the partitioning algorithm's last line
+ *     prints B / (N b), N being all GPUs, and Section 5.2 gives the batch size as b w d g with
+ *     m = d g microbatches averaged per update; a (w, d, b) is admissible iff g is a whole number
+ *     >= 1, so that m = d g >= d as Section 3.1 requires for two weight versions;
  *   - MEMORY: pipelined: 2|W|/d + A_total(b) + d*A_input(b); pipelined with recomputation:
  *     2|W|/d + A_total(b)/d + d*A_input(b); without pipelining one weight version and one
  *     activation set: |W|/d + A_total(b)/d.  state_bytes/d (optimizer state, master copies) is
@@ -54,7 +60,7 @@ typedef struct {
 
 typedef struct {
   int32_t w, d, b, mode;
-  int64_t g;                      /* microbatches per update and replica, B / (w b)               */
+  int64_t g;                      /* degree of gradient accumulation B / (w d b); m = d * g       */
   double throughput;              /* samples/s of the whole job                                   */
   double memory;                  /* bytes per GPU                                                */
 } planner_choice_t;
@@ -63,7 +69,7 @@ typedef struct {
 int planner_throughput(const planner_input_t* in, int32_t w, int32_t d, int32_t b, int32_t mode, double* out);
 /* MEMORY(w, d, b, mode) in bytes per GPU. */
 int planner_memory(const planner_input_t* in, int32_t w, int32_t d, int32_t b, int32_t mode, double* out);
-/* SEARCH(w, d, B): the candidate b (with w*b dividing B) and mode of highest throughput that fit in
+/* SEARCH(w, d, B): the candidate b (with w*d*b dividing B) and mode of highest throughput that fit in
  * memory_capacity; -2 if none fits. */
 int planner_search(const planner_input_t* in, int32_t w, int32_t d, planner_choice_t* out);
 /* The partitioning algorithm: sweep of all (w, d) with w*d <= n_gpus and d dividing n_blocks. */

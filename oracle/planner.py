@@ -4,9 +4,19 @@ by brute force.  Test infrastructure only: nothing in the product imports this.
 
 Readings (the appendix leaves them open): equal stages, d divides the number of blocks; every
 stage pays 2|A_inp+out(b)|/bandwidth when d > 1; the all-reduce moves 2(w-1)/w of a stage's weight
-bytes (the closed form of the PipeDream paper the appendix cites); a group of GPUs communicates
-at the high bandwidth iff it fits in one server, and of the two ways to lay the w x d grid over
-the servers the better one is taken; throughput is that of the whole job (w b / t)."""
+bytes (the closed form of the PipeDream paper the appendix cites); of the two ways to lay the
+w x d grid over the servers the better one is taken; throughput is that of the whole job (w b / t).
+
+Degree of gradient accumulation: the partitioning algorithm's last line gives g = B / (N b), and
+Section 5.2 fixes its meaning through the batch size b w d g of a pipeline whose m = d g
+microbatches are averaged per update.  So g = B / (w d b) for the (w, d) chosen (the printed N when
+every GPU is used), a configuration is admissible iff that is a whole number >= 1, and then
+m = d g >= d, the condition Section 3.1 needs for two weight versions to suffice.
+
+One departure from a printed form, on purpose: the appendix's bandwidth case expression gives
+the high bandwidth for w strictly below the number of GPUs in a server.  A group that fills a
+server exactly still communicates inside it, so the test used here is group size <= server size;
+at equality the printed form would charge the low bandwidth."""
 from dataclasses import dataclass
 from typing import Sequence
 
@@ -76,7 +86,7 @@ def partition(p: Profile):
             if p.n_blocks % d:
                 continue
             for b in p.microbatch_sizes:
-                if w * b > p.global_batch or p.global_batch % (w * b):
+                if p.global_batch % (w * d * b):        # g = B / (w d b) must be a whole number >= 1
                     continue
                 for mode in (NO_PIPELINE, PIPELINE, PIPELINE_RECOMPUTE):
                     mem = memory(p, w, d, b, mode)
@@ -84,5 +94,5 @@ def partition(p: Profile):
                         continue
                     thr = throughput(p, w, d, b, mode)
                     if best is None or thr > best[5]:
-                        best = (w, d, b, mode, p.global_batch // (w * b), thr, mem)
+                        best = (w, d, b, mode, p.global_batch // (w * d * b), thr, mem)
     return best

@@ -69,15 +69,17 @@ double memory(const planner_input_t* in, int d, int bi, int mode) {
 int search(const planner_input_t* in, int w, int d, planner_choice_t* out) {
   bool found = false;
   for (int bi = 0; bi < in->n_sizes; ++bi) {
-    const int64_t wb = (int64_t)w * in->microbatch_sizes[bi];
-    if (wb > in->global_batch || in->global_batch % wb) continue;
+    // g = B / (w d b) (partitioning algorithm, last line; Section 5.2: batch size b w d g, m = d g) must be
+    // a whole number >= 1, which also gives m >= d (Section 3.1)
+    const int64_t wdb = (int64_t)w * d * in->microbatch_sizes[bi];
+    if (in->global_batch % wdb) continue;
     for (int mode = PLANNER_MODE_NO_PIPELINE; mode <= PLANNER_MODE_PIPELINE_RECOMPUTE; ++mode) {
       const double mem = memory(in, d, bi, mode);
       if (mem > in->memory_capacity) continue;
       const double thr = throughput(in, w, d, bi, mode);
       if (!found || thr > out->throughput) {
         found = true;
-        *out = planner_choice_t{w, d, in->microbatch_sizes[bi], mode, in->global_batch / wb, thr, mem};
+        *out = planner_choice_t{w, d, in->microbatch_sizes[bi], mode, in->global_batch / wdb, thr, mem};
       }
     }
   }

@@ -63,7 +63,7 @@ def main(argv):
         return 1
     w, d, b, mode, g, thr, mem = c
     print(f"{n_blocks} blocks on {n_gpus} MI355X, global batch {batch}: w = {w} replicas of a d = {d} stage pipeline, "
-          f"microbatch b = {b}, {g} microbatches per update, {MODES[mode]}: {thr:.0f} samples/s predicted, "
+          f"microbatch b = {b}, m = d g = {d * g} microbatches per update, {MODES[mode]}: {thr:.0f} samples/s predicted, "
           f"{mem / 2**30:.1f} GiB per GPU")
     return 0
 
