@@ -38,10 +38,12 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 
 
 def run_stage_gpu(cfg: synth.StageConfig, w0: np.ndarray, mbs, inflight: int, snapshot: bool = True,
-                  two_streams: bool = False):
+                  two_streams: bool = False, consume=None):
     """Drive the HIP stage over the microbatches; returns per-microbatch Y, dX and, per update,
     the accumulator, Adam moments, both buffers and the master as read right after the update.
-    two_streams: backward passes and updates on a stream of their own."""
+    two_streams: backward passes and updates on a stream of their own.
+    consume: called with each update's snapshot instead of keeping it (the billion-parameter
+    shapes would otherwise hold tens of GB of host copies until the end)."""
     st = B.Stage(cfg, w0)
     bstream = None
     if two_streams:
@@ -63,10 +65,14 @@ def run_stage_gpu(cfg: synth.StageConfig, w0: np.ndarray, mbs, inflight: int, sn
         if not snapshot:
             return
         m_, v_ = st.read_adam()
-        snaps.append(dict(t=t, G=st.read_grad_accum(), m=m_, v=v_,
-                          buf0=st.read_weights(B.WEIGHTS_BUF0), buf1=st.read_weights(B.WEIGHTS_BUF1),
-                          master=st.read_weights(B.WEIGHTS_MASTER),
-                          newest=st.query(B.Q_BUFFER_OF_NEWEST), updates=st.query(B.Q_UPDATES)))
+        snap = dict(t=t, G=st.read_grad_accum(), m=m_, v=v_,
+                    buf0=st.read_weights(B.WEIGHTS_BUF0), buf1=st.read_weights(B.WEIGHTS_BUF1),
+                    master=st.read_weights(B.WEIGHTS_MASTER),
+                    newest=st.query(B.Q_BUFFER_OF_NEWEST), updates=st.query(B.Q_UPDATES))
+        if consume is not None:
+            consume(snap)
+        else:
+            snaps.append(snap)
 
     st.run_1f1b(1, n, lambda k: (X[k], LEN[k], DY[k]), lambda k: (Y[k], DX[k]), inflight, on_update)
     torch.cuda.synchronize()
@@ -91,38 +97,61 @@ def run_stage_oracle(cfg: synth.StageConfig, w0: np.ndarray, mbs, inflight: int 
                      inflight=inflight, version_rule=rule)
 
 
-def compare_stage(cfg, gpu, tr: tb.Trace, tol=None, check_dw=True, check_weights=True):
-    """Element-wise comparison (relative L2) of everything the stage produces; returns the worst
-    ratios for reporting."""
-    tol = TOL[cfg.precision] if tol is None else tol
-    worst = {}
+class StageChecker:
+    """Element-wise comparison (relative L2) of everything the stage produces against an oracle
+    trace; `worst` collects the largest ratio per quantity for reporting."""
 
-    def chk(name, got, want, bar=tol):
+    def __init__(self, cfg, tr: tb.Trace, tol=None, check_dw=True, check_weights=True, release=False):
+        self.cfg, self.tr = cfg, tr
+        self.tol = TOL[cfg.precision] if tol is None else tol
+        self.check_dw, self.check_weights, self.release = check_dw, check_weights, release
+        self.worst = {}
+        self.prev_master = None
+        self.updates_seen = 0
+
+    def chk(self, name, got, want, bar=None):
+        bar = self.tol if bar is None else bar
         r = rel(got, want)
-        worst[name] = max(worst.get(name, 0.0), r)
+        self.worst[name] = max(self.worst.get(name, 0.0), r)
         assert r <= bar, f"{name}: rel L2 {r:.3e} > {bar:.1e}"
 
-    for k in sorted(tr.Y):
-        chk("Y", gpu["Y"][k], tr.Y[k])
-        chk("dX", gpu["dX"][k], tr.dX[k])
-    for s in gpu["snaps"]:
+    def outputs(self, gpu):
+        for k in sorted(self.tr.Y):
+            self.chk("Y", gpu["Y"][k], self.tr.Y[k])
+            self.chk("dX", gpu["dX"][k], self.tr.dX[k])
+
+    def snapshot(self, s):
+        cfg, tr, chk = self.cfg, self.tr, self.chk
         t = s["t"]
+        self.updates_seen += 1
         assert s["updates"] == t and s["newest"] == (0 if cfg.flush else t % 2)
         chk("G", s["G"], tr.G[t - 1])
         chk("adam_m", s["m"], tr.opt_state[t - 1]["m"])
         if cfg.optimizer == synth.OPT_ADAM:
             chk("adam_v", s["v"], tr.opt_state[t - 1]["v"])
-        if not check_weights:
-            continue
-        new, old = (s["buf1"], s["buf0"]) if (t % 2 and not cfg.flush) else (s["buf0"], s["buf1"])
-        chk("W_new_buffer", new, tr.W[t])
-        if cfg.flush:
-            assert np.array_equal(old, new)            # one version: both names read the same buffer
-        else:
-            chk("W_other_buffer", old, tr.W[t - 1])    # the shadow version is still intact
-        chk("W_master", s["master"], tr.W[t])
-        if check_dw:
-            # the raw weights move by only ~lr/0.02 per step; the step itself is the sensitive quantity
-            dw_gpu = s["master"].astype(np.float64) - (gpu["snaps"][t - 2]["master"] if t >= 2 else tr.W[0])
-            chk("dW", dw_gpu, tr.W[t] - tr.W[t - 1], bar=DW_TOL[cfg.precision])
-    return worst
+        if self.check_weights:
+            new, old = (s["buf1"], s["buf0"]) if (t % 2 and not cfg.flush) else (s["buf0"], s["buf1"])
+            chk("W_new_buffer", new, tr.W[t])
+            if cfg.flush:
+                assert np.array_equal(old, new)            # one version: both names read the same buffer
+            else:
+                chk("W_other_buffer", old, tr.W[t - 1])    # the shadow version is still intact
+            chk("W_master", s["master"], tr.W[t])
+            if self.check_dw:
+                # the raw weights move by only ~lr/0.02 per step; the step itself is the sensitive quantity
+                before = self.prev_master if t >= 2 else tr.W[0]
+                chk("dW", s["master"].astype(np.float64) - before, tr.W[t] - tr.W[t - 1], bar=DW_TOL[cfg.precision])
+        self.prev_master = s["master"]
+        if self.release:            # the trace's copies of this update are not needed again
+            tr.G[t - 1] = None
+            tr.opt_state[t - 1] = None
+            tr.W[t - 1] = None if t >= 2 else tr.W[t - 1]
+
+
+def compare_stage(cfg, gpu, tr: tb.Trace, tol=None, check_dw=True, check_weights=True):
+    """Whole-run comparison; returns the worst ratios for reporting."""
+    ck = StageChecker(cfg, tr, tol, check_dw, check_weights)
+    ck.outputs(gpu)
+    for s in gpu["snaps"]:
+        ck.snapshot(s)
+    return ck.worst

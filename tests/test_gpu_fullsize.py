@@ -9,7 +9,7 @@ import pytest
 
 from paper_2006_09503_amd import synth
 
-from gpu_util import compare_stage, run_stage_gpu, run_stage_oracle
+from gpu_util import StageChecker, run_stage_gpu, run_stage_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -18,11 +18,19 @@ def run(cfg, n_batches, inflight, seed=0, two_streams=False):
     gen = synth.StageInputs(cfg, seed)
     w0 = gen.weights()
     mbs = gen.microbatches(n_batches * cfg.m)
-    gpu = run_stage_gpu(cfg, w0, mbs, inflight, two_streams=two_streams)
+    print(f"full-size case L={cfg.n_layers} h={cfg.hidden} f={cfg.ffn} s={cfg.seq} b={cfg.microbatch} m={cfg.m} "
+          f"batches={n_batches} inflight={inflight} recompute={cfg.recompute}: oracle", flush=True)
     tr = run_stage_oracle(cfg, w0, mbs)
-    worst = compare_stage(cfg, gpu, tr)
-    print({k: f"{v:.2e}" for k, v in worst.items()})
-    return worst
+    if n_batches >= 3:
+        # the third batch is the first whose gradient is taken on a version other than W(0)
+        assert tr.version_used[2 * cfg.m + 1] == 1 and max(tr.version_used.values()) == n_batches - 2
+    print("  stage on the GPU", flush=True)
+    ck = StageChecker(cfg, tr, release=True)
+    gpu = run_stage_gpu(cfg, w0, mbs, inflight, two_streams=two_streams, consume=ck.snapshot)
+    ck.outputs(gpu)
+    assert ck.updates_seen == n_batches
+    print({k: f"{v:.2e}" for k, v in ck.worst.items()}, flush=True)
+    return ck.worst
 
 
 def test_bert_large_shape_three_updates():
@@ -39,20 +47,23 @@ def test_bert_large_full_stage_one_batch():
 
 
 def test_gpt_2560_shape_head_size_80():
-    """h=2560, 32 heads of 80, f=10240, s=1024, b=4, causal; 1 layer, m=1, three updates."""
-    cfg = synth.PRESETS["C3"].with_(n_layers=1, m=1, max_inflight=1)
-    run(cfg, 3, 1)
+    """h=2560, 32 heads of 80, f=10240, s=1024, b=4, causal; 1 layer, m=2 with 2 microbatches in
+    flight, three updates: the third batch runs on W(1) after a swap, and both buffers are written."""
+    cfg = synth.PRESETS["C3"].with_(n_layers=1, m=2, max_inflight=2)
+    run(cfg, 3, 2)
 
 
 def test_gpt_4096_shape_with_recomputation():
     """h=4096, 32 heads of 128, f=16384, s=2048, b=2, causal, stage-input stash only; 1 layer,
-    m=2 with 2 microbatches in flight, two updates."""
+    m=2 with 2 microbatches in flight, three updates: the backward passes of the third batch
+    re-run their forward on the tagged older version W(1) while W(2) already exists."""
     cfg = synth.PRESETS["C4"].with_(n_layers=1, m=2, max_inflight=2)
     assert cfg.recompute == 1
-    run(cfg, 2, 2)
+    run(cfg, 3, 2)
 
 
 def test_stress_shape_8192():
-    """h=8192, 64 heads of 128, f=32768, s=2048, b=1, causal; 1 layer, m=1, one update."""
+    """h=8192, 64 heads of 128, f=32768, s=2048, b=1, causal; 1 layer, m=1, three updates (the
+    delayed version is consumed by the third, and Adam has written each buffer)."""
     cfg = synth.PRESETS["C5"].with_(n_layers=1, m=1, max_inflight=1)
-    run(cfg, 1, 1)
+    run(cfg, 3, 1)
