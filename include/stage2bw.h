@@ -103,8 +103,8 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
 /*
  * Forward pass of microbatch mb (1-indexed, global count) on the version the rule assigns it
  * (Section 3.1).  x_dev, y_dev: [b, s, h] contiguous, bf16 in bf16 mode, fp32 in fp32 mode
- * (y_dev may not alias x_dev).  seqlens_dev: b int32 key lengths in [1, s] for
- * STAGE_MASK_PADDING, ignored (may be NULL) otherwise.  The microbatch becomes in flight: its
+ * (y_dev may not alias x_dev).  seqlens_dev: b int32 key lengths in [1, s] (values outside are
+ * clamped into that range by the kernels) for STAGE_MASK_PADDING, ignored (may be NULL) otherwise.  The microbatch becomes in flight: its
  * activations (or just x, with recompute) are stashed with the version tag.
  * BAD_STATE if mb is already in flight, if no stash slot is free, or if the version the rule
  * assigns to mb is not the one new forwards currently read (call stage_swap_versions first,

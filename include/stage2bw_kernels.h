@@ -70,8 +70,23 @@ int64_t k2bw_bias_grad_workspace(int n);
 int k2bw_bias_grad(int dtype, int rows, int n, const void* y, float* out, int accumulate,
                    float* workspace, void* stream);
 
+/* k2bw_bias_grad for callers that cannot allocate device memory or carry a workspace (code under
+ * HIP graph capture, serving loops, harnesses that forbid hipMalloc): same kernels, same result bit
+ * for bit, with the partial rows in a device array that is part of the library image (64 x 32768
+ * floats = 8 MiB on every GPU the library is loaded on, held until the process ends).  Calls no
+ * hipMalloc / hipFree or other allocating routine.  n above k2bw_bias_grad_static_max_cols()
+ * (32768): INVALID_ARG, nothing launched.  The first call on a device looks the array's address up
+ * once (hipGetSymbolAddress; HIP error -> STAGE_ERR_HIP).  All calls on one GPU share the array:
+ * calls on different streams of one GPU that may overlap race on it; calls on one stream are
+ * ordered and need no clearing in between (every partial row read is rewritten by the same call). */
+int k2bw_bias_grad_static_max_cols(void);
+int k2bw_bias_grad_static(int dtype, int rows, int n, const void* y, float* out, int accumulate,
+                          void* stream);
+
 /* qkv: [b*s, 3h] with columns Q|K|V, each head-major, h = a*dh; o: [b*s, h]; lse: fp32 [b,a,s].
- * mask_mode 0 none, 1 causal (key j <= query i), 2 key padding (key j < seqlens[n]). */
+ * mask_mode 0 none, 1 causal (key j <= query i), 2 key padding (key j < seqlens[n]; a length
+ * outside [1, s] is read as the nearest end of that range, so no row is empty and no key past the
+ * sequence is touched). */
 int k2bw_attention_fwd(int dtype, int b, int s, int a, int dh, int mask_mode, const int32_t* seqlens,
                        const void* qkv, void* o, float* lse, void* stream);
 /* dqkv: [b*s, 3h]; delta: fp32 scratch [b,a,s].  dbias_qkv (bf16 with head size 32, 64, 80 or 128

@@ -230,7 +230,7 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_fwd_mfma_ke
   const int h = a * DH;
   const int64_t ld = 3 * (int64_t)h;
   const bf16_t* base = qkv + (int64_t)n * s * ld + head * DH;
-  const int kv_len = mask_mode == 2 ? seqlens[n] : s;
+  const int kv_len = mask_mode == 2 ? min(max(seqlens[n], 1), s) : s;   // lengths outside [1, s] are clamped: no read past the sequence, no empty row
   const bool causal = mask_mode == 1;
   const int iw0 = i0 + wave * 32;
   const int i = iw0 + l32;
@@ -348,7 +348,7 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dq_mfma_ker
   const int h = a * DH;
   const int64_t ld = 3 * (int64_t)h;
   const bf16_t* base = qkv + (int64_t)n * s * ld + head * DH;
-  const int kv_len = mask_mode == 2 ? seqlens[n] : s;
+  const int kv_len = mask_mode == 2 ? min(max(seqlens[n], 1), s) : s;   // lengths outside [1, s] are clamped: no read past the sequence, no empty row
   const bool causal = mask_mode == 1;
   const int iw0 = i0 + wave * 32;
   const int i = iw0 + l32;
@@ -470,7 +470,7 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dkv_mfma_ke
   const bf16_t* dobase = d_o + (int64_t)n * s * h + head * DH;
   const float* lse_row = lse + ((int64_t)n * a + head) * s;
   const float* delta_row = delta + ((int64_t)n * a + head) * s;
-  const int kv_len = mask_mode == 2 ? seqlens[n] : s;
+  const int kv_len = mask_mode == 2 ? min(max(seqlens[n], 1), s) : s;   // lengths outside [1, s] are clamped: no read past the sequence, no empty row
   const bool causal = mask_mode == 1;
   const int jw0 = j0 + wave * 32;
   const int j = jw0 + l32;

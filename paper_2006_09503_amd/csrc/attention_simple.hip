@@ -55,7 +55,7 @@ __global__ __launch_bounds__(kRowsPerWg) void attn_fwd_simple(const T* __restric
   const int i0 = blockIdx.x * kRowsPerWg;
   const int i = i0 + tid;
   const bool row_ok = i < s;
-  const int len = (mask_mode == 2) ? seqlens[n] : s;
+  const int len = (mask_mode == 2) ? min(max(seqlens[n], 1), s) : s;   // clamped into [1, s]
   const T* base = qkv + (int64_t)n * s * ld + head * dh;
   const float scale = 1.0f / sqrtf((float)dh);
 
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(kRowsPerWg) void attn_dq_simple(const T* __restrict
   const int i0 = blockIdx.x * kRowsPerWg;
   const int i = i0 + tid;
   const bool row_ok = i < s;
-  const int len = (mask_mode == 2) ? seqlens[n] : s;
+  const int len = (mask_mode == 2) ? min(max(seqlens[n], 1), s) : s;   // clamped into [1, s]
   const T* base = qkv + (int64_t)n * s * ld + head * dh;
   const float scale = 1.0f / sqrtf((float)dh);
 
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(kRowsPerWg) void attn_dkv_simple(const T* __restric
   const int64_t ld = 3 * (int64_t)h;
   const int j0 = blockIdx.x * kRowsPerWg;
   const int j = j0 + tid;
-  const int len = (mask_mode == 2) ? seqlens[n] : s;
+  const int len = (mask_mode == 2) ? min(max(seqlens[n], 1), s) : s;   // clamped into [1, s]
   const bool row_ok = j < s;
   const T* base = qkv + (int64_t)n * s * ld + head * dh;
   const T* gobase = d_o + (int64_t)n * s * h + head * dh;

@@ -312,6 +312,30 @@ def test_bias_gradient_column_sums(dtype, rows, n):
     assert rel(to_host(out), 2 * y.astype(np.float64).sum(0)) < 1e-5
 
 
+@pytest.mark.parametrize("dtype,dh", [(F32, 16), (BF16, 64)])
+def test_attention_key_lengths_outside_the_sequence_are_clamped(dtype, dh):
+    """A length of 0 or below acts as 1, a length above s as s: same bits as the clamped lengths."""
+    b, s, a = 4, 96, 2
+    h = a * dh
+    rng = np.random.default_rng(5)
+    QKV, DO = dev(rnd(rng, (b, s, 3 * h), dtype), dtype), dev(rnd(rng, (b, s, h), dtype), dtype)
+    L = B.lib()
+    outs = []
+    for lens in ([0, s + 7, -3, 50], [1, s, 1, 50]):
+        LEN = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        O, DQKV = empty((b, s, h), dtype), empty((b, s, 3 * h), dtype)
+        lse = torch.empty((b, a, s), device="cuda"); delta = torch.empty((b, a, s), device="cuda")
+        assert L.k2bw_attention_fwd(dtype, b, s, a, dh, 2, LEN.data_ptr(), QKV.data_ptr(), O.data_ptr(),
+                                    lse.data_ptr(), None) == 0
+        assert L.k2bw_attention_bwd(dtype, b, s, a, dh, 2, LEN.data_ptr(), QKV.data_ptr(), O.data_ptr(),
+                                    lse.data_ptr(), DO.data_ptr(), DQKV.data_ptr(), delta.data_ptr(), None, 0, None,
+                                    None) == 0
+        sync()
+        outs.append((to_host(O), to_host(lse), to_host(DQKV)))
+    for got, want in zip(*outs):
+        assert np.isfinite(got).all() and np.array_equal(got, want)
+
+
 def test_momentum_sgd_kernel():
     rng = np.random.default_rng(11)
     n, m_micro, lr, beta = 4096 * 5 + 8, 4, 0.05, 0.9
