@@ -95,6 +95,8 @@ def lib() -> C.CDLL:
             "k2bw_layernorm_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, vp]),
             "k2bw_bias_grad_workspace": (i64, [C.c_int]),
             "k2bw_bias_grad": (C.c_int, [C.c_int, C.c_int, C.c_int, vp, vp, C.c_int, vp, vp]),
+            "k2bw_bias_grad_static_max_cols": (C.c_int, []),
+            "k2bw_bias_grad_static": (C.c_int, [C.c_int, C.c_int, C.c_int, vp, vp, C.c_int, vp]),
             "k2bw_attention_fwd": (C.c_int, [C.c_int] * 6 + [vp, vp, vp, vp, vp]),
             "k2bw_attention_bwd_workspace": (i64, [C.c_int] * 4),
             "k2bw_attention_bwd": (C.c_int, [C.c_int] * 6 + [vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, vp]),

@@ -15,6 +15,14 @@ int rc_of(hipError_t e) {
   return STAGE_ERR_HIP;
 }
 bool dtype_ok(int d) { return d == kF32 || d == kBF16; }
+
+// Partial rows for k2bw_bias_grad_static: device memory that exists from library load to process end
+// on every GPU that loads the library, so the call never allocates.
+constexpr int kStaticParts = 64;            // == colsum_max_parts()
+constexpr int kStaticMaxCols = 32768;
+constexpr int kStaticMaxDevices = 64;
+__device__ __align__(256) float scratch[kStaticParts * kStaticMaxCols];
+float* scratch_ptr[kStaticMaxDevices] = {};  // per device: the address of that device's copy of `scratch`
 }  // namespace
 
 extern "C" {
@@ -84,6 +92,30 @@ int k2bw_bias_grad(int dtype, int rows, int n, const void* y, float* out, int ac
   hipError_t e = colsum_partial(y, rows, n, n, workspace, &parts, dtype, s);
   if (e != hipSuccess) return rc_of(e);
   return rc_of(colsum_finalize(workspace, parts, n, out, accumulate != 0, s));
+}
+
+int k2bw_bias_grad_static_max_cols(void) { return kStaticMaxCols; }
+
+int k2bw_bias_grad_static(int dtype, int rows, int n, const void* y, float* out, int accumulate, void* stream) {
+  if (!dtype_ok(dtype) || !out || n <= 0 || n > kStaticMaxCols || colsum_max_parts() > kStaticParts)
+    return STAGE_ERR_INVALID_ARG;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return STAGE_ERR_HIP;
+  if (dev < 0 || dev >= kStaticMaxDevices) return STAGE_ERR_INVALID_ARG;
+  if (!scratch_ptr[dev]) {
+    // The array's name is only a host-side handle; its address on the current device has to be asked for.
+    float* p = nullptr;
+    if (hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)) != hipSuccess || !p)
+      return STAGE_ERR_HIP;
+    scratch_ptr[dev] = p;
+  }
+  float* partial = scratch_ptr[dev];
+  int parts = 0;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // Every partial row the second kernel reads is written in full by the first: nothing needs clearing.
+  hipError_t e = colsum_partial(y, rows, n, n, partial, &parts, dtype, s);
+  if (e != hipSuccess) return rc_of(e);
+  return rc_of(colsum_finalize(partial, parts, n, out, accumulate != 0, s));
 }
 
 int k2bw_attention_fwd(int dtype, int b, int s, int a, int dh, int mask_mode, const int32_t* seqlens,
