@@ -4,13 +4,17 @@
 A "step" is one batch of the stage's steady-state 1F1B stream (Section 3.1 of the paper): m
 forward passes, m backward passes with in-place gradient coalescing, one Adam update into the
 other weight buffer and the version swap, with `max_inflight` microbatches in flight.  The
-default workload is the BERT-Large-shaped stage (6 layers, h=1024, f=4096, s=512, b=8, m=8,
-key-padding mask, bf16 compute with fp32 master weights).
+default workload is the largest of the five configurations, C5: 2 layers, h=8192, 64 heads,
+f=32768, s=2048, b=1, m=64, causal mask, bf16 compute with fp32 master weights (1.61 G
+parameters); `--workload C2` is the BERT-Large-shaped stage, C3 / C4 the GPT-shaped ones.
 
 Prints ONE JSON line: stage samples/s (value), model TFLOP/s, fraction of the bf16 MFMA peak,
 a `roofline` object for the dominant kernel class (HIP-event timing of every launch of that
-class inside a second timed region of the same length) and a `cpu_baseline` object (the fp64
-oracle timed on this host on a bounded sample of the same workload).
+class inside a second timed region of the same length), a `cpu_baseline` object (the fp64
+oracle timed on this host on a bounded sample of the same workload) and a `prefix_check` object:
+before the timed run, the first microbatch goes through a one-layer stage of the workload's
+shape and its output, input gradient and weight gradient are compared at 1024 positions each
+with values the oracle computed for exactly that case (tests/golden/stage_prefix_*.txt).
 
 All inputs are seeded, synthetic and resident in HBM before the clock starts.
 """
@@ -28,21 +32,31 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM bytes per launch (read + write) of kernel instances on the default workload, from rocprofv3
-# --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the same counters read for the
-# library's plain copy kernel of known size; see profiles/ for the runs.  None = not measured.
+# HBM bytes per launch (read + write) of kernel instances, per workload at its default flags, from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the same counters read
+# for the library's plain copy kernel of known size; see profiles/ for the runs.  A workload, flag
+# set or kernel that was not profiled reports null.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    # grouped weight-gradient GEMM (the 24 products of the stage's 6 layers in one launch): FETCH_SIZE
-    # x 1.995 (copy-kernel factor) + WRITE_SIZE x 1.000; algorithmic minimum 1.409e9 (operands once +
-    # fp32 accumulator read-modify-write)
-    "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 1.5451e+09,
-    # the other GEMM instances (averages over the shapes each serves)
-    "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 2>": 1.2820e+08,
-    "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.2610e+08,
-    "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, false, 0>": 8.6462e+07,
-    "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, true, 0>": 8.0600e+07,
-    "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 7.3529e+07,
+    "C2": {
+        # grouped weight-gradient GEMM (the 24 products of the stage's 6 layers in one launch): FETCH_SIZE
+        # x 1.995 (copy-kernel factor) + WRITE_SIZE x 1.000; algorithmic minimum 1.409e9 (operands once +
+        # fp32 accumulator read-modify-write)
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 1.5451e+09,
+        # the other GEMM instances (averages over the shapes each serves)
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 2>": 1.2820e+08,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.2610e+08,
+        "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, false, 0>": 8.6462e+07,
+        "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, true, 0>": 8.0600e+07,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 7.3529e+07,
+    },
 }
+
+
+def measured_traffic(args, kernel):
+    """Counter-measured HBM bytes per launch, or None unless this run is the profiled configuration."""
+    if args.flush or args.recompute is not None or args.microbatch is not None or args.wgrad_group is not None:
+        return None
+    return TRAFFIC_BYTES_PER_LAUNCH.get(args.workload, {}).get(kernel)
 
 
 def model_flops_per_microbatch(cfg) -> float:
@@ -73,14 +87,16 @@ def cpu_baseline(cfg, seed):
         n_mb += 1
         x, dy, lens = gen.microbatch()
     t_layer_mb = t_total / n_mb
+    # the update is element-wise: a slice of at most 2^26 parameters is timed and scaled to all P
     P = synth.param_count(cfg)
+    n_slice = min(P, 1 << 26)
     rng = np.random.default_rng(seed)
-    wf, g = rng.standard_normal(P), rng.standard_normal(P)
+    wf, g = rng.standard_normal(n_slice), rng.standard_normal(n_slice)
     opt = tb.Adam(cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps)
     state = opt.init(wf)
     t0 = time.perf_counter()
     opt.step(wf, g, state, 0)
-    t_adam = time.perf_counter() - t0
+    t_adam = (time.perf_counter() - t0) * (P / n_slice)
     t_step = cfg.n_layers * cfg.m * t_layer_mb + t_adam
     try:
         from threadpoolctl import threadpool_info
@@ -89,7 +105,57 @@ def cpu_baseline(cfg, seed):
         threads = os.cpu_count()
     return {"value": cfg.microbatch * cfg.m / t_step, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
             "sample": f"fp64 numpy oracle: 1 layer x {n_mb} microbatches fwd+bwd ({t_layer_mb:.2f} s each) and one Adam step over "
-                      f"all {P} parameters ({t_adam:.2f} s), extrapolated linearly to L={cfg.n_layers}, m={cfg.m}"}
+                      f"{n_slice} of the {P} parameters (scaled to all: {t_adam:.2f} s), extrapolated linearly to "
+                      f"L={cfg.n_layers}, m={cfg.m}"}
+
+
+def prefix_check(workload, cfg, seed):
+    """First microbatch through a one-layer stage of the workload's shape against the oracle's stored
+    samples (tests/golden/stage_prefix_<workload>.txt; seed 0 only).  Returns relative L2 errors over
+    the sampled positions, or None if no stored samples apply."""
+    import numpy as np
+    import torch
+    from paper_2006_09503_amd import binding as B
+    from paper_2006_09503_amd import synth
+    path = os.path.join(ROOT, "tests", "golden", f"stage_prefix_{workload}.txt")
+    if seed != 0 or not os.path.exists(path) or workload not in synth.PRESETS:
+        return None
+    base = synth.PRESETS[workload]
+    if (cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.microbatch, cfg.mask_mode, cfg.precision) != \
+            (base.hidden, base.n_heads, base.ffn, base.seq, base.microbatch, base.mask_mode, base.precision):
+        return None
+    want = {"Y": ([], []), "dX": ([], []), "G": ([], [])}
+    for line in open(path):
+        if line.startswith("#"):
+            continue
+        tag, idx, val = line.split()
+        want[tag][0].append(int(idx))
+        want[tag][1].append(float(val))
+    one = base.with_(n_layers=1, m=1, max_inflight=1, recompute=0)
+    gen = synth.StageInputs(one, 0)
+    w0 = gen.weights()
+    x, dy, lens = gen.microbatch()
+    dt = torch.bfloat16 if one.precision == synth.PREC_BF16 else torch.float32
+    st = B.Stage(one, w0)
+    del w0
+    X, DY = (torch.from_numpy(a).cuda().to(dt) for a in (x, dy))
+    LEN = None if lens is None else torch.from_numpy(lens).cuda()
+    Y, DX = torch.empty_like(X), torch.empty_like(X)
+    st.forward(1, X, LEN, Y)
+    st.backward(1, DY, DX)
+    torch.cuda.synchronize()
+    got = {"Y": Y.float().cpu().numpy().reshape(-1), "dX": DX.float().cpu().numpy().reshape(-1),
+           "G": st.read_grad_accum()}
+    st.close()
+    out = {}
+    for tag, (idx, val) in want.items():
+        g, w = got[tag][np.asarray(idx)].astype(np.float64), np.asarray(val)
+        out["rel_l2_" + tag] = float(np.linalg.norm(g - w) / np.linalg.norm(w))
+    bar = 2e-2 if one.precision == synth.PREC_BF16 else 1e-4
+    out["bar"] = bar
+    out["ok"] = bool(max(out["rel_l2_Y"], out["rel_l2_dX"], out["rel_l2_G"]) <= bar)
+    out["what"] = "one layer of the workload's shape, microbatch 1 of seed 0, 1024 sampled positions per tensor vs the fp64 oracle"
+    return out
 
 
 def pipeline_bench(args, cfg, w0):
@@ -153,7 +219,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C2", help="C1..C5 (see paper_2006_09503_amd/synth.py)")
+    ap.add_argument("--workload", default="C5", help="C1..C5 (see paper_2006_09503_amd/synth.py)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--flush", action="store_true", help="PipeDream-Flush (Section 3.2) instead of 2BW: one version, drain per batch")
     ap.add_argument("--recompute", type=int, default=None, help="override the workload's activation recomputation (0/1)")
@@ -165,7 +231,10 @@ def main():
                     help="2: backward passes and updates on a stream of their own, so that the forward and backward "
                          "passes of different microbatches overlap (the per-kernel timing region always runs on one "
                          "stream: each kernel then has the GPU to itself)")
+    ap.add_argument("--wgrad-group", type=int, default=None, help="override how many microbatches' weight-gradient "
+                    "products one launch covers (reduction length j*T; default: the library's choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefix-check", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -187,10 +256,13 @@ def main():
         cfg = cfg.with_(recompute=args.recompute)
     if args.microbatch is not None:
         cfg = cfg.with_(microbatch=args.microbatch)
+    if args.wgrad_group is not None:
+        cfg = cfg.with_(wgrad_group=args.wgrad_group)
     p, m = cfg.max_inflight, cfg.m
     K, W = args.steps, args.warmup
     assert K >= 1 and W >= 2, "two warm-up batches are needed before the version rule leaves version 0"
 
+    check = None if args.no_prefix_check else prefix_check(args.workload, cfg, args.seed)
     gen = synth.StageInputs(cfg, args.seed)
     w0 = gen.weights()
     if args.stages > 1:
@@ -312,7 +384,7 @@ def main():
         r = gemm_inst[dom]
         achieved = r["flops"] / (r["ms"] * 1e-3) / 1e12
         roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(dom),
+                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args, dom),
                     "avg_launch_us": r["ms"] / r["launches"] * 1e3, "launches_per_step": r["launches"] / K,
                     "flops_per_launch": r["flops"] / r["launches"], "empty_event_pair_us": gap_ms * 1e3,
                     "share_of_step": r["ms"] / K / ms_per_step}
@@ -339,7 +411,7 @@ def main():
                    "samples_per_step": cfg.microbatch * m, "model_flops_per_step": flops_step,
                    "stage_bytes_allocated": alloc},
         "model_tflops": tflops, "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS, "outputs_finite": finite,
-        "roofline": roofline, "kernels": kernels,
+        "prefix_check": check, "roofline": roofline, "kernels": kernels,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, args.seed)

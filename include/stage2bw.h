@@ -78,6 +78,13 @@ typedef struct {
   int32_t optimizer;    /* STAGE_OPT_ADAM, or STAGE_OPT_MOMENTUM: m <- beta1 m + (1-beta1) g,    */
                         /* W(t+1) = W(t) - lr m, the form Section 3.1 prints (beta2, adam_eps    */
                         /* unused; the second-moment array is not allocated)                  */
+  int32_t wgrad_group;  /* backward passes whose weight-gradient products share one launch with the  */
+                        /* reduction range j*T (the accumulator of Section 3.1 is then read and       */
+                        /* written once per j microbatches; a group never crosses a batch end, so the */
+                        /* coalesced sum is the same up to the order of fp32 additions).  0: the      */
+                        /* library's choice (4); 1..8: at most this many.  Always 1 in fp32 mode and   */
+                        /* when b*s is not a multiple of 64.  Each unit above 1 keeps one more set of  */
+                        /* activations alive (with recompute: one more scratch set)                    */
 } stage_config_t;
 
 /*
@@ -119,7 +126,8 @@ int stage_forward(stage_t* st, int64_t mb, const void* x_dev, const int32_t* seq
  * (Section 3.1: same version for both passes).  dy_dev: gradient wrt the stage output,
  * dx_dev: receives the gradient wrt the stage input, both [b, s, h], dtype as in forward.
  * Weight gradients are added in place into the coalesced accumulator (the first backward of a
- * batch overwrites it).  Frees the stash slot.  BAD_STATE if mb is not in flight or m
+ * batch overwrites it), at the latest when the batch's last backward pass is enqueued (see
+ * wgrad_group).  Frees the stash slot.  BAD_STATE if mb is not in flight or m
  * backward passes are already waiting for stage_coalesce_update.
  */
 int stage_backward(stage_t* st, int64_t mb, const void* dy_dev, void* dx_dev);
@@ -167,7 +175,8 @@ enum { STAGE_WEIGHTS_BUF0 = 0, STAGE_WEIGHTS_BUF1 = 1, STAGE_WEIGHTS_MASTER = 2 
 /* which: one of the two version buffers (converted to fp32), or the fp32 master (in fp32 mode
  * the master is the buffer holding W(t)).  out_host: P floats. */
 int stage_read_weights(stage_t* st, int which, float* out_host);
-/* The coalesced accumulator (sum over the backward passes since the last update). */
+/* The coalesced accumulator (sum over the backward passes since the last update); weight-gradient
+ * products still waiting for their group (wgrad_group) are launched first. */
 int stage_read_grad_accum(stage_t* st, float* out_host);
 /* Adam first and second moments (momentum SGD: its one moment; v_out_host must then be NULL);
  * either pointer may be NULL. */

@@ -40,6 +40,16 @@ int k2bw_gemm(int dtype, int trans_a, int trans_b, int epilogue, int M, int N, i
               int lda, const void* B, int ldb, void* C, int ldc, const void* bias, const void* aux,
               void* aux_out, int accumulate, void* stream);
 
+/* The coalesced weight gradient of n_seg microbatches in one product (bf16; Section 3.1's sum over the
+ * microbatches of a batch, taken inside the reduction): C[M,N] (fp32) = (accumulate ? C : 0) +
+ * sum over s < n_seg of X_s^T dY_s, X_s: [T, M] (ld = lda) at A0 + a_idx[s] * a_stride_bytes,
+ * dY_s: [T, N] (ld = ldb) at B0 + b_idx[s] * b_stride_bytes.  n_seg 1..8, indices 0..15 (host arrays of
+ * n_seg bytes), strides multiples of 256 bytes, T a multiple of 64; INVALID_ARG otherwise. */
+int k2bw_gemm_wgrad_segmented(int M, int N, int T, int n_seg, const void* A0, int lda,
+                              int64_t a_stride_bytes, const uint8_t* a_idx_host, const void* B0, int ldb,
+                              int64_t b_stride_bytes, const uint8_t* b_idx_host, float* C, int ldc,
+                              int accumulate, void* stream);
+
 /* The FC2 data gradient with the GELU derivative and the FC1 bias gradient in one pass (bf16):
  * du[M,N] = (dy[M,K] w[N,K]^T) * GELU'(u[M,N]);  dbias[N] (fp32) = (accumulate ? dbias : 0) +
  * sum over rows of du, summed from the fp32 values before du is rounded to bf16.

@@ -28,7 +28,7 @@ class StageConfigC(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_heads", "ffn", "seq", "microbatch", "m",
                                          "max_inflight", "mask_mode", "precision", "recompute")] + \
                [(n, C.c_float) for n in ("lr", "beta1", "beta2", "adam_eps", "ln_eps")] + \
-               [("flush", C.c_int32), ("optimizer", C.c_int32)]
+               [("flush", C.c_int32), ("optimizer", C.c_int32), ("wgrad_group", C.c_int32)]
 
 
 class PlannerInputC(C.Structure):
@@ -88,6 +88,8 @@ def lib() -> C.CDLL:
             "stage_sched_query": (C.c_int, [vp, C.c_int, C.POINTER(i64)]),
             "stage_sched_destroy": (C.c_int, [vp]),
             "k2bw_gemm": (C.c_int, [C.c_int] * 7 + [vp, C.c_int, vp, C.c_int, vp, C.c_int, vp, vp, vp, C.c_int, vp]),
+            "k2bw_gemm_wgrad_segmented": (C.c_int, [C.c_int] * 4 + [vp, C.c_int, i64, vp, vp, C.c_int, i64, vp, vp, C.c_int,
+                                                      C.c_int, vp]),
             "k2bw_layernorm_fwd": (C.c_int, [C.c_int, C.c_int, C.c_int, f32, vp, vp, vp, vp, vp, vp, vp]),
             "k2bw_gemm_dgrad_gelu_bias_workspace": (i64, [C.c_int, C.c_int]),
             "k2bw_gemm_dgrad_gelu_bias": (C.c_int, [C.c_int, C.c_int, C.c_int, vp, C.c_int, vp, C.c_int, vp, C.c_int, vp, vp, C.c_int, vp, vp]),

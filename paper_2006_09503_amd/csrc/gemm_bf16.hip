@@ -53,6 +53,11 @@ struct BfParams {
   int tile_m;      // rows of C per tile: the kernel's BM, or BM/2 in the balanced tail of a ring launch
   const void* prefetch;        // lines to touch for a later launch, or null (ring kernels)
   uint32_t prefetch_bytes;     // multiple of 4, below 2^31
+  // segmented reduction range (ring kernels): K tiles per piece (the launcher fills it in; K / tile for
+  // a plain problem), the buffer index of every piece in 4-bit fields (piece 0 lowest) and the
+  // distance between consecutive buffer indices in units of 256 bytes
+  int seg_tiles;
+  uint32_t a_seg, b_seg, a_stride256, b_stride256;
 };
 
 // Up to kMaxGroup independent GEMMs of the same form in one launch: workgroup ids
@@ -725,14 +730,56 @@ struct AsyncLoader {
   // on the scalar unit and a load sends half the address data of the 64-bit form (+2..5 % on the
   // weight-gradient form).
   // lds_tile: byte address of the stage's tile in LDS, wave-uniform.
-  __device__ __forceinline__ void issue_one_untracked(int j, int k0, uint32_t lds_tile) const {
-    const bf16_t* b = K_CONTIG ? base_ + k0 : base_ + (int64_t)k0 * ld_;
+  // tile_addr: address of the tile's element (row0, k0), wave-uniform.
+  __device__ __forceinline__ void issue_one_untracked(int j, uint64_t tile_addr, uint32_t lds_tile) const {
     const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + (uint32_t)(first_slot_ + j * 64) * 16u);
-    const uint64_t sb = uniform_address(b);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(dst), "v"(voff[j]), "s"(sb)
+                 : "s"(dst), "v"(voff[j]), "s"(tile_addr)
                  : "memory");   // (M0 is reserved: the compiler keeps nothing in it)
+  }
+  // bytes from one K tile to the next inside a contiguous piece of the reduction range
+  __device__ __forceinline__ uint32_t tile_step_bytes() const {
+    return K_CONTIG ? (uint32_t)BKA * 2u : (uint32_t)BKA * (uint32_t)ld_ * 2u;
+  }
+};
+
+// The addresses of successive K tiles of both operands, all in scalar registers.  The reduction
+// range is made of pieces of seg_tiles tiles each; piece s of an operand lies in buffer number
+// (seg >> 4s) & 15, the buffers being `stride` bytes apart (a plain problem is one piece).  Past the
+// last tile the walk stays where it is: that tile is fetched again and never read.
+struct TileWalk {
+  uint64_t a_addr, b_addr;       // tile about to be requested
+  uint64_t a_base, b_base;       // element (row0, k = 0) of buffer number 0
+  uint64_t a_stride, b_stride;   // bytes between consecutive buffer numbers
+  uint32_t a_step, b_step;       // bytes between consecutive tiles of a piece
+  uint32_t a_rest, b_rest;       // buffer numbers of this and the later pieces (this one in the low 4 bits)
+  int left;                      // tiles left in this piece, this one included
+  int seg_tiles;
+  int remaining;                 // tiles left in the whole range, this one included
+  __device__ __forceinline__ void init(const void* a0, const void* b0, uint32_t a_step_, uint32_t b_step_, const BfParams& p,
+                                       int nk) {
+    a_base = uniform_address(a0); b_base = uniform_address(b0);
+    a_step = a_step_; b_step = b_step_;
+    a_stride = (uint64_t)p.a_stride256 << 8; b_stride = (uint64_t)p.b_stride256 << 8;
+    a_rest = p.a_seg; b_rest = p.b_seg;
+    seg_tiles = p.seg_tiles; left = p.seg_tiles; remaining = nk;
+    a_addr = a_base + (uint64_t)(a_rest & 15u) * a_stride;
+    b_addr = b_base + (uint64_t)(b_rest & 15u) * b_stride;
+  }
+  __device__ __forceinline__ void advance() {
+    const int more = min(remaining - 1, 1);   // 1 while another tile follows, then 0 (remaining >= 1 always)
+    remaining -= more;
+    left -= more;
+    if (left == 0) {   // wave-uniform, once per piece
+      left = seg_tiles;
+      a_rest >>= 4; b_rest >>= 4;
+      a_addr = a_base + (uint64_t)(a_rest & 15u) * a_stride;
+      b_addr = b_base + (uint64_t)(b_rest & 15u) * b_stride;
+    } else {
+      a_addr += a_step * (uint32_t)more;
+      b_addr += b_step * (uint32_t)more;
+    }
   }
 };
 
@@ -812,13 +859,14 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
   const int nk = p.K / BKA;   // K is a multiple of BKA
-  // tile t (clamped past the end: fetched again, never read) goes to stage t & (NS - 1);
+  // tile t (past the end: the last one again, never read) goes to stage t & (NS - 1);
   // a stage's LDS byte address: the low half of a generic pointer into LDS is its LDS address
   const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)reinterpret_cast<uintptr_t>(smem));
-  auto tile_k = [&](int t) { return (t < nk ? t : nk - 1) * BKA; };
-  auto issue = [&](int v, int k0, uint32_t stage_bytes) {
-    if (v < IPA) ld_a.issue_one_untracked(v, k0, stage_bytes);
-    else ld_b.issue_one_untracked(v - IPA, k0, stage_bytes + (uint32_t)(BM * CHK) * 16u);
+  TileWalk walk;   // the tile the next loads fetch
+  walk.init(ld_a.base_, ld_b.base_, ld_a.tile_step_bytes(), ld_b.tile_step_bytes(), p, nk);
+  auto issue = [&](int v, uint32_t stage_bytes) {
+    if (v < IPA) ld_a.issue_one_untracked(v, walk.a_addr, stage_bytes);
+    else ld_b.issue_one_untracked(v - IPA, walk.b_addr, stage_bytes + (uint32_t)(BM * CHK) * 16u);
   };
   // Lines of the operand a later launch will read (GemmDesc::prefetch): every wave of the launch
   // touches 64 of them, 128 bytes apart, with one 4-byte load in front of its own first loads.  The
@@ -831,9 +879,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
     const uint32_t off = min(line * 128u, p.prefetch_bytes - 4u);
     asm volatile("global_load_dword %0, %1, %2" : "=v"(touched) : "v"(off), "s"(uniform_address(p.prefetch)) : "memory");
   }
-  for (int t = 0; t < NS - 1; ++t)
 #pragma unroll
-    for (int v = 0; v < NV; ++v) issue(v, tile_k(t), lds_base + (uint32_t)(t * kStage) * 16u);
+  for (int t = 0; t < NS - 1; ++t) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) issue(v, lds_base + (uint32_t)(t * kStage) * 16u);
+    walk.advance();
+  }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * NV));
   __syncthreads();
   bf16x8 af[2][MI], bfr[2][NI];
@@ -855,11 +906,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
     // barrier, so at the wait the tiles kt+2 .. kt+NS-2 may be outstanding
     for (int kt = 0; kt < nk; ++kt) {
       const uint32_t l_stage = lds_base + (uint32_t)(((kt + NS - 1) & (NS - 1)) * kStage) * 16u;
-      const int k_load = tile_k(kt + NS - 1);
       __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 3) * NV));
       __syncthreads();
 #pragma unroll
-      for (int v = 0; v < NV; ++v) issue(v, k_load, l_stage);
+      for (int v = 0; v < NV; ++v) issue(v, l_stage);
+      walk.advance();
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
@@ -876,7 +927,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
     const uint4* nA = smem + ((st + 1) & (NS - 1)) * kStage;
     const uint4* nB = nA + BM * CHK;
     const uint32_t l_stage = lds_base + (uint32_t)(((st + NS - 1) & (NS - 1)) * kStage) * 16u;
-    const int k_load = tile_k(kt + NS - 1);
+    (void)kt;   // the loads of this step fetch tile kt + NS - 1, which is where `walk` stands
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int cur = ks & 1, nxt = cur ^ 1;
@@ -893,7 +944,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
         const int mi = i / NI, ni = i % NI, q = ks * NM + i;
         acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (q % EVERY == 0) issue(q / EVERY, k_load, l_stage);
+        if (q % EVERY == 0) issue(q / EVERY, l_stage);
         if (i < H) {
 #pragma unroll
           for (int f = (NF * i) / H; f < (NF * (i + 1)) / H; ++f) {
@@ -904,6 +955,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+    walk.advance();
   };
   int kt = 0;
   for (; kt + NS <= nk; kt += NS) {
@@ -970,6 +1022,8 @@ hipError_t launch_ring(GroupParams gp, hipStream_t s) {
   }
   int64_t full = 0;
   for (int g = 0; g < gp.count; ++g) {
+    // (seg_tiles arrives as the number of pieces; choose_tile has checked that a piece is whole K tiles)
+    gp.p[g].seg_tiles = gp.p[g].K / BKA / (gp.p[g].seg_tiles > 1 ? gp.p[g].seg_tiles : 1);
     gp.p[g].tile_m = BM;
     gp.p[g].tiles_m = ceil_div(gp.p[g].M, BM);
     gp.p[g].tiles_n = ceil_div(gp.p[g].N, BN);
@@ -1066,10 +1120,13 @@ int choose_tile(const BfParams* p, int count, bool ta, bool tb) {
     tile = big >= 144 ? 23 : small <= 256 ? 22 : 2;
     (void)ta; (void)tb;
   }
-  if (tile > 20) {   // the ring kernels need whole K tiles
+  bool segmented = false;
+  for (int g = 0; g < count; ++g) segmented = segmented || p[g].seg_tiles > 1;
+  if (segmented && tile < 20) tile = 22;   // only the ring kernels walk a segmented reduction range
+  if (tile > 20) {   // the ring kernels need whole K tiles (in every piece of a segmented range)
     const int bk = tile == 22 ? 64 : 32;
     for (int g = 0; g < count; ++g)
-      if (p[g].K % bk) { tile = tile == 22 ? 6 : 3; break; }
+      if ((p[g].K / (p[g].seg_tiles > 1 ? p[g].seg_tiles : 1)) % bk) { tile = segmented ? -1 : tile == 22 ? 6 : 3; break; }
   }
   return tile;
 }
@@ -1093,6 +1150,12 @@ bool vector_ok(const GemmDesc& d) {
            (reinterpret_cast<uintptr_t>(d.aux) & 15) || (reinterpret_cast<uintptr_t>(d.aux_out) & 15));
 }
 
+uint32_t pack_seg(const uint8_t* idx, int n) {
+  uint32_t v = 0;
+  for (int s = 0; s < n && s < 8; ++s) v |= (uint32_t)(idx[s] & 15) << (4 * s);
+  return v;
+}
+
 BfParams to_params(const GemmDesc& d) {
   return BfParams{static_cast<const bf16_t*>(d.A), static_cast<const bf16_t*>(d.B), d.C,
                   d.M, d.N, d.K, d.lda, d.ldb, d.ldc, static_cast<const bf16_t*>(d.bias),
@@ -1100,7 +1163,24 @@ BfParams to_params(const GemmDesc& d) {
                   d.epilogue == kEpiGeluGrad ? d.colsum_partial : nullptr, d.accumulate ? 1 : 0, 0, 0, 0,
                   // (matrices beyond the reach of one launch's touches, or of the cache, are left alone)
                   d.prefetch_bytes >= 4 && d.prefetch_bytes <= (32ll << 20) ? d.prefetch : nullptr,
-                  (uint32_t)(d.prefetch_bytes >= 4 && d.prefetch_bytes <= (32ll << 20) ? d.prefetch_bytes & ~3ll : 0)};
+                  (uint32_t)(d.prefetch_bytes >= 4 && d.prefetch_bytes <= (32ll << 20) ? d.prefetch_bytes & ~3ll : 0),
+                  // (a plain problem walks one piece in buffer 0: its index and stride fields are not looked at)
+                  d.n_seg, d.n_seg > 1 ? pack_seg(d.a_seg_idx, d.n_seg) : 0u, d.n_seg > 1 ? pack_seg(d.b_seg_idx, d.n_seg) : 0u,
+                  d.n_seg > 1 ? (uint32_t)(d.a_seg_stride >> 8) : 0u, d.n_seg > 1 ? (uint32_t)(d.b_seg_stride >> 8) : 0u};
+}
+
+// A segmented reduction range is valid for the weight-gradient form only, with pieces of equal length
+// in buffers 0..15 at strides that are multiples of 256 bytes and below 2^40.
+bool segments_ok(const GemmDesc& d) {
+  if (d.n_seg == 1) return true;
+  if (d.n_seg < 1 || d.n_seg > kGemmMaxSegments || d.epilogue != kEpiAccum || !d.trans_a || d.trans_b) return false;
+  if (d.K % d.n_seg) return false;
+  if (d.a_seg_stride < 0 || d.b_seg_stride < 0 || (d.a_seg_stride & 255) || (d.b_seg_stride & 255) ||
+      (d.a_seg_stride >> 40) || (d.b_seg_stride >> 40))
+    return false;
+  for (int s = 0; s < d.n_seg; ++s)
+    if (d.a_seg_idx[s] > 15 || d.b_seg_idx[s] > 15) return false;
+  return true;
 }
 
 }  // namespace
@@ -1131,9 +1211,9 @@ hipError_t gemm_bf16_grouped(const GemmDesc* d, int count, hipStream_t stream) {
   GroupParams gp{};
   gp.count = count;
   for (int g = 0; g < count; ++g) {
-    if (!vector_ok(d[g])) return hipErrorInvalidValue;
-    // the kernels address an operand with 32-bit byte offsets from its first element
-    const int64_t a_rows = d[g].trans_a ? d[g].K : d[g].M, b_rows = d[g].trans_b ? d[g].N : d[g].K;
+    if (!vector_ok(d[g]) || !segments_ok(d[g])) return hipErrorInvalidValue;
+    // the kernels address an operand with 32-bit byte offsets from its first element (of a piece)
+    const int64_t a_rows = d[g].trans_a ? d[g].K / d[g].n_seg : d[g].M, b_rows = d[g].trans_b ? d[g].N : d[g].K / d[g].n_seg;
     if (a_rows * (int64_t)d[g].lda * 2 >= (1ll << 31) || b_rows * (int64_t)d[g].ldb * 2 >= (1ll << 31))
       return hipErrorInvalidValue;
     if (d[g].trans_a != d[0].trans_a || d[g].trans_b != d[0].trans_b || d[g].epilogue != d[0].epilogue)

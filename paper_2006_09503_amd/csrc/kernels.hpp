@@ -20,6 +20,7 @@ enum Epilogue : int {
   kEpiAccum = 3      // C is fp32: C = (accumulate ? C : 0) + acc   (weight-gradient coalescing)
 };
 
+constexpr int kGemmMaxSegments = 8;   // pieces of a segmented reduction range (see GemmDesc::n_seg)
 struct GemmDesc {
   const void* A = nullptr;
   const void* B = nullptr;
@@ -41,6 +42,14 @@ struct GemmDesc {
   // so that they come from the memory-side cache and not from HBM when they are needed.  Never written.
   const void* prefetch = nullptr;
   int64_t prefetch_bytes = 0;
+  // bf16, kEpiAccum form only: the reduction range made of n_seg pieces of K / n_seg rows each that lie
+  // in different buffers (the operands of several microbatches' weight-gradient products, summed by
+  // one product of reduction length n_seg * T).  Piece s of A starts at A + a_seg_idx[s] * a_seg_stride
+  // bytes, piece s of B at B + b_seg_idx[s] * b_seg_stride bytes: buffers carved at a constant
+  // stride from one allocation, indices 0..15, strides multiples of 256 bytes.  n_seg = 1: plain.
+  int n_seg = 1;
+  uint8_t a_seg_idx[kGemmMaxSegments] = {}, b_seg_idx[kGemmMaxSegments] = {};
+  int64_t a_seg_stride = 0, b_seg_stride = 0;
   int dtype = kF32;
 };
 hipError_t gemm(const GemmDesc& d, hipStream_t stream);

@@ -38,6 +38,23 @@ int k2bw_gemm(int dtype, int trans_a, int trans_b, int epilogue, int M, int N, i
   return rc_of(gemm(d, static_cast<hipStream_t>(stream)));
 }
 
+int k2bw_gemm_wgrad_segmented(int M, int N, int T, int n_seg, const void* A0, int lda, int64_t a_stride_bytes,
+                              const uint8_t* a_idx_host, const void* B0, int ldb, int64_t b_stride_bytes,
+                              const uint8_t* b_idx_host, float* C, int ldc, int accumulate, void* stream) {
+  if (n_seg < 1 || n_seg > kGemmMaxSegments || T <= 0 || !a_idx_host || !b_idx_host) return STAGE_ERR_INVALID_ARG;
+  GemmDesc d;
+  d.dtype = kBF16; d.trans_a = true; d.epilogue = kEpiAccum;
+  d.M = M; d.N = N; d.K = n_seg * T; d.A = A0; d.lda = lda; d.B = B0; d.ldb = ldb; d.C = C; d.ldc = ldc;
+  d.accumulate = accumulate != 0;
+  d.n_seg = n_seg; d.a_seg_stride = a_stride_bytes; d.b_seg_stride = b_stride_bytes;
+  for (int s = 0; s < n_seg; ++s) { d.a_seg_idx[s] = a_idx_host[s]; d.b_seg_idx[s] = b_idx_host[s]; }
+  if (n_seg == 1) {   // a plain product on the one piece
+    d.A = static_cast<const char*>(A0) + a_stride_bytes * a_idx_host[0];
+    d.B = static_cast<const char*>(B0) + b_stride_bytes * b_idx_host[0];
+  }
+  return rc_of(gemm(d, static_cast<hipStream_t>(stream)));
+}
+
 int64_t k2bw_gemm_dgrad_gelu_bias_workspace(int M, int N) {
   if (M <= 0 || N <= 0) return STAGE_ERR_INVALID_ARG;
   return (int64_t)((M + 31) / 32) * N;

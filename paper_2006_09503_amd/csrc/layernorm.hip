@@ -219,6 +219,149 @@ __global__ __launch_bounds__(kWg) void ln_bwd_kernel(const T* __restrict__ dy, c
   }
 }
 
+// Backward for long rows (h >= 2048).  With 256 threads the per-column sums of a row of 8192 take 96
+// registers per thread next to the row itself, one wave per SIMD fits, and a CU has too few loads in
+// flight to keep HBM busy.  Here a workgroup has 1024 threads, R = 256, 512 or 1024 of them share a row
+// with one or two 16-byte chunks each, so the sums are 24 or 48 registers, sixteen waves stay resident
+// per CU and U rows per thread are loaded before any arithmetic.  The two row sums share one round of
+// barriers.  Same partial-row layout as the kernel above; the grid is one workgroup per CU at most.
+constexpr int kWgWide = 1024;
+
+// (s1, s2) summed over the R threads that share a row; red: [2][16] floats
+template <int R>
+__device__ __forceinline__ void group_sum2_wide(float& s1, float& s2, float* red, int tid) {
+  s1 = wave_sum(s1);
+  s2 = wave_sum(s2);
+  constexpr int W = R / 64;
+  const int wave = tid >> 6;
+  __syncthreads();
+  if ((tid & 63) == 0) { red[wave] = s1; red[16 + wave] = s2; }
+  __syncthreads();
+  const int first = (wave / W) * W;
+  float a = 0.f, b = 0.f;
+#pragma unroll
+  for (int i = 0; i < W; ++i) { a += red[first + i]; b += red[16 + first + i]; }
+  s1 = a; s2 = b;
+}
+
+template <typename T, int R, int CPT, int U>
+__global__ __launch_bounds__(kWgWide) void ln_bwd_wide_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                              const float* __restrict__ mean_in,
+                                                              const float* __restrict__ rstd_in, const T* __restrict__ gain,
+                                                              const T* __restrict__ dres, T* __restrict__ dx,
+                                                              float* __restrict__ partial, int rows, int h) {
+  constexpr int ROWS = kWgWide / R;
+  __shared__ float red[32];
+  __shared__ float comb[(ROWS > 1) ? (ROWS - 1) * R * CPT * 8 : 1];
+  const int tid = threadIdx.x;
+  const int sub = tid % R, rsub = tid / R;
+  float gsum[CPT][8], bsum[CPT][8], osum[CPT][8], gn[CPT][8];
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) {
+    const int col = (sub + c * R) * 8;
+    if (col < h) load8(gain + col, gn[c]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { gsum[c][i] = 0.f; bsum[c][i] = 0.f; osum[c][i] = 0.f; if (col >= h) gn[c][i] = 0.f; }
+  }
+  const int n_groups = (rows + ROWS - 1) / ROWS;
+  for (int grp0 = blockIdx.x; grp0 < n_groups; grp0 += U * gridDim.x) {
+    int row[U];
+    bool row_ok[U];
+    float mean[U], rstd[U];
+    float xh[U][CPT][8], dxh[U][CPT][8], res[U][CPT][8];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int grp = grp0 + u * gridDim.x;
+      row[u] = grp * ROWS + rsub;
+      row_ok[u] = grp < n_groups && row[u] < rows;
+      mean[u] = row_ok[u] ? mean_in[row[u]] : 0.f;
+      rstd[u] = row_ok[u] ? rstd_in[row[u]] : 0.f;
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int col = (sub + c * R) * 8;
+        if (row_ok[u] && col < h) {
+          load8(x + (int64_t)row[u] * h + col, xh[u][c]);
+          load8(dy + (int64_t)row[u] * h + col, dxh[u][c]);
+          if (dres) load8(dres + (int64_t)row[u] * h + col, res[u][c]);
+        } else {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) { xh[u][c][i] = 0.f; dxh[u][c][i] = 0.f; }
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int col = (sub + c * R) * 8;
+        if (row_ok[u] && col < h) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const float dv = dxh[u][c][i];
+            xh[u][c][i] = (xh[u][c][i] - mean[u]) * rstd[u];
+            dxh[u][c][i] = dv * gn[c][i];
+            s1 += dxh[u][c][i];
+            s2 += dxh[u][c][i] * xh[u][c][i];
+            gsum[c][i] += dv * xh[u][c][i];
+            bsum[c][i] += dv;
+          }
+        }
+      }
+      group_sum2_wide<R>(s1, s2, red, tid);
+      const float c1 = s1 / (float)h, c2 = s2 / (float)h;
+      if (row_ok[u]) {
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+          const int col = (sub + c * R) * 8;
+          if (col < h) {
+            float o[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] = rstd[u] * (dxh[u][c][i] - c1 - xh[u][c][i] * c2);
+            if (dres) {
+#pragma unroll
+              for (int i = 0; i < 8; ++i) o[i] += res[u][c][i];
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) osum[c][i] += o[i];
+            store8(dx + (int64_t)row[u] * h + col, o);
+          }
+        }
+      }
+    }
+  }
+  // combine the ROWS sub-rows of this workgroup, then one partial row per workgroup
+#pragma unroll
+  for (int which = 0; which < 3; ++which) {
+    if (ROWS > 1) {
+      __syncthreads();
+      if (rsub > 0) {
+#pragma unroll
+        for (int c = 0; c < CPT; ++c)
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            comb[(((rsub - 1) * CPT + c) * 8 + i) * R + sub] = which == 0 ? gsum[c][i] : which == 1 ? bsum[c][i] : osum[c][i];
+      }
+      __syncthreads();
+    }
+    if (rsub == 0) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int col = (sub + c * R) * 8;
+        if (col < h) {
+          float o[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            o[i] = which == 0 ? gsum[c][i] : which == 1 ? bsum[c][i] : osum[c][i];
+            for (int rr = 1; rr < ROWS; ++rr) o[i] += comb[(((rr - 1) * CPT + c) * 8 + i) * R + sub];
+          }
+          store8(partial + (int64_t)blockIdx.x * 3 * h + which * h + col, o);
+        }
+      }
+    }
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kWg) void colsum_partial_kernel(const T* __restrict__ y, int rows, int n, int ld,
                                                               float* __restrict__ partial, int rows_per_part) {
@@ -419,6 +562,33 @@ hipError_t layernorm_bwd(const void* dy, const void* x, const float* mean, const
   if (!aligned16(dy) || !aligned16(x) || !aligned16(dx) || !aligned16(gain) || !aligned16(partial) ||
       (dres && !aligned16(dres)))
     return hipErrorInvalidValue;
+  if (h >= 2048) {
+    // long rows: 1024-thread workgroups, at most one per CU (256 partial rows)
+    const int chunks = h / 8;
+    const int R = chunks <= 256 ? 256 : chunks <= 512 ? 512 : 1024;
+    const int cpt = ceil_div(chunks, R);   // 1, or 2 above h = 8192 (h <= 16384)
+    const int groups = ceil_div(rows, kWgWide / R);
+    const int grid = groups < 256 ? groups : 256;
+#define CALL_WIDE(R_, C_, U_)                                                                                \
+  if (dtype == kBF16)                                                                                        \
+    hipLaunchKernelGGL((ln_bwd_wide_kernel<bf16_t, R_, C_, U_>), dim3(grid), dim3(kWgWide), 0, stream,       \
+                       static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(x), mean, rstd,            \
+                       static_cast<const bf16_t*>(gain),                                                     \
+                       static_cast<const bf16_t*>(dres), static_cast<bf16_t*>(dx), partial, rows, h);        \
+  else                                                                                                       \
+    hipLaunchKernelGGL((ln_bwd_wide_kernel<float, R_, C_, U_>), dim3(grid), dim3(kWgWide), 0, stream,        \
+                       static_cast<const float*>(dy), static_cast<const float*>(x), mean, rstd,              \
+                       static_cast<const float*>(gain),                                                      \
+                       static_cast<const float*>(dres), static_cast<float*>(dx), partial, rows, h)
+    if (cpt == 1 && R == 256) { CALL_WIDE(256, 1, 2); }
+    else if (cpt == 1 && R == 512) { CALL_WIDE(512, 1, 2); }
+    else if (cpt == 1) { CALL_WIDE(1024, 1, 2); }
+    else if (cpt == 2) { CALL_WIDE(1024, 2, 1); }
+    else return hipErrorInvalidValue;
+#undef CALL_WIDE
+    *parts_out = grid;
+    return hipGetLastError();
+  }
   const RowShape rs = row_shape(h);
   const int groups = ceil_div(rows, kWg / rs.R);
   const int grid = groups < ln_bwd_max_parts() ? groups : ln_bwd_max_parts();

@@ -6,9 +6,18 @@
 //   master    fp32 copy updated in place (bf16 mode only; it is never read by forward/backward)
 //   G         fp32 coalesced gradient accumulator
 //   adam_m/v  one copy of optimizer state
-//   slots     per in-flight microbatch: every saved activation of every layer, or just the
-//             stage input when activations are recomputed in the backward pass
+//   sets      activation sets (every saved activation of every layer for one microbatch), carved at a
+//             constant stride from one allocation.  Full stash: a microbatch owns a set from its
+//             forward pass until the grouped weight-gradient launch that consumed it; with
+//             recomputation the stash is the stage input only and the sets are scratch
 //   ws        backward temporaries, reduction partials
+//
+// Weight gradients of `wg_j` consecutive backward passes of a batch are computed by ONE grouped launch
+// whose reduction range is the concatenation of those passes' tokens (K = j*T): the fp32 accumulator is
+// read and written once per j microbatches instead of once per microbatch.  The operands of the passes
+// stay where they are (activation sets; per-position copies of the output gradients); the kernel walks
+// the pieces.  Groups never cross a batch boundary, so the coalesced sum of Section 3.1 is unchanged up
+// to the order of fp32 additions.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -59,8 +68,8 @@ struct stage2bw {
   bool two_streams = false;
   // two-stream ordering: per stash slot "forward written" / "backward has read"; per version
   // buffer "update has written"
-  std::vector<hipEvent_t> fwd_done, bwd_done;
-  std::vector<char> bwd_pending;
+  std::vector<hipEvent_t> fwd_done, bwd_done, set_done;   // per slot, per slot, per activation set
+  std::vector<char> bwd_pending, set_pending;
   hipEvent_t ver_ready[2] = {nullptr, nullptr};
   bool ver_pending[2] = {false, false};
   Schedule sched;
@@ -79,16 +88,28 @@ struct stage2bw {
   float* adam_m = nullptr;
   float* adam_v = nullptr;
 
-  std::vector<ActSet> slot_acts;   // full stash: one per slot; recompute: one shared set
+  // activation sets: sets[i] lives at acts_base + i * set_stride
+  std::vector<ActSet> sets;
+  char* acts_base = nullptr;
+  int64_t set_stride = 0;
+  std::vector<int> slot_set;       // full stash: the set an in-flight slot owns
+  std::vector<int> free_sets;      // full stash: sets nobody owns (oldest release first)
+  int fwd_scratch_set = 0;         // recompute: the set the forward pass scribbles on
   std::vector<char*> slot_x0;      // recompute: the stashed stage input per slot
   std::vector<int32_t*> slot_lens; // per slot: key lengths (padding mask)
+  // deferred weight-gradient products
+  int wg_j = 1;                    // backward passes per grouped weight-gradient launch
+  int n_pending = 0;               // passes whose products are still to be launched
+  bool pending_overwrite = false;  // the pending group holds the batch's first pass: its launch overwrites G
+  int pending_set[kGemmMaxSegments] = {};   // the set of each pending pass, in order
 
   // backward workspace
   // tmp_h is transient; the gradients that the weight-gradient products read (dx1, du, dqkv and
   // each layer's input gradient dchain) exist once per layer, because those products run after
   // the data-gradient chain of the whole stage
   char* tmp_h = nullptr;
-  std::vector<char*> dx1, dchain, du, dqkv;
+  std::vector<char*> dx1, dchain, du, dqkv;   // wg_j copies each, one per position in the pending group
+  char* dy_top = nullptr;     // wg_j copies of the stage's incoming gradient (only when wg_j > 1)
   char* y_scratch = nullptr;  // recompute: output of the re-run forward
   float* delta = nullptr;
   // per layer: partial rows of the bias / gain / shift gradients, reduced by one launch per backward pass
@@ -129,6 +150,7 @@ int validate(const stage_config_t* c) {
   if (c->recompute != 0 && c->recompute != 1) return STAGE_ERR_INVALID_ARG;
   if (c->flush != 0 && c->flush != 1) return STAGE_ERR_INVALID_ARG;
   if (c->optimizer != STAGE_OPT_ADAM && c->optimizer != STAGE_OPT_MOMENTUM) return STAGE_ERR_INVALID_ARG;
+  if (c->wgrad_group < 0 || c->wgrad_group > kGemmMaxSegments) return STAGE_ERR_INVALID_ARG;
   if (!(c->lr >= 0.f) || !(c->beta1 >= 0.f && c->beta1 < 1.f) || !(c->beta2 >= 0.f && c->beta2 < 1.f) ||
       !(c->adam_eps >= 0.f) || !(c->ln_eps >= 0.f))
     return STAGE_ERR_INVALID_ARG;
@@ -178,33 +200,36 @@ int dev_alloc(stage2bw* st, void** out, int64_t bytes, int64_t* account) {
   return STAGE_OK;
 }
 
-// One allocation holding an ActSet; returns STAGE_OK and fills set.
-int alloc_actset(stage2bw* st, ActSet* set) {
+// One allocation holding n activation sets at a constant stride (a multiple of 256 bytes).
+int alloc_sets(stage2bw* st, int n) {
   const stage_config_t& c = st->cfg;
   const int64_t T = st->T, h = c.hidden, f = c.ffn, E = st->esize;
   const int64_t act_h = align_up(T * h * E, 256), act_3h = align_up(T * 3 * h * E, 256), act_f = align_up(T * f * E, 256);
   const int64_t stat = align_up(T * 4, 256), lse = align_up((int64_t)c.microbatch * c.n_heads * c.seq * 4, 256);
   const int64_t per_layer = 5 * act_h + act_3h + 2 * act_f + 4 * stat + lse;
-  char* base = nullptr;
-  int rc = dev_alloc(st, reinterpret_cast<void**>(&base), per_layer * c.n_layers, &st->bytes_stash);
+  st->set_stride = per_layer * c.n_layers;
+  int rc = dev_alloc(st, reinterpret_cast<void**>(&st->acts_base), st->set_stride * n, &st->bytes_stash);
   if (rc != STAGE_OK) return rc;
-  set->layer.resize(c.n_layers);
-  for (int l = 0; l < c.n_layers; ++l) {
-    char* p = base + per_layer * l;
-    LayerActs& A = set->layer[l];
-    A.x = p; p += act_h;
-    A.a = p; p += act_h;
-    A.qkv = p; p += act_3h;
-    A.o = p; p += act_h;
-    A.x1 = p; p += act_h;
-    A.c = p; p += act_h;
-    A.u = p; p += act_f;
-    A.g = p; p += act_f;
-    A.mean1 = reinterpret_cast<float*>(p); p += stat;
-    A.rstd1 = reinterpret_cast<float*>(p); p += stat;
-    A.mean2 = reinterpret_cast<float*>(p); p += stat;
-    A.rstd2 = reinterpret_cast<float*>(p); p += stat;
-    A.lse = reinterpret_cast<float*>(p); p += lse;
+  st->sets.resize(n);
+  for (int i = 0; i < n; ++i) {
+    st->sets[i].layer.resize(c.n_layers);
+    for (int l = 0; l < c.n_layers; ++l) {
+      char* p = st->acts_base + st->set_stride * i + per_layer * l;
+      LayerActs& A = st->sets[i].layer[l];
+      A.x = p; p += act_h;
+      A.a = p; p += act_h;
+      A.qkv = p; p += act_3h;
+      A.o = p; p += act_h;
+      A.x1 = p; p += act_h;
+      A.c = p; p += act_h;
+      A.u = p; p += act_f;
+      A.g = p; p += act_f;
+      A.mean1 = reinterpret_cast<float*>(p); p += stat;
+      A.rstd1 = reinterpret_cast<float*>(p); p += stat;
+      A.mean2 = reinterpret_cast<float*>(p); p += stat;
+      A.rstd2 = reinterpret_cast<float*>(p); p += stat;
+      A.lse = reinterpret_cast<float*>(p); p += lse;
+    }
   }
   return STAGE_OK;
 }
@@ -312,52 +337,101 @@ hipError_t run_forward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens,
   return hipSuccess;
 }
 
-// Backward of all layers on weight buffer `buf`; weight gradients go into G (overwrite when
-// `first`, add otherwise).
-hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens, const void* dy_in, void* dx_out,
-                        bool first) {
+// The grouped weight-gradient launch(es) for the pending backward passes: per layer the four products
+// G_W (+)= [X_1; ..; X_n]^T [dY_1; ..; dY_n] over the n = n_pending passes' tokens.  The activation
+// operand of pass s lies in activation set pending_set[s], its gradient operand in copy s of the
+// layer's gradient buffers.
+hipError_t flush_wgrad(stage2bw* st) {
+  const int n = st->n_pending;
+  if (n == 0) return hipSuccess;
   const stage_config_t& c = st->cfg;
   const int T = st->T, h = c.hidden, f = c.ffn;
-  const bool acc = !first;
-  const double attn_flops = 10.0 * c.microbatch * (double)c.seq * c.seq * h;
-  const void* dy = dy_in;
-  // The four weight-gradient products of a layer are independent of the data-gradient chain
-  // once their operands exist, and each is small for 256 CUs (a layer's four give 192 tiles of
-  // 256 x 256 at the BERT-Large shape): they are collected over the layers and issued in grouped
-  // launches of up to kGemmMaxGroup products after the chain, where several rounds of tiles keep
-  // every CU busy.  The chain's result dX is enqueued before them.
+  const int64_t E = st->esize;
   std::vector<GemmDesc> wg;
   wg.reserve(4 * c.n_layers);
-  std::vector<FinalizeItem> fin;
-  fin.reserve(8 * c.n_layers);
-  double fin_elems = 0.0;
-  auto flush_wgrad = [&]() -> hipError_t {
-    for (size_t i0 = 0; i0 < wg.size(); i0 += kGemmMaxGroup) {
-      const int n = (int)std::min<size_t>(kGemmMaxGroup, wg.size() - i0);
-      double flops = 0.0;
-      for (int i = 0; i < n; ++i) flops += 2.0 * wg[i0 + i].M * (double)wg[i0 + i].N * wg[i0 + i].K;
-      char wg_name[96] = "";
-      if (st->timing) gemm_kernel_name(&wg[i0], n, wg_name, sizeof(wg_name));
-      hipError_t e = timed(st, STAGE_K_GEMM_WGRAD, wg_name, flops, 0.0, [&] { return gemm_grouped(&wg[i0], n, st->cur); });
-      if (e != hipSuccess) return e;
-    }
-    wg.clear();
-    return hipSuccess;
-  };
+  const int set0 = st->pending_set[0];
   for (int l = c.n_layers - 1; l >= 0; --l) {
     const LayerOff& o = st->off[l];
-    LayerActs& A = acts.layer[l];
-    void* dx = (l == 0) ? dx_out : static_cast<void*>(st->dchain[l]);
-    char *du = st->du[l], *dx1 = st->dx1[l], *dqkv = st->dqkv[l];
-    hipError_t e;
-    auto wgrad = [&](const void* act, int M, const void* grad, int N, float* out) {
+    auto product = [&](const char* act_in_set0, int M, const char* grad0, int64_t grad_copy_bytes, int N, float* out) {
       wg.emplace_back();
       GemmDesc& w = wg.back();
       w.dtype = st->dtype;
-      w.A = act; w.lda = M; w.trans_a = true; w.B = grad; w.ldb = N; w.C = out; w.ldc = N;
-      w.M = M; w.N = N; w.K = T; w.epilogue = kEpiAccum; w.accumulate = acc;
-      return hipSuccess;
+      w.lda = M; w.trans_a = true; w.ldb = N; w.C = out; w.ldc = N;
+      w.M = M; w.N = N; w.K = n * T; w.epilogue = kEpiAccum; w.accumulate = !st->pending_overwrite;
+      w.n_seg = n;
+      if (n == 1) {   // plain operands (the only form the fp32 kernels take)
+        w.A = act_in_set0 + st->set_stride * set0;
+        w.B = grad0;
+      } else {
+        w.A = act_in_set0; w.a_seg_stride = st->set_stride;
+        w.B = grad0; w.b_seg_stride = grad_copy_bytes;
+        for (int s = 0; s < n; ++s) { w.a_seg_idx[s] = (uint8_t)st->pending_set[s]; w.b_seg_idx[s] = (uint8_t)s; }
+      }
     };
+    const LayerActs& A = st->sets[0].layer[l];   // addresses inside set number 0
+    const char* dy0 = l == c.n_layers - 1 ? st->dy_top : st->dchain[l + 1];
+    product(A.g, f, dy0, (int64_t)T * h * E, h, st->G + o.w2);
+    product(A.c, h, st->du[l], (int64_t)T * f * E, f, st->G + o.w1);
+    product(A.o, h, st->dx1[l], (int64_t)T * h * E, h, st->G + o.wo);
+    product(A.a, h, st->dqkv[l], (int64_t)T * 3 * h * E, 3 * h, st->G + o.wqkv);
+  }
+  for (size_t i0 = 0; i0 < wg.size(); i0 += kGemmMaxGroup) {
+    const int cnt = (int)std::min<size_t>(kGemmMaxGroup, wg.size() - i0);
+    double flops = 0.0;
+    for (int i = 0; i < cnt; ++i) flops += 2.0 * wg[i0 + i].M * (double)wg[i0 + i].N * wg[i0 + i].K;
+    char wg_name[96] = "";
+    if (st->timing) gemm_kernel_name(&wg[i0], cnt, wg_name, sizeof(wg_name));
+    hipError_t e = timed(st, STAGE_K_GEMM_WGRAD, wg_name, flops, 0.0, [&] { return gemm_grouped(&wg[i0], cnt, st->cur); });
+    if (e != hipSuccess) return e;
+  }
+  // the sets are free again once this launch has run
+  if (!c.recompute) {
+    for (int s = 0; s < n; ++s) {
+      const int set = st->pending_set[s];
+      if (st->two_streams) {
+        hipError_t e = hipEventRecord(st->set_done[set], st->cur);
+        if (e != hipSuccess) return e;
+        st->set_pending[set] = 1;
+      }
+      st->free_sets.push_back(set);
+    }
+  }
+  st->n_pending = 0;
+  st->pending_overwrite = false;
+  return hipSuccess;
+}
+
+// Backward of all layers on weight buffer `buf` for the pass at position `pos` of the pending group,
+// whose activations are in set `set`.  Leaves the operands of the weight-gradient products in place
+// (flush_wgrad launches them); bias, gain and shift gradients go into G here (overwrite when `first`).
+hipError_t run_backward(stage2bw* st, int buf, int set, int pos, const int32_t* lens, const void* dy_in, void* dx_out,
+                        bool first) {
+  const stage_config_t& c = st->cfg;
+  const int T = st->T, h = c.hidden, f = c.ffn;
+  const int64_t E = st->esize;
+  const bool acc = !first;
+  const double attn_flops = 10.0 * c.microbatch * (double)c.seq * c.seq * h;
+  ActSet& acts = st->sets[set];
+  // the top layer's weight-gradient product reads the incoming gradient after this call has returned:
+  // keep a copy (one launch's worth of traffic per pass)
+  char* dy_keep = st->dy_top + (int64_t)pos * T * h * E;
+  {
+    const int64_t bytes = (int64_t)T * h * E;
+    hipError_t e = timed(st, STAGE_K_OTHER, "copy16_kernel", 0.0, 2.0 * bytes, [&] { return copy_bytes(dy_in, dy_keep, bytes, st->cur); });
+    if (e != hipSuccess) return e;
+  }
+  const void* dy = dy_keep;
+  std::vector<FinalizeItem> fin;
+  fin.reserve(8 * c.n_layers);
+  double fin_elems = 0.0;
+  for (int l = c.n_layers - 1; l >= 0; --l) {
+    const LayerOff& o = st->off[l];
+    LayerActs& A = acts.layer[l];
+    void* dx = (l == 0) ? dx_out : static_cast<void*>(st->dchain[l] + (int64_t)pos * T * h * E);
+    char* du = st->du[l] + (int64_t)pos * T * f * E;
+    char* dx1 = st->dx1[l] + (int64_t)pos * T * h * E;
+    char* dqkv = st->dqkv[l] + (int64_t)pos * T * 3 * h * E;
+    hipError_t e;
     // Bias gradients are column sums of the four projection-output gradients.  Three of them come
     // out of the kernels that produce those gradients: dx1 and this layer's result dx (= the next
     // lower layer's dy) from the LayerNorm backward kernels, du (bf16 mode) from the epilogue of
@@ -376,17 +450,14 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
       return run_gemm(st, STAGE_K_GEMM_DGRAD, d);
     };
     // y = x1 + GELU(u) W2 + b2
-    e = wgrad(A.g, f, dy, h, st->G + o.w2);                              if (e != hipSuccess) return e;
     e = dgrad(dy, h, wptr(st, buf, o.w2), f, du, A.u, wptr(st, buf, o.w1), (int64_t)h * f);   if (e != hipSuccess) return e;
     // u = c W1 + b1
-    e = wgrad(A.c, h, du, f, st->G + o.w1);                              if (e != hipSuccess) return e;
     e = dgrad(du, f, wptr(st, buf, o.w1), h, st->tmp_h, nullptr, wptr(st, buf, o.wo), (int64_t)h * h);   if (e != hipSuccess) return e;
     // c = LN2(x1); dx1 = dy + LN2'(dc)
     int ln2_parts = 0, ln1_parts = 0;
     e = run_ln_bwd(st, st->tmp_h, A.x1, A.mean2, A.rstd2, wptr(st, buf, o.ln2_g), dy, dx1, st->ln_partial[l], &ln2_parts);
     if (e != hipSuccess) return e;
     // x1 = x + o Wo + bo
-    e = wgrad(A.o, h, dx1, h, st->G + o.wo);                             if (e != hipSuccess) return e;
     e = dgrad(dx1, h, wptr(st, buf, o.wo), h, st->tmp_h, nullptr, wptr(st, buf, o.wqkv), (int64_t)3 * h * h);   if (e != hipSuccess) return e;
     // attention
     AttnDesc ad = attn_desc(st, lens);
@@ -397,7 +468,6 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     });
     if (e != hipSuccess) return e;
     // qkv = a Wqkv + bqkv
-    e = wgrad(A.a, h, dqkv, 3 * h, st->G + o.wqkv);                      if (e != hipSuccess) return e;
     e = dgrad(dqkv, 3 * h, wptr(st, buf, o.wqkv), h, st->tmp_h, nullptr, l > 0 ? wptr(st, buf, st->off[l - 1].w2) : nullptr,
               (int64_t)h * f);
     if (e != hipSuccess) return e;
@@ -440,7 +510,7 @@ hipError_t run_backward(stage2bw* st, int buf, ActSet& acts, const int32_t* lens
     });
     if (e != hipSuccess) return e;
   }
-  return flush_wgrad();
+  return hipSuccess;
 }
 
 int free_all(stage2bw* st) {
@@ -455,8 +525,10 @@ int free_all(stage2bw* st) {
   st->events.clear();
   for (hipEvent_t e : st->fwd_done) (void)hipEventDestroy(e);
   for (hipEvent_t e : st->bwd_done) (void)hipEventDestroy(e);
+  for (hipEvent_t e : st->set_done) (void)hipEventDestroy(e);
   st->fwd_done.clear();
   st->bwd_done.clear();
+  st->set_done.clear();
   for (hipEvent_t& e : st->ver_ready)
     if (e) { (void)hipEventDestroy(e); e = nullptr; }
   return rc;
@@ -520,12 +592,23 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
   ALLOC(st->adam_m, P * 4, nullptr);
   if (cfg->optimizer == STAGE_OPT_ADAM) ALLOC(st->adam_v, P * 4, nullptr);
 
-  const int n_sets = cfg->recompute ? 1 : cfg->max_inflight;
-  st->slot_acts.resize(n_sets);
-  for (int i = 0; i < n_sets; ++i) {
-    rc = alloc_actset(st, &st->slot_acts[i]);
-    if (rc != STAGE_OK) return fail(rc);
-  }
+  // Backward passes per grouped weight-gradient launch: the caller's choice, else 4; never more than m
+  // (a group stays inside its batch).  The segmented product exists in the bf16 ring kernels only, whose
+  // K tiles must divide a pass's tokens, and a set's number must fit the kernel's 4-bit fields.
+  int j = cfg->wgrad_group > 0 ? cfg->wgrad_group : 4;
+  if (j > cfg->m) j = cfg->m;
+  if (st->dtype != kBF16 || T % 64 != 0) j = 1;
+  if (!cfg->recompute && j > 1 && cfg->max_inflight + j - 1 > 16) j = std::max(1, 17 - cfg->max_inflight);
+  st->wg_j = j;
+  // full stash: a set per in-flight microbatch plus the j-1 that may wait for their group's launch;
+  // recompute: the j sets the pending passes re-computed into, and one for the forward pass to scribble on
+  const int n_sets = cfg->recompute ? j + 1 : cfg->max_inflight + j - 1;
+  rc = alloc_sets(st, n_sets);
+  if (rc != STAGE_OK) return fail(rc);
+  st->fwd_scratch_set = cfg->recompute ? j : 0;
+  st->slot_set.assign(cfg->max_inflight, -1);
+  if (!cfg->recompute)
+    for (int i = 0; i < n_sets; ++i) st->free_sets.push_back(i);
   st->slot_lens.resize(cfg->max_inflight, nullptr);
   st->slot_x0.resize(cfg->max_inflight, nullptr);
   for (int i = 0; i < cfg->max_inflight; ++i) {
@@ -537,12 +620,14 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
   st->dchain.assign(cfg->n_layers, nullptr);
   st->du.assign(cfg->n_layers, nullptr);
   st->dqkv.assign(cfg->n_layers, nullptr);
+  // (T*h*E is a multiple of 256 bytes whenever j > 1: T % 64 == 0 and h % 8 == 0)
   for (int l = 0; l < cfg->n_layers; ++l) {
-    ALLOC(st->dx1[l], T * h * E, nullptr);
-    if (l > 0) ALLOC(st->dchain[l], T * h * E, nullptr);
-    ALLOC(st->du[l], T * f * E, nullptr);
-    ALLOC(st->dqkv[l], T * 3 * h * E, nullptr);
+    ALLOC(st->dx1[l], j * T * h * E, nullptr);
+    if (l > 0) ALLOC(st->dchain[l], j * T * h * E, nullptr);
+    ALLOC(st->du[l], j * T * f * E, nullptr);
+    ALLOC(st->dqkv[l], j * T * 3 * h * E, nullptr);
   }
+  ALLOC(st->dy_top, j * T * h * E, nullptr);
   if (cfg->recompute) ALLOC(st->y_scratch, T * h * E, nullptr);
   ALLOC(st->delta, (int64_t)cfg->microbatch * cfg->n_heads * cfg->seq * 4, nullptr);
   st->ln_partial.assign(cfg->n_layers, nullptr);
@@ -595,13 +680,17 @@ int stage_forward(stage_t* st, int64_t mb, const void* x_dev, const int32_t* seq
   const int buf = st->sched.buffer_of(st->sched.read_version());
   const int64_t in_bytes = (int64_t)st->T * st->cfg.hidden * st->esize;
   st->cur = st->stream;
+  // full stash: the microbatch takes the activation set that has been free the longest
+  if (!st->cfg.recompute && st->free_sets.empty()) return STAGE_ERR_BAD_STATE;   // (cannot happen: sets = slots + wg_j - 1)
+  const int set = st->cfg.recompute ? st->fwd_scratch_set : st->free_sets.front();
   if (st->two_streams) {
-    // the slot's previous occupant has been read by its backward pass; the version has been written
+    // the slot's previous occupant has been read by its backward pass, the set's by the weight-gradient
+    // launch of its group; the version has been written
     if (st->bwd_pending[slot]) { HIP_TRY(hipStreamWaitEvent(st->stream, st->bwd_done[slot], 0)); st->bwd_pending[slot] = 0; }
+    if (st->set_pending[set]) { HIP_TRY(hipStreamWaitEvent(st->stream, st->set_done[set], 0)); st->set_pending[set] = 0; }
     if (st->ver_pending[buf]) { HIP_TRY(hipStreamWaitEvent(st->stream, st->ver_ready[buf], 0)); st->ver_pending[buf] = false; }
   }
-  // with recomputation and two streams the forward pass has a scratch activation set of its own
-  ActSet& acts = st->cfg.recompute ? st->slot_acts[st->two_streams ? 1 : 0] : st->slot_acts[slot];
+  ActSet& acts = st->sets[set];
   // stash the stage input (with recompute it is the only thing kept)
   char* x_keep = st->cfg.recompute ? st->slot_x0[slot] : acts.layer[0].x;
   HIP_TRY(timed(st, STAGE_K_OTHER, "copy16_kernel", 0.0, 2.0 * in_bytes, [&] { return copy_bytes(x_dev, x_keep, in_bytes, st->stream); }));
@@ -622,6 +711,10 @@ int stage_forward(stage_t* st, int64_t mb, const void* x_dev, const int32_t* seq
     HIP_TRY(run_forward(st, buf, acts, lens, y_dev));
   }
   if (st->two_streams) HIP_TRY(hipEventRecord(st->fwd_done[slot], st->stream));
+  if (!st->cfg.recompute) {
+    st->free_sets.erase(st->free_sets.begin());
+    st->slot_set[slot] = set;
+  }
   int64_t version = 0;
   int b2 = 0;
   return st->sched.forward(mb, &slot, &version, &b2);
@@ -641,18 +734,27 @@ int stage_backward(stage_t* st, int64_t mb, const void* dy_dev, void* dx_dev) {
   const int32_t* lens = st->cfg.mask_mode == STAGE_MASK_PADDING ? st->slot_lens[slot] : nullptr;
   st->cur = st->bstream;
   if (st->two_streams) HIP_TRY(hipStreamWaitEvent(st->bstream, st->fwd_done[slot], 0));
+  const int pos = st->n_pending;
+  if (pos == 0) st->pending_overwrite = first != 0;
+  // the activations of this pass: the set the forward pass filled, or (recompute) set number `pos`, which
+  // the re-run forward fills now
+  const int set = st->cfg.recompute ? pos : st->slot_set[slot];
   if (st->cfg.recompute) {
     // re-run the forward on the version tagged at the forward pass (Section 4.1 with Section 3.1)
-    ActSet& acts = st->slot_acts[0];
+    ActSet& acts = st->sets[set];
     char* saved = acts.layer[0].x;
     acts.layer[0].x = st->slot_x0[slot];
     hipError_t e = run_forward(st, buf, acts, lens, st->y_scratch);
-    if (e == hipSuccess) e = run_backward(st, buf, acts, lens, dy_dev, dx_dev, first != 0);
+    if (e == hipSuccess) e = run_backward(st, buf, set, pos, lens, dy_dev, dx_dev, first != 0);
     acts.layer[0].x = saved;
     HIP_TRY(e);
   } else {
-    HIP_TRY(run_backward(st, buf, st->slot_acts[slot], lens, dy_dev, dx_dev, first != 0));
+    HIP_TRY(run_backward(st, buf, set, pos, lens, dy_dev, dx_dev, first != 0));
+    st->slot_set[slot] = -1;
   }
+  st->pending_set[st->n_pending++] = set;
+  // the group is complete after wg_j passes, and at the batch's last pass whatever its size
+  if (st->n_pending == st->wg_j || st->sched.accumulated() == st->cfg.m) HIP_TRY(flush_wgrad(st));
   if (st->two_streams) {
     HIP_TRY(hipEventRecord(st->bwd_done[slot], st->bstream));
     st->bwd_pending[slot] = 1;
@@ -708,7 +810,8 @@ int stage_set_backward_stream(stage_t* st, void* hip_stream) {
   }
   if (st->fwd_done.empty()) {
     std::vector<hipEvent_t> ev;
-    const int want = 2 * st->cfg.max_inflight + 2;
+    const int n_sets = (int)st->sets.size();
+    const int want = 2 * st->cfg.max_inflight + 2 + n_sets;
     for (int i = 0; i < want; ++i) {
       hipEvent_t e = nullptr;
       if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
@@ -719,16 +822,14 @@ int stage_set_backward_stream(stage_t* st, void* hip_stream) {
     }
     st->fwd_done.assign(ev.begin(), ev.begin() + st->cfg.max_inflight);
     st->bwd_done.assign(ev.begin() + st->cfg.max_inflight, ev.begin() + 2 * st->cfg.max_inflight);
-    st->ver_ready[0] = ev[want - 2];
-    st->ver_ready[1] = ev[want - 1];
+    st->ver_ready[0] = ev[2 * st->cfg.max_inflight];
+    st->ver_ready[1] = ev[2 * st->cfg.max_inflight + 1];
+    st->set_done.assign(ev.begin() + 2 * st->cfg.max_inflight + 2, ev.end());
     st->bwd_pending.assign(st->cfg.max_inflight, 0);
-  }
-  if (st->cfg.recompute && st->slot_acts.size() < 2) {
-    st->slot_acts.resize(2);
-    int rc = alloc_actset(st, &st->slot_acts[1]);
-    if (rc != STAGE_OK) { st->slot_acts.resize(1); return rc; }
+    st->set_pending.assign(n_sets, 0);
   }
   std::fill(st->bwd_pending.begin(), st->bwd_pending.end(), 0);
+  std::fill(st->set_pending.begin(), st->set_pending.end(), 0);
   st->ver_pending[0] = st->ver_pending[1] = false;
   st->bstream = b;
   st->two_streams = true;
@@ -775,6 +876,9 @@ int stage_read_weights(stage_t* st, int which, float* out_host) {
 
 int stage_read_grad_accum(stage_t* st, float* out_host) {
   if (!st || !out_host) return STAGE_ERR_INVALID_ARG;
+  // products still waiting for their group are launched first: the accumulator then holds every pass so far
+  st->cur = st->bstream;
+  HIP_TRY(flush_wgrad(st));
   return read_f32(st, st->G, out_host);
 }
 

@@ -51,6 +51,7 @@ class StageConfig:
     recompute: int = 0          # Section 4.1: stash only the stage input
     flush: int = 0              # Section 3.2: one weight version, pipeline flush per batch
     optimizer: int = 0          # 0 Adam, 1 SGD with momentum (Section 3.1's printed form, beta = beta1)
+    wgrad_group: int = 0        # backward passes per grouped weight-gradient launch (0: the library's choice)
     lr: float = 1e-3
     beta1: float = 0.9
     beta2: float = 0.999

@@ -99,53 +99,108 @@ def run_stage_oracle(cfg: synth.StageConfig, w0: np.ndarray, mbs, inflight: int 
 
 class StageChecker:
     """Element-wise comparison (relative L2) of everything the stage produces against an oracle
-    trace; `worst` collects the largest ratio per quantity for reporting."""
+    trace; `worst` collects the largest ratio per quantity for reporting.  Every comparison is
+    made and recorded before `finish` raises for the ones above their bar, so a failing run still
+    shows the whole picture (`per_update`: quantity -> [(t, ratio)])."""
 
-    def __init__(self, cfg, tr: tb.Trace, tol=None, check_dw=True, check_weights=True, release=False):
+    def __init__(self, cfg, tr: tb.Trace, tol=None, check_dw=True, check_weights=True, release=False,
+                 drift_factor=None):
         self.cfg, self.tr = cfg, tr
         self.tol = TOL[cfg.precision] if tol is None else tol
         self.check_dw, self.check_weights, self.release = check_dw, check_weights, release
+        # From the third batch on a microbatch runs on a version that the GPU and the oracle each produced
+        # themselves, and the two differ (within the bar on weights: in bf16 mode mostly the Adam steps of
+        # near-zero gradient elements, whose sign is rounding noise).  What is then computed from that version
+        # compares two runs that have drifted apart, not one pass's arithmetic.  With drift_factor set, the
+        # bar on those quantities is tol + drift_factor * (relative L2 distance of the two runs' copies of
+        # the version read); the same batch is checked at the plain bar against the oracle evaluated on the
+        # GPU's own version (last_batch_on_the_gpus_own_weights).  None: the plain bar everywhere.
+        self.drift_factor = drift_factor
+        self.version_distance = {0: 0.0}      # version id -> rel L2 between the GPU's and the oracle's copy
         self.worst = {}
+        self.per_update = {}
+        self.failures = []
         self.prev_master = None
         self.updates_seen = 0
+        self.version_buffers = {}
+        self.last_G = None
 
-    def chk(self, name, got, want, bar=None):
-        bar = self.tol if bar is None else bar
+    def chk(self, name, got, want, bar=None, t=None):
+        if bar is None:
+            bar = self.tol
+            if self.drift_factor is not None and t is not None and name in ("Y", "dX", "G", "adam_m", "adam_v"):
+                version = 0 if self.cfg.flush else max(t - 2, 0)       # the version batch t runs on (2BW rule)
+                bar = self.tol + self.drift_factor * self.version_distance.get(version, 0.0)
         r = rel(got, want)
         self.worst[name] = max(self.worst.get(name, 0.0), r)
-        assert r <= bar, f"{name}: rel L2 {r:.3e} > {bar:.1e}"
+        if t is not None:
+            self.per_update.setdefault(name, []).append((t, r))
+        if not r <= bar:
+            self.failures.append(f"{name}{'' if t is None else f' (update {t})'}: rel L2 {r:.3e} > {bar:.1e}")
 
     def outputs(self, gpu):
         for k in sorted(self.tr.Y):
-            self.chk("Y", gpu["Y"][k], self.tr.Y[k])
-            self.chk("dX", gpu["dX"][k], self.tr.dX[k])
+            t = (k - 1) // self.cfg.m + 1
+            self.chk("Y", gpu["Y"][k], self.tr.Y[k], t=t)
+            self.chk("dX", gpu["dX"][k], self.tr.dX[k], t=t)
 
     def snapshot(self, s):
         cfg, tr, chk = self.cfg, self.tr, self.chk
         t = s["t"]
         self.updates_seen += 1
         assert s["updates"] == t and s["newest"] == (0 if cfg.flush else t % 2)
-        chk("G", s["G"], tr.G[t - 1])
-        chk("adam_m", s["m"], tr.opt_state[t - 1]["m"])
+        chk("G", s["G"], tr.G[t - 1], t=t)
+        chk("adam_m", s["m"], tr.opt_state[t - 1]["m"], t=t)
         if cfg.optimizer == synth.OPT_ADAM:
-            chk("adam_v", s["v"], tr.opt_state[t - 1]["v"])
+            chk("adam_v", s["v"], tr.opt_state[t - 1]["v"], t=t)
+        new = None
         if self.check_weights:
             new, old = (s["buf1"], s["buf0"]) if (t % 2 and not cfg.flush) else (s["buf0"], s["buf1"])
-            chk("W_new_buffer", new, tr.W[t])
+            chk("W_new_buffer", new, tr.W[t], t=t)
+            self.version_distance[t] = rel(new, tr.W[t])
             if cfg.flush:
                 assert np.array_equal(old, new)            # one version: both names read the same buffer
             else:
-                chk("W_other_buffer", old, tr.W[t - 1])    # the shadow version is still intact
-            chk("W_master", s["master"], tr.W[t])
+                chk("W_other_buffer", old, tr.W[t - 1], t=t)    # the shadow version is still intact
+            chk("W_master", s["master"], tr.W[t], t=t)
             if self.check_dw:
                 # the raw weights move by only ~lr/0.02 per step; the step itself is the sensitive quantity
                 before = self.prev_master if t >= 2 else tr.W[0]
-                chk("dW", s["master"].astype(np.float64) - before, tr.W[t] - tr.W[t - 1], bar=DW_TOL[cfg.precision])
+                chk("dW", s["master"].astype(np.float64) - before, tr.W[t] - tr.W[t - 1], bar=DW_TOL[cfg.precision], t=t)
         self.prev_master = s["master"]
+        self.version_buffers[t] = new          # version t as the GPU holds it (bf16 mode: exact in fp32)
+        self.version_buffers.pop(t - 3, None)
+        self.last_G = s["G"]
         if self.release:            # the trace's copies of this update are not needed again
             tr.G[t - 1] = None
             tr.opt_state[t - 1] = None
             tr.W[t - 1] = None if t >= 2 else tr.W[t - 1]
+
+    def last_batch_on_the_gpus_own_weights(self, gpu, mbs, n_batches):
+        """The last batch once more, with the oracle evaluated at the delayed version AS THE GPU HOLDS IT
+        (read back after the update that wrote it): Y, dX and the coalesced G of that batch then differ
+        from the GPU's by one pass's arithmetic only, not by how far the two runs' weights have drifted
+        apart over the earlier updates -- and they match only if the GPU really read that version."""
+        cfg = self.cfg
+        assert n_batches >= 3 and not cfg.flush
+        w = self.version_buffers[n_batches - 2]
+        assert w is not None
+        st = ob.Stage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.mask_mode, cfg.ln_eps)
+        w64 = w.astype(np.float64)
+        G = None
+        for k in range((n_batches - 1) * cfg.m + 1, n_batches * cfg.m + 1):
+            y, dx, g = st.vjp(w64, *mbs[k - 1])
+            self.chk("Y_on_gpu_weights", gpu["Y"][k], y, bar=self.tol, t=n_batches)
+            self.chk("dX_on_gpu_weights", gpu["dX"][k], dx, bar=self.tol, t=n_batches)
+            G = g if G is None else G + g
+        self.chk("G_on_gpu_weights", self.last_G, G, bar=self.tol, t=n_batches)
+
+    def report(self):
+        return {k: " ".join(f"t{t}:{r:.2e}" for t, r in sorted(set(v))[:12]) for k, v in self.per_update.items()}
+
+    def finish(self):
+        assert not self.failures, "; ".join(self.failures) + f" | all: {self.report()}"
+        return self.worst
 
 
 def compare_stage(cfg, gpu, tr: tb.Trace, tol=None, check_dw=True, check_weights=True):
@@ -154,4 +209,4 @@ def compare_stage(cfg, gpu, tr: tb.Trace, tol=None, check_dw=True, check_weights
     ck.outputs(gpu)
     for s in gpu["snaps"]:
         ck.snapshot(s)
-    return ck.worst
+    return ck.finish()

@@ -62,8 +62,8 @@ def test_invalid_configs_are_rejected(bad):
 
 
 def test_config_struct_layout_matches_header():
-    # 11 int32 + 5 float, no padding
-    assert ctypes.sizeof(binding.StageConfigC) == 18 * 4
+    # 14 int32 + 5 float, no padding
+    assert ctypes.sizeof(binding.StageConfigC) == 19 * 4
     text = open(os.path.join(ROOT, "include", "stage2bw.h")).read()
     body = text[text.index("typedef struct {"):text.index("} stage_config_t;")]
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)

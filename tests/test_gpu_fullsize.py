@@ -3,7 +3,9 @@
 The fp64 oracle needs 0.3..10 TFLOP per layer and microbatch at these shapes, so the repetition
 is reduced (fewer layers, fewer microbatches per batch, 1..3 updates) while every tensor keeps
 the shape and the launch configuration the benchmark uses; the full BERT-Large-shaped stage
-(6 layers, m = 8) is run for one whole batch.  Bars as everywhere: relative L2 <= 2e-2."""
+(6 layers, m = 8) is run for one whole batch.  Bars as everywhere: relative L2 <= 2e-2; for what the third batch computes on the delayed version W(1) that
+bar applies with the oracle evaluated on the GPU's own copy of W(1), and a wider one (2e-2 + 6 x the distance of
+the two runs' W(1), which itself stays under 2e-2) to the comparison of the two free-running runs."""
 import numpy as np
 import pytest
 
@@ -25,12 +27,19 @@ def run(cfg, n_batches, inflight, seed=0, two_streams=False):
         # the third batch is the first whose gradient is taken on a version other than W(0)
         assert tr.version_used[2 * cfg.m + 1] == 1 and max(tr.version_used.values()) == n_batches - 2
     print("  stage on the GPU", flush=True)
-    ck = StageChecker(cfg, tr, release=True)
+    # at these widths a relative distance e between two copies of the weights moves dX and G by about 5 e
+    # (measured at h = 8192: 5.3e-3 apart after the first Adam step -> 2.8e-2 in dX and G), so the quantities
+    # computed from a version of the runs' own making get the drift bar; the last batch is also held to the
+    # plain 2e-2 with the oracle evaluated on the GPU's own copy of the version
+    ck = StageChecker(cfg, tr, release=True, drift_factor=6.0 if n_batches >= 3 else None)
     gpu = run_stage_gpu(cfg, w0, mbs, inflight, two_streams=two_streams, consume=ck.snapshot)
     ck.outputs(gpu)
     assert ck.updates_seen == n_batches
-    print({k: f"{v:.2e}" for k, v in ck.worst.items()}, flush=True)
-    return ck.worst
+    if n_batches >= 3:
+        print("  last batch again, oracle on the GPU's own delayed version", flush=True)
+        ck.last_batch_on_the_gpus_own_weights(gpu, mbs, n_batches)
+    print(ck.report(), flush=True)
+    return ck.finish()
 
 
 def test_bert_large_shape_three_updates():
@@ -67,3 +76,14 @@ def test_stress_shape_8192():
     delayed version is consumed by the third, and Adam has written each buffer)."""
     cfg = synth.PRESETS["C5"].with_(n_layers=1, m=1, max_inflight=1)
     run(cfg, 3, 1)
+
+
+@pytest.mark.parametrize("workload", ["C2", "C3", "C4", "C5"])
+def test_first_microbatch_at_full_width_against_stored_oracle_samples(workload):
+    """One layer of the workload's shape, microbatch 1 of seed 0: Y, dX and G at 1024 positions each against
+    what the oracle gave for exactly that case (tests/golden/stage_prefix_*.txt, written by the script beside
+    them, which calls only the oracle).  bench.py runs the same check in front of every throughput run."""
+    import bench
+    r = bench.prefix_check(workload, synth.PRESETS[workload], 0)
+    print(workload, r, flush=True)
+    assert r is not None and r["ok"], r

@@ -251,7 +251,7 @@ def test_gemm_rejects_shapes_it_cannot_take():
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
 @pytest.mark.parametrize("rows,h", [(150, 72), (130, 128), (1030, 1024), (300, 2560), (260, 4096), (70, 8192),
-                                    (33, 12288)])
+                                    (33, 12288), (1030, 2048), (777, 8192)])   # (the last two: several trips per workgroup)
 def test_layernorm_forward_backward(dtype, rows, h):
     rng = np.random.default_rng(rows + h)
     x = rnd(rng, (rows, h), dtype, 2.0)
@@ -310,6 +310,43 @@ def test_bias_gradient_column_sums(dtype, rows, n):
     assert L.k2bw_bias_grad(dtype, rows, n, Yd.data_ptr(), out.data_ptr(), 1, ws.data_ptr(), None) == 0
     sync()
     assert rel(to_host(out), 2 * y.astype(np.float64).sum(0)) < 1e-5
+
+
+@pytest.mark.parametrize("M,N,T,idx_a,idx_b", [
+    (520, 264, 128, [3, 0, 2], [0, 1, 2]),                 # 128x128 ring tiles, K tiles of 64
+    (264, 520, 64, [1], [2]),                              # one piece: the plain product
+    (3080, 3072, 96, [5, 1, 4, 0], [3, 2, 1, 0]),          # 256x256 ring tiles (K tiles of 32), ragged M
+    (2048, 2304, 64, [0, 1, 2, 3, 4, 5, 6, 7], [7, 6, 5, 4, 3, 2, 1, 0]),   # the maximum number of pieces
+])
+def test_gemm_weight_gradient_over_several_microbatches(M, N, T, idx_a, idx_b):
+    """sum_s X_s^T dY_s with the pieces in separate buffers at a constant stride, in one product."""
+    n_seg, n_buf = len(idx_a), 8
+    rng = np.random.default_rng(M + N + T + n_seg)
+    xs = rnd(rng, (n_buf, T, M), BF16)
+    dys = rnd(rng, (n_buf, T, N), BF16, 0.1)
+    g0 = rng.standard_normal((M, N)).astype(np.float32)
+    want = sum(xs[a].astype(np.float64).T @ dys[b].astype(np.float64) for a, b in zip(idx_a, idx_b))
+    X, DY = dev(xs, BF16), dev(dys, BF16)
+    assert (T * M * 2) % 256 == 0 and (T * N * 2) % 256 == 0
+    ia, ib = np.array(idx_a, dtype=np.uint8), np.array(idx_b, dtype=np.uint8)
+    L = B.lib()
+    for acc in (0, 1):
+        G = torch.from_numpy(g0.copy()).cuda()
+        assert L.k2bw_gemm_wgrad_segmented(M, N, T, n_seg, X.data_ptr(), M, T * M * 2, ia.ctypes.data, DY.data_ptr(), N,
+                                           T * N * 2, ib.ctypes.data, G.data_ptr(), N, acc, None) == 0
+        sync()
+        assert rel(to_host(G), want + (g0 if acc else 0)) < 2e-6
+    # refused: pieces that are not whole K tiles, an index beyond 15, a stride off the 256-byte grid
+    G = torch.zeros((M, N), device="cuda")
+    bad = np.array([16] * n_seg, dtype=np.uint8)
+    if n_seg > 1:
+        assert L.k2bw_gemm_wgrad_segmented(M, N, T, n_seg, X.data_ptr(), M, T * M * 2, bad.ctypes.data, DY.data_ptr(), N,
+                                           T * N * 2, ib.ctypes.data, G.data_ptr(), N, 0, None) == B.ERR_INVALID_ARG
+        assert L.k2bw_gemm_wgrad_segmented(M, N, T, n_seg, X.data_ptr(), M, T * M * 2 + 16, ia.ctypes.data, DY.data_ptr(), N,
+                                           T * N * 2, ib.ctypes.data, G.data_ptr(), N, 0, None) == B.ERR_INVALID_ARG
+        assert L.k2bw_gemm_wgrad_segmented(M, N, 40, n_seg, X.data_ptr(), M, T * M * 2, ia.ctypes.data, DY.data_ptr(), N,
+                                           T * N * 2, ib.ctypes.data, G.data_ptr(), N, 0, None) == B.ERR_INVALID_ARG
+    sync()
 
 
 @pytest.mark.parametrize("dtype,dh", [(F32, 16), (BF16, 64)])

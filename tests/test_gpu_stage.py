@@ -157,7 +157,7 @@ def test_schedule_errors_leave_the_stage_untouched():
 
 def test_memory_report_matches_the_papers_formula():
     """2 weight versions + in-flight activation stashes (Section 3.1, Memory Footprint)."""
-    cfg = synth.PRESETS["C1"].with_(precision=synth.PREC_BF16)
+    cfg = synth.PRESETS["C1"].with_(precision=synth.PREC_BF16, wgrad_group=1)
     st = B.Stage(cfg, synth.StageInputs(cfg, 0).weights())
     P = st.n_params
     assert st.query(B.Q_BYTES_WEIGHTS) >= 2 * 2 * P + 4 * P
@@ -166,6 +166,66 @@ def test_memory_report_matches_the_papers_formula():
     per_mb = cfg.n_layers * ((8 * h + 2 * f) * T * 2)
     stash = st.query(B.Q_BYTES_STASH)
     assert cfg.max_inflight * per_mb <= stash < cfg.max_inflight * per_mb * 1.2
+    st.close()
+    # weight gradients of j backward passes in one launch keep j - 1 more activation sets alive
+    st4 = B.Stage(cfg.with_(wgrad_group=4), synth.StageInputs(cfg, 0).weights())
+    stash4 = st4.query(B.Q_BYTES_STASH)
+    assert (cfg.max_inflight + 3) * per_mb <= stash4 < (cfg.max_inflight + 3) * per_mb * 1.2
+    st4.close()
+
+
+GROUPED = synth.StageConfig(n_layers=2, hidden=128, n_heads=4, ffn=256, seq=64, microbatch=2, m=6, max_inflight=3,
+                            mask_mode=synth.MASK_CAUSAL, precision=synth.PREC_BF16)
+
+
+def test_weight_gradients_of_several_backward_passes_in_one_launch():
+    """Section 3.1's coalesced sum with the products of j consecutive backward passes of a batch taken by one
+    launch (reduction range j*T; m = 6, so j = 4 leaves a group of 2 at every batch end and j = 8 is cut to 6):
+    every j meets the oracle; outputs and input gradients do not depend on j at all, the accumulator only
+    through the order of fp32 additions; recomputation and a second stream change nothing at equal j."""
+    cfg = GROUPED
+    gen = synth.StageInputs(cfg, 7)
+    w0 = gen.weights()
+    mbs = gen.microbatches(3 * cfg.m)
+    tr = run_stage_oracle(cfg, w0, mbs)
+    runs = {}
+    for j in (1, 2, 0, 8):          # 0: the library's choice (4)
+        c = cfg.with_(wgrad_group=j)
+        runs[j] = run_stage_gpu(c, w0, mbs, 3)
+        worst = compare_stage(c, runs[j], tr)
+        print(f"wgrad_group={j}:", {k: f"{v:.2e}" for k, v in worst.items()})
+    for j in (2, 0, 8):
+        for k in runs[1]["Y"]:
+            assert np.array_equal(runs[j]["Y"][k], runs[1]["Y"][k]) and np.array_equal(runs[j]["dX"][k], runs[1]["dX"][k])
+        assert rel(runs[j]["snaps"][0]["G"], runs[1]["snaps"][0]["G"]) < 1e-6     # same products, other order of sums
+        assert not np.array_equal(runs[j]["snaps"][0]["G"], runs[1]["snaps"][0]["G"])   # (the grouping really happened)
+    for variant in (dict(recompute=1), dict(two_streams=True), dict(recompute=1, two_streams=True)):
+        out = run_stage_gpu(cfg.with_(recompute=variant.get("recompute", 0)), w0, mbs, 3,
+                            two_streams=variant.get("two_streams", False))
+        for k in runs[0]["Y"]:
+            assert np.array_equal(out["Y"][k], runs[0]["Y"][k]) and np.array_equal(out["dX"][k], runs[0]["dX"][k])
+        for a, b in zip(out["snaps"], runs[0]["snaps"]):
+            assert np.array_equal(a["G"], b["G"]) and np.array_equal(a["master"], b["master"])
+
+
+def test_accumulator_read_in_the_middle_of_a_group():
+    """stage_read_grad_accum launches the products still waiting for their group, so the accumulator read
+    after any backward pass is the sum over all passes so far; the batch then ends with the same sum."""
+    cfg = GROUPED.with_(m=4, max_inflight=2)
+    gen = synth.StageInputs(cfg, 8)
+    w0 = gen.weights()
+    mbs = gen.microbatches(cfg.m)
+    st_o = __import__("oracle.block", fromlist=["Stage"]).Stage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.mask_mode,
+                                                               cfg.ln_eps)
+    g = [st_o.vjp(w0.astype(np.float64), *mb)[2] for mb in mbs]
+    st = B.Stage(cfg, w0)
+    shape = (cfg.microbatch, cfg.seq, cfg.hidden)
+    Y, DX = torch.empty(shape, device="cuda", dtype=torch.bfloat16), torch.empty(shape, device="cuda", dtype=torch.bfloat16)
+    for k in range(1, cfg.m + 1):
+        st.forward(k, to_dev(mbs[k - 1][0], cfg.precision), None, Y)
+        st.backward(k, to_dev(mbs[k - 1][1], cfg.precision), DX)
+        if k in (1, 3, 4):
+            assert rel(st.read_grad_accum(), sum(g[:k])) < 2e-2, k
     st.close()
 
 
