@@ -202,6 +202,42 @@ def pipeline_bench(args, cfg, w0):
         "frac_of_bf16_mfma_peak": flops_step * K / elapsed / 1e12 / PEAK_BF16_TFLOPS}))
 
 
+def probe_gemm(spec):
+    """`--probe-gemm f32,4096,4096,4096` (or bf16,...): one GEMM kernel alone, the three forms the stage issues,
+    warm operands, HIP-event average over 20 launches; prints one JSON line."""
+    import torch
+    from paper_2006_09503_amd import binding as B
+    name, M, N, K = spec.split(",")
+    M, N, K = int(M), int(N), int(K)
+    dt, code, peak = (torch.float32, 0, 157.3) if name == "f32" else (torch.bfloat16, 1, PEAK_BF16_TFLOPS)
+    L = B.lib()
+    g = torch.Generator(device="cuda").manual_seed(0)
+    rnd = lambda *shape: torch.randn(shape, generator=g, device="cuda", dtype=torch.float32).to(dt)
+    out = {}
+    forms = {"forward (A[M,K] B[K,N])": (0, 0, 0, rnd(M, K), K, rnd(K, N), N, torch.empty(M, N, device="cuda", dtype=dt)),
+             "data gradient (A[M,K] B[N,K]^T)": (0, 1, 0, rnd(M, K), K, rnd(N, K), K, torch.empty(M, N, device="cuda", dtype=dt)),
+             "weight gradient (A[K,M]^T B[K,N], fp32 +=)": (1, 0, 3, rnd(K, M), M, rnd(K, N), N,
+                                                           torch.zeros(M, N, device="cuda", dtype=torch.float32))}
+    for form, (ta, tb, epi, A, lda, Bm, ldb, Cm) in forms.items():
+        def launch():
+            rc = L.k2bw_gemm(code, ta, tb, epi, M, N, K, A.data_ptr(), lda, Bm.data_ptr(), ldb, Cm.data_ptr(), N, None, None,
+                             None, 1 if epi == 3 else 0, None)
+            assert rc == 0, rc
+        for _ in range(3):
+            launch()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(20):
+            launch()
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) / 20 * 1e3
+        tf = 2.0 * M * N * K / (us * 1e-6) / 1e12
+        out[form] = {"us": us, "tflops": tf, "frac_of_peak": tf / peak}
+    print(json.dumps({"probe": f"k2bw_gemm {name} M={M} N={N} K={K}", "peak_tflops": peak, "forms": out}))
+
+
 def event_pair_gap_us(stream, n=200):
     """Median time between two HIP events recorded back to back on `stream` with nothing in between."""
     import torch
@@ -235,6 +271,8 @@ def main():
                     "products one launch covers (reduction length j*T; default: the library's choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefix-check", action="store_true")
+    ap.add_argument("--probe-gemm", default=None, help="dtype,M,N,K: time one GEMM kernel alone (e.g. f32,4096,4096,4096) "
+                    "instead of the stage; an extra measurement, not the headline")
     ap.add_argument("--no-kernel-timing", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -249,6 +287,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
+    if args.probe_gemm:
+        probe_gemm(args.probe_gemm)
+        return
     cfg = synth.PRESETS[args.workload]
     if args.flush:
         cfg = cfg.with_(flush=1)
