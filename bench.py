@@ -37,17 +37,28 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # for the library's plain copy kernel of known size; see profiles/ for the runs.  A workload, flag
 # set or kernel that was not profiled reports null.
 TRAFFIC_BYTES_PER_LAUNCH = {
+    "C5": {
+        # grouped weight-gradient GEMM: the 8 products of the stage's 2 layers over 4 microbatches' tokens each
+        # (reduction length 8192): L2-miss read traffic 8.03e10 (the operand panels of products this size pass
+        # through the 4 MB L2 of every XCD many times; most of it is served by the memory-side cache) +
+        # 6.44e9 written.  Algorithmic minimum 1.72e10: operands once + fp32 accumulator read-modify-write.
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 8.6736e+10,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 2>": 1.9306e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.9083e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 0>": 1.4378e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 1.2520e+09,
+    },
     "C2": {
-        # grouped weight-gradient GEMM (the 24 products of the stage's 6 layers in one launch): FETCH_SIZE
-        # x 1.995 (copy-kernel factor) + WRITE_SIZE x 1.000; algorithmic minimum 1.409e9 (operands once +
-        # fp32 accumulator read-modify-write)
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 1.5451e+09,
+        # grouped weight-gradient GEMM (the 24 products of the stage's 6 layers over 4 microbatches' tokens each,
+        # reduction length 16384): FETCH_SIZE x 1.995 (copy-kernel factor) + WRITE_SIZE x 1.000; algorithmic minimum
+        # 3.825e9 (operands once + fp32 accumulator read-modify-write)
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 4.3727e+09,
         # the other GEMM instances (averages over the shapes each serves)
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 2>": 1.2820e+08,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.2610e+08,
-        "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, false, 0>": 8.6462e+07,
-        "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, true, 0>": 8.0600e+07,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 7.3529e+07,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 2>": 1.2821e+08,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.2612e+08,
+        "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, false, 0>": 8.6468e+07,
+        "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, true, 0>": 8.0625e+07,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 7.3551e+07,
     },
 }
 

@@ -275,7 +275,7 @@ hipError_t run_ln_bwd(stage2bw* st, const void* dy, const void* x, const float* 
                       const void* gain, const void* dres, void* dx, float* partial, int* parts) {
   const int h = st->cfg.hidden;
   const double bytes = 4.0 * st->T * h * st->esize + 8.0 * st->T;
-  return timed(st, STAGE_K_LN_BWD, "ln_bwd_kernel", 0.0, bytes, [&] {
+  return timed(st, STAGE_K_LN_BWD, h >= 2048 ? "ln_bwd_wide_kernel" : "ln_bwd_kernel", 0.0, bytes, [&] {
     return layernorm_bwd(dy, x, mean, rstd, gain, dres, dx, partial, parts, st->T, h, st->dtype, st->cur);
   });
 }
