@@ -256,10 +256,7 @@ __device__ __forceinline__ void unpack4(uint2 w, float (&v)[4]) {
 // the workgroups running at the same time on an XCD (consecutive ids after the XCD remap) cover
 // a kGroupM x (32 / kGroupM) block of tiles and share A row panels and B column panels in that
 // XCD's L2 instead of streaming a whole row of B panels.
-#ifndef K2BW_GROUP_M
-#define K2BW_GROUP_M 8
-#endif
-constexpr int kGroupM = K2BW_GROUP_M;
+constexpr int kGroupM = 8;
 __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int& bm, int& bn) {
   const int per_group = kGroupM * tiles_n;
   const int group = t / per_group;
@@ -871,8 +868,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
   // Lines of the operand a later launch will read (GemmDesc::prefetch): every wave of the launch
   // touches 64 of them, 128 bytes apart, with one 4-byte load in front of its own first loads.  The
   // load is older than every tile load, so the waits below (which count the newest operations that
-  // may still be outstanding) stay sufficient whenever it returns; its destination register is kept
-  // out of other use until the kernel ends (the compiler does not know that the value arrives late).
+  // may still be outstanding) stay sufficient whenever it returns.  The compiler does not know that the
+  // value arrives late: its destination register is kept out of other use up to the first wait below,
+  // after which the load has returned (vector-memory loads return in order) and the register is free.
   uint32_t touched = 0;
   if (p.prefetch != nullptr) {
     const uint32_t line = ((uint32_t)blockIdx.x * NW + (uint32_t)wave) * 64u + (uint32_t)lane;
@@ -886,6 +884,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
     walk.advance();
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * NV));
+  asm volatile("" : "+v"(touched));   // the touch has landed: last use of its register
   __syncthreads();
   bf16x8 af[2][MI], bfr[2][NI];
 #pragma unroll
@@ -914,7 +913,6 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
-    asm volatile("" : : "v"(touched));
     return;
   }
   // One step on the tile in stage st = kt & (NS - 1).  The loop below runs NS steps per trip with st a
@@ -967,13 +965,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_ring_ker
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   __syncthreads();
   epilogue<MI, NI, WM, WN, EPI>(acc, gp.p[g], m0, n0, wm, wn, lane, smem, wave, 0, MI);
-  asm volatile("" : : "v"(touched));
 }
 
-#ifndef K2BW_BALANCE_TAIL
-#define K2BW_BALANCE_TAIL 1
-#endif
-int g_balance_tail = K2BW_BALANCE_TAIL;   // build-time tuning aid: 0 switches the half-row tail of the ring launches off
 
 int compute_units() {
   static int n = 0;
@@ -1030,7 +1023,7 @@ hipError_t launch_ring(GroupParams gp, hipStream_t s) {
     full += (int64_t)gp.p[g].tiles_m * gp.p[g].tiles_n;
   }
   int first_half = gp.count;   // problems [first_half, count) get tiles of BM/2 rows
-  if (BM == 2 * WM && g_balance_tail) {
+  if (BM == 2 * WM) {
     const int n_cu = compute_units();
     int64_t need = full % n_cu;
     if (full > n_cu && need > 0 && need <= n_cu / 2) {

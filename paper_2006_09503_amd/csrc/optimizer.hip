@@ -1,5 +1,5 @@
 // Fused coalesce + Adam update writing the other weight buffer, and dtype conversions.
-// HBM-bound: 16-byte accesses, grid-stride, every byte touched once.
+// HBM-bound: 16-byte accesses, one pass front to back (no grid-stride loop), every byte touched once.
 //   fp32 mode: read W(t), m, v, G (16 B/param); write W(t+1), m, v (12 B/param).
 //   bf16 mode: read master, m, v, G (16 B); write master, m, v, bf16 W(t+1) (14 B).
 #include "kernels.hpp"
