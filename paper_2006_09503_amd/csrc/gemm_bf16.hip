@@ -68,7 +68,10 @@ struct GroupParams {
   int tile_start[kMaxProblems + 1];
   int count;
   int n_tiles;   // = tile_start[count] = the launch's workgroups
-  int seg1, seg2;   // multiples of 8: workgroups [0, seg1) and [seg1, seg1 + seg2) are each dealt to the XCDs in runs
+  // workgroup id -> tile number (see select_problem): [0, seg0) in blocks of 32 tiles dealt to the XCDs in turn
+  // (seg0 a multiple of 256), then [seg0, seg0 + seg1) and the seg2 ids behind them each dealt to the XCDs in
+  // runs (multiples of 8), the rest as they come
+  int seg0, seg1, seg2;
 };
 
 // Chunk swizzle.  Three LDS access patterns have to avoid bank conflicts at once: fragment
@@ -268,8 +271,13 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
 }
 
 // The problem and the tile of a workgroup.  Consecutive workgroup ids land on different XCDs
-// (round-robin over 8), so each XCD gets a contiguous run of tiles: they share A rows / B columns
-// in that XCD's L2.  Kernel arguments live in device memory and every dependent round of loads
+// (round-robin over 8).  An XCD's 32 CUs get 32 consecutive tiles at a time (8 tile rows x 4 columns in
+// the order of tile_coords: they share A rows / B columns in that XCD's L2), and the eight XCDs work on
+// eight consecutive such blocks: at any moment the whole chip is inside the same few operand panels, which
+// the memory-side cache then serves to all XCDs from one HBM read (with each XCD on a contiguous eighth of
+// the launch instead, eight distant regions of the operands compete for that cache at once: measured, the
+// multi-round weight-gradient launches are 3..5 % slower that way).  What does not fill whole blocks is dealt
+// to the XCDs in contiguous runs.  Kernel arguments live in device memory and every dependent round of loads
 // from them costs the better part of a microsecond before the first tile can be requested: with
 // one problem in the launch (all but the grouped weight-gradient launches) everything here comes
 // from one round -- problem 0 is read unconditionally and replaced only in a grouped launch.
@@ -280,10 +288,13 @@ __device__ __forceinline__ BfParams select_problem(const GroupParams& gp, int& w
   BfParams p = gp.p[0];
   const int count = gp.count;
   // (mask arithmetic, not branches: all the loads above stay in one round)
-  const int b = blockIdx.x, seg1 = gp.seg1, seg2 = gp.seg2;
-  const int in1 = -(int)(b < seg1), in2 = -(int)(b >= seg1 && b < seg1 + seg2);
-  const int b2 = b - seg1;
-  wg = (((b % 8) * (seg1 / 8) + b / 8) & in1) | ((seg1 + (b2 % 8) * (seg2 / 8) + b2 / 8) & in2) | (b & ~(in1 | in2));
+  const int b = blockIdx.x, seg0 = gp.seg0, seg1 = gp.seg1, seg2 = gp.seg2;
+  const int in0 = -(int)(b < seg0), in1 = -(int)(b >= seg0 && b < seg0 + seg1);
+  const int in2 = -(int)(b >= seg0 + seg1 && b < seg0 + seg1 + seg2);
+  const int i0 = b >> 3, b1 = b - seg0, b2 = b - seg0 - seg1;
+  const int w0 = ((((i0 >> 5) << 3) + (b & 7)) << 5) + (i0 & 31);
+  wg = (w0 & in0) | ((seg0 + (b1 % 8) * (seg1 / 8) + b1 / 8) & in1) | ((seg0 + seg1 + (b2 % 8) * (seg2 / 8) + b2 / 8) & in2) |
+       (b & ~(in0 | in1 | in2));
   g = 0;
   if (count > 1) {
 #pragma unroll
@@ -1058,8 +1069,10 @@ hipError_t launch_ring(GroupParams gp, hipStream_t s) {
   }
   for (int g = gp.count; g <= kMaxProblems; ++g) gp.tile_start[g] = total;
   gp.n_tiles = total;
-  gp.seg1 = (first_half < gp.count ? gp.tile_start[first_half] : total) / 8 * 8;
-  gp.seg2 = (total - gp.seg1) / 8 * 8;
+  const int full_tiles = first_half < gp.count ? gp.tile_start[first_half] : total;
+  gp.seg0 = full_tiles / 256 * 256;
+  gp.seg1 = (full_tiles - gp.seg0) / 8 * 8;
+  gp.seg2 = (total - gp.seg0 - gp.seg1) / 8 * 8;
   hipLaunchKernelGGL(kern, dim3(total), dim3(NT), lds, s, gp);
   return hipGetLastError();
 }
@@ -1086,6 +1099,7 @@ hipError_t launch(GroupParams gp, hipStream_t s) {
   }
   for (int g = gp.count; g <= kMaxProblems; ++g) gp.tile_start[g] = total;
   gp.n_tiles = total;
+  gp.seg0 = 0;
   gp.seg1 = total / 8 * 8;
   gp.seg2 = 0;
   hipLaunchKernelGGL(kern, dim3(total), dim3(NT), lds, s, gp);

@@ -41,8 +41,9 @@ def sync():
 # ----------------------------------------------------------------------------- GEMM
 
 GEMM_SHAPES = [
-    # (M, N, K)   small ragged; several 128-tiles; 256x256-tile path (>= 144 big tiles), ragged
-    (70, 40, 24), (300, 264, 200), (512, 384, 256), (4000, 3080, 136),
+    # (M, N, K)   small ragged; several 128-tiles; 256x256-tile path (>= 144 big tiles), ragged; more than two
+    # rounds of 256 tiles (the tile -> XCD mapping in whole blocks, then in runs, then the halved tail)
+    (70, 40, 24), (300, 264, 200), (512, 384, 256), (4000, 3080, 136), (4100, 8200, 64),
 ]
 
 
