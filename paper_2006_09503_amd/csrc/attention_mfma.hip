@@ -226,7 +226,12 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_fwd_mfma_ke
   extern __shared__ uint4 smem[];   // stage st: K tile at st * 2 * kTileU4, V tile behind it
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l32 = lane & 31, hf = lane >> 5;
-  const int n = blockIdx.z, head = blockIdx.y, i0 = blockIdx.x * kBlockRows;
+  // grid = (heads, sequences, row blocks): the row block varies slowest, so all heads' copies of a block are
+  // dispatched together, and under a causal mask the blocks with the most keys to visit (the last queries) go
+  // first: the workgroups that take longest start earliest and the launch does not end on one of them
+  const int n = blockIdx.y, head = blockIdx.x;
+  const int blk = mask_mode == 1 ? (int)(gridDim.z - 1 - blockIdx.z) : (int)blockIdx.z;
+  const int i0 = blk * kBlockRows;
   const int h = a * DH;
   const int64_t ld = 3 * (int64_t)h;
   const bf16_t* base = qkv + (int64_t)n * s * ld + head * DH;
@@ -344,7 +349,12 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dq_mfma_ker
   extern __shared__ uint4 smem[];   // stage st: K tile at st * 2 * kTileU4, V tile behind it
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l32 = lane & 31, hf = lane >> 5;
-  const int n = blockIdx.z, head = blockIdx.y, i0 = blockIdx.x * kBlockRows;
+  // grid = (heads, sequences, row blocks): the row block varies slowest, so all heads' copies of a block are
+  // dispatched together, and under a causal mask the blocks with the most keys to visit (the last queries) go
+  // first: the workgroups that take longest start earliest and the launch does not end on one of them
+  const int n = blockIdx.y, head = blockIdx.x;
+  const int blk = mask_mode == 1 ? (int)(gridDim.z - 1 - blockIdx.z) : (int)blockIdx.z;
+  const int i0 = blk * kBlockRows;
   const int h = a * DH;
   const int64_t ld = 3 * (int64_t)h;
   const bf16_t* base = qkv + (int64_t)n * s * ld + head * DH;
@@ -434,7 +444,7 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dq_mfma_ker
   }
   if (colsum) {   // rows past the end of the sequence hold zeros
     __syncthreads();   // every wave is done with the K / V tiles
-    float* row = colsum + ((int64_t)n * gridDim.x + blockIdx.x) * ld + head * DH;
+    float* row = colsum + ((int64_t)n * gridDim.z + blk) * ld + head * DH;
     block_column_sums<DH>(dq, scale, reinterpret_cast<float*>(smem), row, tid, lane, wave);
   }
   if (!row_ok) return;
@@ -463,7 +473,10 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dkv_mfma_ke
   constexpr int kStageU4 = 2 * C::kTileU4 + 2 * kTile / 4;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l32 = lane & 31, hf = lane >> 5;
-  const int n = blockIdx.z, head = blockIdx.y, j0 = blockIdx.x * kBlockRows;
+  // grid = (heads, sequences, key blocks), key block slowest: under a causal mask the first keys are seen by
+  // the most queries, and those workgroups are dispatched first (see the forward kernel)
+  const int n = blockIdx.y, head = blockIdx.x, blk = blockIdx.z;
+  const int j0 = blk * kBlockRows;
   const int h = a * DH;
   const int64_t ld = 3 * (int64_t)h;
   const bf16_t* base = qkv + (int64_t)n * s * ld + head * DH;
@@ -554,7 +567,7 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dkv_mfma_ke
     }
   }
   if (colsum) {   // masked and non-existent keys hold zeros
-    float* row = colsum + ((int64_t)n * gridDim.x + blockIdx.x) * ld + head * DH;
+    float* row = colsum + ((int64_t)n * gridDim.z + blk) * ld + head * DH;
     float* red = reinterpret_cast<float*>(smem);
     __syncthreads();
     block_column_sums<DH>(dk, scale, red, row + h, tid, lane, wave);
@@ -593,7 +606,7 @@ hipError_t fwd_launch(const AttnDesc& d, const void* qkv, void* o, float* lse, h
   static bool done = false;
   hipError_t e = set_lds(attn_fwd_mfma_kernel<DH>, lds, &done);
   if (e != hipSuccess) return e;
-  dim3 grid(ceil_div(d.s, kBlockRows), d.a, d.b);
+  dim3 grid(d.a, d.b, ceil_div(d.s, kBlockRows));
   hipLaunchKernelGGL(attn_fwd_mfma_kernel<DH>, grid, dim3(kThreads), lds, st, static_cast<const bf16_t*>(qkv),
                      static_cast<bf16_t*>(o), lse, d.s, d.a, d.mask_mode, d.seqlens);
   return hipGetLastError();
@@ -610,7 +623,7 @@ hipError_t bwd_launch(const AttnDesc& d, const void* qkv, const void* o, const f
   if (e != hipSuccess) return e;
   e = set_lds(attn_dkv_mfma_kernel<DH>, lds_dkv, &done_dkv);
   if (e != hipSuccess) return e;
-  dim3 grid(ceil_div(d.s, kBlockRows), d.a, d.b);
+  dim3 grid(d.a, d.b, ceil_div(d.s, kBlockRows));
   hipLaunchKernelGGL(attn_dq_mfma_kernel<DH>, grid, dim3(kThreads), lds_dq, st, static_cast<const bf16_t*>(qkv),
                      static_cast<const bf16_t*>(o), static_cast<const bf16_t*>(d_o), lse, delta,
                      static_cast<bf16_t*>(dqkv), d.s, d.a, d.mask_mode, d.seqlens, d.colsum_partial);
