@@ -39,14 +39,24 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 TRAFFIC_BYTES_PER_LAUNCH = {
     "C5": {
         # grouped weight-gradient GEMM: the 8 products of the stage's 2 layers over 4 microbatches' tokens each
-        # (reduction length 8192): L2-miss read traffic 8.03e10 (the operand panels of products this size pass
-        # through the 4 MB L2 of every XCD many times; most of it is served by the memory-side cache) +
-        # 6.44e9 written.  Algorithmic minimum 1.72e10: operands once + fp32 accumulator read-modify-write.
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 8.6736e+10,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 2>": 1.9306e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.9083e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 0>": 1.4378e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 1.2520e+09,
+        # (reduction length 8192): L2-miss read traffic 8.75e10 (the operand panels of products this size pass
+        # through the 4 MB L2 of every XCD many times; the counter sees what misses L2, whether HBM or the
+        # memory-side cache serves it) + 6.44e9 written.  Algorithmic minimum 1.72e10: operands once + fp32
+        # accumulator read-modify-write.
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 9.3915e+10,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 2>": 1.9242e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.9175e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 0>": 1.4301e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 1.2723e+09,
+    },
+    "C4": {
+        # (activation recomputation: the forward GEMMs run twice per microbatch; 4 layers x 4 products over 4 passes per
+        # weight-gradient launch, reduction length 16384)
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 7.5823e+10,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 2>": 1.0822e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.0775e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 6.7883e+08,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, true, 0>": 6.4694e+08,
     },
     "C2": {
         # grouped weight-gradient GEMM (the 24 products of the stage's 6 layers over 4 microbatches' tokens each,

@@ -393,8 +393,8 @@ def test_momentum_sgd_kernel():
 
 # ----------------------------------------------------------------------------- attention
 
-ATTN_SHAPES = [  # b, s, a, dh
-    (2, 50, 3, 24), (1, 200, 2, 64), (2, 130, 2, 80), (1, 257, 2, 128), (3, 64, 4, 32),
+ATTN_SHAPES = [  # b, s, a, dh   (the last: three 256-row blocks per head, several heads and sequences)
+    (2, 50, 3, 24), (1, 200, 2, 64), (2, 130, 2, 80), (1, 257, 2, 128), (3, 64, 4, 32), (2, 700, 3, 64),
 ]
 
 

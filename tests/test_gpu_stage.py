@@ -208,6 +208,19 @@ def test_weight_gradients_of_several_backward_passes_in_one_launch():
             assert np.array_equal(a["G"], b["G"]) and np.array_equal(a["master"], b["master"])
 
 
+def test_grouped_weight_gradients_under_the_flush_schedule():
+    """Section 3.2's schedule drains the pipeline at every batch end; the groups of weight-gradient products end
+    there too (m = 6, groups of 4 + 2), and the vanilla update sees the whole batch's sum."""
+    cfg = GROUPED.with_(flush=1)
+    gen = synth.StageInputs(cfg, 9)
+    w0 = gen.weights()
+    mbs = gen.microbatches(3 * cfg.m)
+    tr = run_stage_oracle(cfg, w0, mbs)
+    worst = compare_stage(cfg, run_stage_gpu(cfg, w0, mbs, 3), tr)
+    print("flush, grouped:", {k: f"{v:.2e}" for k, v in worst.items()})
+    assert [tr.version_used[k] for k in (1, 6, 7, 13)] == [0, 0, 1, 2]
+
+
 def test_accumulator_read_in_the_middle_of_a_group():
     """stage_read_grad_accum launches the products still waiting for their group, so the accumulator read
     after any backward pass is the sum over all passes so far; the batch then ends with the same sum."""
