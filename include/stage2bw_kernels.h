@@ -33,7 +33,7 @@ extern "C" {
  *          2: C = acc * GELU'(aux[m,n])                     (data gradient through GELU)
  *          3: C fp32: C = (accumulate ? C : 0) + acc        (weight gradient, coalesced in place)
  * bf16 supports the pairs the stage issues: (trans_a,trans_b,epilogue) in
- * {(0,0,0),(0,0,1),(0,1,0),(0,1,2),(1,0,3)}; fp32 supports all.  bf16: A and B each smaller than
+ * {(0,0,0),(0,0,1),(0,0,2),(0,1,0),(0,1,2),(1,0,3)}; fp32 supports all.  bf16: A and B each smaller than
  * 2 GiB (rows * ld * 2 bytes), INVALID_ARG otherwise.
  */
 int k2bw_gemm(int dtype, int trans_a, int trans_b, int epilogue, int M, int N, int K, const void* A,

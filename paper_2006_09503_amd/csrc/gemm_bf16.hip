@@ -1231,6 +1231,7 @@ hipError_t gemm_bf16_grouped(const GemmDesc* d, int count, hipStream_t stream) {
   if (!f.trans_a && !f.trans_b) {
     if (f.epilogue == kEpiStore) return pick_tile<false, false, kEpiStore>(gp, stream);
     if (f.epilogue == kEpiGelu) return pick_tile<false, false, kEpiGelu>(gp, stream);
+    if (f.epilogue == kEpiGeluGrad) return pick_tile<false, false, kEpiGeluGrad>(gp, stream);
   } else if (!f.trans_a && f.trans_b) {
     if (f.epilogue == kEpiStore) return pick_tile<false, true, kEpiStore>(gp, stream);
     if (f.epilogue == kEpiGeluGrad) return pick_tile<false, true, kEpiGeluGrad>(gp, stream);

@@ -143,5 +143,10 @@ hipError_t squared_error_grad(const void* y, const void* target, void* dy, float
 hipError_t convert_f32_to_bf16(const float* in, bf16_t* out, int64_t n, hipStream_t stream);
 hipError_t convert_bf16_to_f32(const bf16_t* in, float* out, int64_t n, hipStream_t stream);
 hipError_t copy_bytes(const void* in, void* out, int64_t bytes, hipStream_t stream);
+// dst[c][r] = src[r][c] for bf16 matrices src [rows][cols] (rows, cols multiples of 8), any number of them;
+// kTransposeMaxItems per launch.
+struct TransposeItem { const void* src; void* dst; int rows, cols; };
+constexpr int kTransposeMaxItems = 32;
+hipError_t transpose_bf16_grouped(const TransposeItem* items, int count, hipStream_t stream);
 
 }  // namespace k2bw

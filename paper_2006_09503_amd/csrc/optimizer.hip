@@ -125,6 +125,54 @@ __global__ __launch_bounds__(256) void squared_error_grad_kernel(const T* __rest
   }
 }
 
+// Transposes of up to kTransposeMaxItems bf16 matrices in one launch: dst[c][r] = src[r][c] for src [rows][cols]
+// (both multiples of 8).  A workgroup moves one 64 x 64 tile through LDS: 16-byte loads along the source rows,
+// 16-byte stores along the destination rows.
+struct TransposeGroup {
+  const bf16_t* src[kTransposeMaxItems];
+  bf16_t* dst[kTransposeMaxItems];
+  int rows[kTransposeMaxItems], cols[kTransposeMaxItems], tiles_c[kTransposeMaxItems], tile0[kTransposeMaxItems];
+  int count;
+};
+__global__ __launch_bounds__(256) void transpose_bf16_grouped_kernel(TransposeGroup g) {
+  __shared__ bf16_t tile[64][64 + 2];
+  int q = 0;
+  for (int i = 1; i < g.count; ++i)
+    if ((int)blockIdx.x >= g.tile0[i]) q = i;
+  const bf16_t* __restrict__ src = g.src[q];
+  bf16_t* __restrict__ dst = g.dst[q];
+  const int rows = g.rows[q], cols = g.cols[q];
+  const int t = blockIdx.x - g.tile0[q];
+  const int r0 = (t / g.tiles_c[q]) * 64, c0 = (t % g.tiles_c[q]) * 64;
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const int idx = tid + it * 256;          // 64 rows x 8 chunks of 8 elements
+    const int r = idx / 8, c8 = (idx % 8) * 8;
+    if (r0 + r < rows && c0 + c8 < cols) {
+      const uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)(r0 + r) * cols + c0 + c8);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        tile[r][c8 + 2 * i] = (bf16_t)(w[i] & 0xffffu);
+        tile[r][c8 + 2 * i + 1] = (bf16_t)(w[i] >> 16);
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const int idx = tid + it * 256;          // 64 destination rows (source columns) x 8 chunks
+    const int c = idx / 8, r8 = (idx % 8) * 8;
+    if (c0 + c < cols && r0 + r8 < rows) {
+      uint32_t w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) w[i] = (uint32_t)tile[r8 + 2 * i][c] | ((uint32_t)tile[r8 + 2 * i + 1][c] << 16);
+      *reinterpret_cast<uint4*>(dst + (int64_t)(c0 + c) * rows + r0 + r8) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  }
+}
+
 int stream_grid(int64_t items) {
   // enough workgroups to cover 256 CUs several times over, capped so the grid-stride loop does the rest
   int64_t g = (items + 255) / 256;
@@ -198,6 +246,31 @@ hipError_t squared_error_grad(const void* y, const void* target, void* dy, float
     hipLaunchKernelGGL(squared_error_grad_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, stream,
                        static_cast<const float*>(y), static_cast<const float*>(target), static_cast<float*>(dy), scale, n);
   return hipGetLastError();
+}
+
+hipError_t transpose_bf16_grouped(const TransposeItem* items, int count, hipStream_t stream) {
+  if (!items || count < 1) return hipErrorInvalidValue;
+  for (int i0 = 0; i0 < count; i0 += kTransposeMaxItems) {
+    TransposeGroup g{};
+    g.count = count - i0 < kTransposeMaxItems ? count - i0 : kTransposeMaxItems;
+    int64_t tiles = 0;
+    for (int i = 0; i < g.count; ++i) {
+      const TransposeItem& it = items[i0 + i];
+      if (!it.src || !it.dst || it.rows <= 0 || it.cols <= 0 || it.rows % 8 || it.cols % 8 || !aligned16(it.src) ||
+          !aligned16(it.dst))
+        return hipErrorInvalidValue;
+      g.src[i] = static_cast<const bf16_t*>(it.src); g.dst[i] = static_cast<bf16_t*>(it.dst);
+      g.rows[i] = it.rows; g.cols[i] = it.cols;
+      g.tiles_c[i] = ceil_div(it.cols, 64);
+      g.tile0[i] = (int)tiles;
+      tiles += (int64_t)ceil_div(it.rows, 64) * g.tiles_c[i];
+      if (tiles > 0x7fffffff) return hipErrorInvalidValue;
+    }
+    hipLaunchKernelGGL(transpose_bf16_grouped_kernel, dim3((unsigned)tiles), dim3(256), 0, stream, g);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t copy_bytes(const void* in, void* out, int64_t bytes, hipStream_t stream) {

@@ -95,6 +95,23 @@ def test_gemm_data_gradient_form(dtype, M, N, K, epi):
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_data_gradient_through_gelu_on_a_transposed_weight_copy(dtype, M, N, K):
+    """(dY[M,K'] Wt[K',N]) * GELU'(u): the form the bf16 stage issues, reading its transposed copy of the weights
+    (the forward's operand form with the data-gradient epilogue)."""
+    rng = np.random.default_rng(11 * M + N + K)
+    dy, wt = rnd(rng, (M, K), dtype), rnd(rng, (K, N), dtype, 0.1)
+    u = rnd(rng, (M, N), dtype)
+    want = (dy.astype(np.float64) @ wt.astype(np.float64)) * ob.gelu_grad(u.astype(np.float64))
+    DY, WT, U = dev(dy, dtype), dev(wt, dtype), dev(u, dtype)
+    Cc = empty((M, N), dtype)
+    assert B.lib().k2bw_gemm(dtype, 0, 0, 2, M, N, K, DY.data_ptr(), K, WT.data_ptr(), N, Cc.data_ptr(), N, None,
+                             U.data_ptr(), None, 0, None) == 0
+    sync()
+    assert rel(to_host(Cc), want) < TIGHT[dtype]
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
 @pytest.mark.parametrize("M,N,K", [(72, 40, 150), (264, 136, 150), (512, 384, 1000), (4096, 3080, 130)])
 def test_gemm_weight_gradient_form_coalesces_in_place(dtype, M, N, K):
     """G[M,N] (fp32) = X[K,M]^T dY[K,N], then += a second product (Section 3.1 coalescing)."""
