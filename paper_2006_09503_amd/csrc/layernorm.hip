@@ -222,26 +222,31 @@ __global__ __launch_bounds__(kWg) void ln_bwd_kernel(const T* __restrict__ dy, c
 // Backward for long rows (h >= 2048).  With 256 threads the per-column sums of a row of 8192 take 96
 // registers per thread next to the row itself, one wave per SIMD fits, and a CU has too few loads in
 // flight to keep HBM busy.  Here a workgroup has 1024 threads, R = 256, 512 or 1024 of them share a row
-// with one or two 16-byte chunks each, so the sums are 24 or 48 registers, sixteen waves stay resident
-// per CU and U rows per thread are loaded before any arithmetic.  The two row sums share one round of
-// barriers.  Same partial-row layout as the kernel above; the grid is one workgroup per CU at most.
+// with one or two 16-byte chunks each, so the sums are 24 or 48 registers and sixteen waves stay resident
+// per CU.  A workgroup is alone on its CU, so nothing else hides its trips to HBM: the U rows per thread
+// of the next step are requested (and held as loaded, 16 bytes per chunk) before the arithmetic of the
+// current step starts, and the row sums of all U rows share one barrier (the exchange buffer alternates
+// between steps, so a wave that runs ahead cannot overwrite sums that a slower one still reads).
+// Same partial-row layout as the kernel above; the grid is one workgroup per CU at most.
 constexpr int kWgWide = 1024;
 
-// (s1, s2) summed over the R threads that share a row; red: [2][16] floats
-template <int R>
-__device__ __forceinline__ void group_sum2_wide(float& s1, float& s2, float* red, int tid) {
-  s1 = wave_sum(s1);
-  s2 = wave_sum(s2);
-  constexpr int W = R / 64;
-  const int wave = tid >> 6;
-  __syncthreads();
-  if ((tid & 63) == 0) { red[wave] = s1; red[16 + wave] = s2; }
-  __syncthreads();
-  const int first = (wave / W) * W;
-  float a = 0.f, b = 0.f;
-#pragma unroll
-  for (int i = 0; i < W; ++i) { a += red[first + i]; b += red[16 + first + i]; }
-  s1 = a; s2 = b;
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> { uint4 a; };
+template <> struct Raw8<float> { float4 a, b; };
+__device__ __forceinline__ void load_raw(const bf16_t* p, Raw8<bf16_t>& r) { r.a = *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ void load_raw(const float* p, Raw8<float>& r) {
+  r.a = *reinterpret_cast<const float4*>(p);
+  r.b = *reinterpret_cast<const float4*>(p + 4);
+}
+__device__ __forceinline__ void unpack_raw(const Raw8<bf16_t>& r, float (&v)[8]) {
+  v[0] = __uint_as_float(r.a.x << 16); v[1] = __uint_as_float(r.a.x & 0xffff0000u);
+  v[2] = __uint_as_float(r.a.y << 16); v[3] = __uint_as_float(r.a.y & 0xffff0000u);
+  v[4] = __uint_as_float(r.a.z << 16); v[5] = __uint_as_float(r.a.z & 0xffff0000u);
+  v[6] = __uint_as_float(r.a.w << 16); v[7] = __uint_as_float(r.a.w & 0xffff0000u);
+}
+__device__ __forceinline__ void unpack_raw(const Raw8<float>& r, float (&v)[8]) {
+  v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w;
+  v[4] = r.b.x; v[5] = r.b.y; v[6] = r.b.z; v[7] = r.b.w;
 }
 
 template <typename T, int R, int CPT, int U>
@@ -251,10 +256,19 @@ __global__ __launch_bounds__(kWgWide) void ln_bwd_wide_kernel(const T* __restric
                                                               const T* __restrict__ dres, T* __restrict__ dx,
                                                               float* __restrict__ partial, int rows, int h) {
   constexpr int ROWS = kWgWide / R;
-  __shared__ float red[32];
+  constexpr int W = R / 64;   // waves per row
+  // Requesting a step ahead costs 12 registers per chunk next to the 24 of the column sums; the budget of a
+  // 1024-thread workgroup is 128, so it is done for 2-byte elements with one chunk per thread; with one chunk
+  // per thread the sums of the results live in LDS (one 16-byte slot per thread and column quad, touched by
+  // its owner only).
+  constexpr bool kAhead = sizeof(T) == 2 && CPT == 1;
+  constexpr bool kLdsSums = CPT == 1;
+  __shared__ float red[2][2 * U][16];
+  __shared__ float4 osum_lds[kLdsSums ? 2 * kWgWide : 1];
   __shared__ float comb[(ROWS > 1) ? (ROWS - 1) * R * CPT * 8 : 1];
   const int tid = threadIdx.x;
   const int sub = tid % R, rsub = tid / R;
+  const int wave = tid >> 6, first_wave = (wave / W) * W;
   float gsum[CPT][8], bsum[CPT][8], osum[CPT][8], gn[CPT][8];
 #pragma unroll
   for (int c = 0; c < CPT; ++c) {
@@ -264,34 +278,70 @@ __global__ __launch_bounds__(kWgWide) void ln_bwd_wide_kernel(const T* __restric
     for (int i = 0; i < 8; ++i) { gsum[c][i] = 0.f; bsum[c][i] = 0.f; osum[c][i] = 0.f; if (col >= h) gn[c][i] = 0.f; }
   }
   const int n_groups = (rows + ROWS - 1) / ROWS;
-  for (int grp0 = blockIdx.x; grp0 < n_groups; grp0 += U * gridDim.x) {
+  const int stride = U * gridDim.x;
+  // the rows of the step after the one being worked on, as loaded
+  Raw8<T> nx[U][CPT], ndy[U][CPT], nres[U][CPT];
+  float nmean[U], nrstd[U];
+  auto fetch = [&](int grp0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int grp = grp0 + u * gridDim.x;
+      const int row = grp * ROWS + rsub;
+      const bool ok = grp < n_groups && row < rows;
+      nmean[u] = ok ? mean_in[row] : 0.f;
+      nrstd[u] = ok ? rstd_in[row] : 0.f;
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        const int col = (sub + c * R) * 8;
+        if (ok && col < h) {
+          load_raw(x + (int64_t)row * h + col, nx[u][c]);
+          load_raw(dy + (int64_t)row * h + col, ndy[u][c]);
+          if (dres) load_raw(dres + (int64_t)row * h + col, nres[u][c]);
+          else nres[u][c] = Raw8<T>{};
+        } else {
+          nx[u][c] = Raw8<T>{}; ndy[u][c] = Raw8<T>{}; nres[u][c] = Raw8<T>{};
+        }
+      }
+    }
+  };
+  if (kLdsSums) {
+    osum_lds[tid] = make_float4(0.f, 0.f, 0.f, 0.f);
+    osum_lds[kWgWide + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  if (kAhead && (int)blockIdx.x < n_groups) fetch(blockIdx.x);
+  int parity = 0;
+  for (int grp0 = blockIdx.x; grp0 < n_groups; grp0 += stride) {
+    if (!kAhead) fetch(grp0);
     int row[U];
     bool row_ok[U];
     float mean[U], rstd[U];
-    float xh[U][CPT][8], dxh[U][CPT][8], res[U][CPT][8];
+    float xh[U][CPT][8], dxh[U][CPT][8];
+    Raw8<T> res[U][CPT];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int grp = grp0 + u * gridDim.x;
       row[u] = grp * ROWS + rsub;
       row_ok[u] = grp < n_groups && row[u] < rows;
-      mean[u] = row_ok[u] ? mean_in[row[u]] : 0.f;
-      rstd[u] = row_ok[u] ? rstd_in[row[u]] : 0.f;
+      mean[u] = nmean[u];
+      rstd[u] = nrstd[u];
 #pragma unroll
       for (int c = 0; c < CPT; ++c) {
         const int col = (sub + c * R) * 8;
         if (row_ok[u] && col < h) {
-          load8(x + (int64_t)row[u] * h + col, xh[u][c]);
-          load8(dy + (int64_t)row[u] * h + col, dxh[u][c]);
-          if (dres) load8(dres + (int64_t)row[u] * h + col, res[u][c]);
+          unpack_raw(nx[u][c], xh[u][c]);
+          unpack_raw(ndy[u][c], dxh[u][c]);
+          res[u][c] = nres[u][c];
         } else {
 #pragma unroll
           for (int i = 0; i < 8; ++i) { xh[u][c][i] = 0.f; dxh[u][c][i] = 0.f; }
         }
       }
     }
+    if (kAhead && grp0 + stride < n_groups) fetch(grp0 + stride);
+    float s1[U], s2[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float s1 = 0.f, s2 = 0.f;
+      s1[u] = 0.f; s2[u] = 0.f;
 #pragma unroll
       for (int c = 0; c < CPT; ++c) {
         const int col = (sub + c * R) * 8;
@@ -301,15 +351,27 @@ __global__ __launch_bounds__(kWgWide) void ln_bwd_wide_kernel(const T* __restric
             const float dv = dxh[u][c][i];
             xh[u][c][i] = (xh[u][c][i] - mean[u]) * rstd[u];
             dxh[u][c][i] = dv * gn[c][i];
-            s1 += dxh[u][c][i];
-            s2 += dxh[u][c][i] * xh[u][c][i];
+            s1[u] += dxh[u][c][i];
+            s2[u] += dxh[u][c][i] * xh[u][c][i];
             gsum[c][i] += dv * xh[u][c][i];
             bsum[c][i] += dv;
           }
         }
       }
-      group_sum2_wide<R>(s1, s2, red, tid);
-      const float c1 = s1 / (float)h, c2 = s2 / (float)h;
+      s1[u] = wave_sum(s1[u]);
+      s2[u] = wave_sum(s2[u]);
+    }
+    if ((tid & 63) == 0) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) { red[parity][2 * u][wave] = s1[u]; red[parity][2 * u + 1][wave] = s2[u]; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float a = 0.f, b = 0.f;
+#pragma unroll
+      for (int i = 0; i < W; ++i) { a += red[parity][2 * u][first_wave + i]; b += red[parity][2 * u + 1][first_wave + i]; }
+      const float c1 = a / (float)h, c2 = b / (float)h;
       if (row_ok[u]) {
 #pragma unroll
         for (int c = 0; c < CPT; ++c) {
@@ -319,16 +381,31 @@ __global__ __launch_bounds__(kWgWide) void ln_bwd_wide_kernel(const T* __restric
 #pragma unroll
             for (int i = 0; i < 8; ++i) o[i] = rstd[u] * (dxh[u][c][i] - c1 - xh[u][c][i] * c2);
             if (dres) {
+              float rv[8];
+              unpack_raw(res[u][c], rv);
 #pragma unroll
-              for (int i = 0; i < 8; ++i) o[i] += res[u][c][i];
+              for (int i = 0; i < 8; ++i) o[i] += rv[i];
             }
+            if (kLdsSums) {
+              float4 lo = osum_lds[tid], hi = osum_lds[kWgWide + tid];
+              lo.x += o[0]; lo.y += o[1]; lo.z += o[2]; lo.w += o[3];
+              hi.x += o[4]; hi.y += o[5]; hi.z += o[6]; hi.w += o[7];
+              osum_lds[tid] = lo; osum_lds[kWgWide + tid] = hi;
+            } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) osum[c][i] += o[i];
+              for (int i = 0; i < 8; ++i) osum[c][i] += o[i];
+            }
             store8(dx + (int64_t)row[u] * h + col, o);
           }
         }
       }
     }
+    parity ^= 1;
+  }
+  if (kLdsSums) {
+    const float4 lo = osum_lds[tid], hi = osum_lds[kWgWide + tid];
+    osum[0][0] = lo.x; osum[0][1] = lo.y; osum[0][2] = lo.z; osum[0][3] = lo.w;
+    osum[0][4] = hi.x; osum[0][5] = hi.y; osum[0][6] = hi.z; osum[0][7] = hi.w;
   }
   // combine the ROWS sub-rows of this workgroup, then one partial row per workgroup
 #pragma unroll
