@@ -269,7 +269,9 @@ def test_gemm_rejects_shapes_it_cannot_take():
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
 @pytest.mark.parametrize("rows,h", [(150, 72), (130, 128), (1030, 1024), (300, 2560), (260, 4096), (70, 8192),
-                                    (33, 12288), (1030, 2048), (777, 8192)])   # (the last two: several trips per workgroup)
+                                    (33, 12288), (1030, 2048), (777, 8192), (2100, 4096), (4100, 2048)])
+# (from (1030, 2048) on: several trips per workgroup; the last two: three trips with two and four rows per workgroup and
+# trip, so that rows requested a trip ahead are used, and the last trip is ragged)
 def test_layernorm_forward_backward(dtype, rows, h):
     rng = np.random.default_rng(rows + h)
     x = rnd(rng, (rows, h), dtype, 2.0)
