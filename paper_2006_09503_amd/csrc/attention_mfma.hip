@@ -63,6 +63,7 @@ struct Cfg {
   // accumulator file and copies every score to a VGPR and back around the softmax arithmetic,
   // which costs more than the MFMAs.
   static constexpr int kMinWaves = 2;
+  static constexpr bool kDkvVInLds = DH == 128;   // dK/dV kernel: V fragments of the wave's keys in LDS, not registers
 };
 
 // Chunk swizzle per head size (rows are 64 / 128 / 160 / 256 bytes; the LDS has 64 banks of 4 bytes).
@@ -494,6 +495,15 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dkv_mfma_ke
   bf16x8 kf[C::KS], vf[C::KS];
   load_frags<DH>(base + h + (int64_t)j * ld, row_ok, hf, kf);
   load_frags<DH>(base + 2 * h + (int64_t)j * ld, row_ok, hf, vf);
+  // At head size 128 the two accumulators are 128 registers and the K and V fragments of the wave's keys 64 more: with
+  // the scores on top the kernel spilled.  There the V fragments wait in a wave-private piece of LDS (16 bytes per
+  // lane and k-step, read back in the order written: no bank conflicts, no barrier) and are fetched per use.
+  constexpr bool kVInLds = Cfg<DH>::kDkvVInLds;
+  uint4* vstore = smem + 2 * kStageU4 + C::kPadU4 + wave * (C::KS * 64);
+  if (kVInLds) {
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) vstore[ks * 64 + lane] = __builtin_bit_cast(uint4, vf[ks]);
+  }
   f32x16 dk[C::DB], dv[C::DB];
 #pragma unroll
   for (int db = 0; db < C::DB; ++db) { dk[db] = zero16(); dv[db] = zero16(); }
@@ -529,7 +539,8 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dkv_mfma_ke
 #pragma unroll
       for (int ks = 0; ks < C::KS; ++ks) {
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows<DH>(q_lds, qb * 32 + l32, ks, hf), kf[ks], sacc, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows<DH>(do_lds, qb * 32 + l32, ks, hf), vf[ks], dp, 0, 0, 0);
+        const bf16x8 vfr = kVInLds ? __builtin_bit_cast(bf16x8, vstore[ks * 64 + lane]) : vf[ks];
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_rows<DH>(do_lds, qb * 32 + l32, ks, hf), vfr, dp, 0, 0, 0);
       }
       const bool need_mask = (jw0 + 32 > kv_len) || (causal && jw0 + 31 > ib) || (ib + 32 > s);
       if (need_mask) {   // a masked score of -inf gives probability exactly 0
@@ -617,7 +628,8 @@ hipError_t bwd_launch(const AttnDesc& d, const void* qkv, const void* o, const f
                       float* delta, hipStream_t st) {
   using C = Cfg<DH>;
   constexpr size_t lds_dq = (4 * C::kTileU4 + C::kPadU4) * sizeof(uint4);
-  constexpr size_t lds_dkv = (2 * (2 * C::kTileU4 + 2 * kTile / 4) + C::kPadU4) * sizeof(uint4);
+  constexpr size_t lds_dkv = (2 * (2 * C::kTileU4 + 2 * kTile / 4) + C::kPadU4 + (C::kDkvVInLds ? kWaves * C::KS * 64 : 0)) * sizeof(uint4);
+  static_assert(lds_dkv <= 160 * 1024, "LDS of a CU");
   static bool done_dq = false, done_dkv = false;
   hipError_t e = set_lds(attn_dq_mfma_kernel<DH>, lds_dq, &done_dq);
   if (e != hipSuccess) return e;
