@@ -217,6 +217,49 @@ __device__ __forceinline__ void block_column_sums(const f32x16 (&acc)[Cfg<DH>::D
   }
 }
 
+// Rows of a result held as acc[db][r] (lane % 32 = row, registers = head columns db*32 + 8*(r/4) + 4*hf + r%4),
+// times `scale`, to out[row][0 .. DH) (bf16, `ld` elements between rows; `out` is row 0 of this wave's 32 rows, of
+// which the first rows_valid exist).  Stored as they lie in the registers, a lane writes 8-byte pieces and one store
+// instruction touches 32 rows with 16 bytes each: measured, those stores were two thirds of what the dK/dV kernel costs
+// beyond its loop (8.5 of 12.5 us per workgroup at head size 128).  So the rows pass through a wave-private piece
+// of LDS (rows 16 bytes apart from a multiple of 256: the 8-byte writes of 32 rows spread over the banks) and
+// leave with 16 bytes per lane along a row.  No barrier: the piece belongs to the wave, whose LDS operations
+// complete in order.  `strip`: 32 * (2 * DH + 16) bytes.
+template <int DH>
+constexpr int out_strip_u4() { return 32 * (2 * DH + 16) / 16; }
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+template <int DH>
+__device__ __forceinline__ void store_rows(const f32x16 (&acc)[Cfg<DH>::DB], float scale, uint4* strip, bf16_t* out, int64_t ld,
+                                           int rows_valid, int lane) {
+  using C = Cfg<DH>;
+  constexpr int STRIDE = 2 * DH + 16;   // bytes
+  char* w = reinterpret_cast<char*>(strip);
+  const int l32 = lane & 31, hf = lane >> 5;
+#pragma unroll
+  for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int d = db * 32 + 8 * g + 4 * hf;
+      if (d < DH)
+        *reinterpret_cast<uint2*>(w + l32 * STRIDE + d * 2) =
+            pack4f(acc[db][4 * g] * scale, acc[db][4 * g + 1] * scale, acc[db][4 * g + 2] * scale, acc[db][4 * g + 3] * scale);
+    }
+  wave_lds_sync();
+  constexpr int TOTAL = 32 * C::CH;   // 16-byte chunks of the 32 rows
+#pragma unroll
+  for (int it = 0; it < (TOTAL + 63) / 64; ++it) {
+    const int L = it * 64 + lane;
+    const int row = L / C::CH, ch = L % C::CH;
+    if (L < TOTAL && row < rows_valid)
+      *reinterpret_cast<uint4*>(out + row * ld + ch * 8) = *reinterpret_cast<const uint4*>(w + row * STRIDE + ch * 16);
+  }
+  wave_lds_sync();   // the strip may be written again
+}
+
 // ------------------------------------------------------------------------------------------------
 // forward
 template <int DH>
@@ -323,19 +366,10 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_fwd_mfma_ke
   }
 
   const float l_tot = l_i + __shfl_xor(l_i, 32, 64);
-  if (i >= s) return;
-  const float inv = 1.0f / l_tot;
-  bf16_t* orow = o + ((int64_t)n * s + i) * h + head * DH;
-#pragma unroll
-  for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int d = db * 32 + 8 * g + 4 * hf;
-      if (d < DH)
-        *reinterpret_cast<uint2*>(orow + d) = pack4f(oacc[db][4 * g] * inv, oacc[db][4 * g + 1] * inv,
-                                                     oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv);
-    }
-  if (hf == 0) lse[((int64_t)n * a + head) * s + i] = m_i * scale + logf(l_tot);
+  __syncthreads();   // every wave is done with the K / V tiles, whose LDS the output strips re-use
+  const float inv = 1.0f / l_tot;   // (rows past the sequence: never stored)
+  store_rows<DH>(oacc, inv, smem + wave * out_strip_u4<DH>(), o + ((int64_t)n * s + iw0) * h + head * DH, h, s - iw0, lane);
+  if (i < s && hf == 0) lse[((int64_t)n * a + head) * s + i] = m_i * scale + logf(l_tot);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -443,22 +477,13 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dq_mfma_ker
       for (int kk = 0; kk < 4; ++kk)
         dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_cols<DH>(k_lds, db * 32, kk, lane), dsb[kk], dq[db], 0, 0, 0);
   }
+  __syncthreads();   // every wave is done with the K / V tiles
   if (colsum) {   // rows past the end of the sequence hold zeros
-    __syncthreads();   // every wave is done with the K / V tiles
     float* row = colsum + ((int64_t)n * gridDim.z + blk) * ld + head * DH;
     block_column_sums<DH>(dq, scale, reinterpret_cast<float*>(smem), row, tid, lane, wave);
+    __syncthreads();   // ... and with the partial rows of the sums
   }
-  if (!row_ok) return;
-  bf16_t* out = dqkv + ((int64_t)n * s + i) * ld + head * DH;
-#pragma unroll
-  for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int d = db * 32 + 8 * g + 4 * hf;
-      if (d < DH)
-        *reinterpret_cast<uint2*>(out + d) = pack4f(dq[db][4 * g] * scale, dq[db][4 * g + 1] * scale,
-                                                    dq[db][4 * g + 2] * scale, dq[db][4 * g + 3] * scale);
-    }
+  store_rows<DH>(dq, scale, smem + wave * out_strip_u4<DH>(), dqkv + ((int64_t)n * s + iw0) * ld + head * DH, ld, s - iw0, lane);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -577,28 +602,19 @@ __global__ __launch_bounds__(kThreads, Cfg<DH>::kMinWaves) void attn_dkv_mfma_ke
       }
     }
   }
+  __syncthreads();   // every wave is done with the Q / dO tiles
   if (colsum) {   // masked and non-existent keys hold zeros
     float* row = colsum + ((int64_t)n * gridDim.z + blk) * ld + head * DH;
     float* red = reinterpret_cast<float*>(smem);
-    __syncthreads();
     block_column_sums<DH>(dk, scale, red, row + h, tid, lane, wave);
     __syncthreads();
     block_column_sums<DH>(dv, 1.0f, red, row + 2 * h, tid, lane, wave);
+    __syncthreads();
   }
-  if (!row_ok) return;
-  bf16_t* outk = dqkv + ((int64_t)n * s + j) * ld + h + head * DH;
-  bf16_t* outv = outk + h;
-#pragma unroll
-  for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int d = db * 32 + 8 * g + 4 * hf;
-      if (d < DH) {
-        *reinterpret_cast<uint2*>(outk + d) = pack4f(dk[db][4 * g] * scale, dk[db][4 * g + 1] * scale,
-                                                     dk[db][4 * g + 2] * scale, dk[db][4 * g + 3] * scale);
-        *reinterpret_cast<uint2*>(outv + d) = pack4f(dv[db][4 * g], dv[db][4 * g + 1], dv[db][4 * g + 2], dv[db][4 * g + 3]);
-      }
-    }
+  bf16_t* outk = dqkv + ((int64_t)n * s + jw0) * ld + h + head * DH;
+  uint4* strip = smem + wave * out_strip_u4<DH>();
+  store_rows<DH>(dk, scale, strip, outk, ld, s - jw0, lane);
+  store_rows<DH>(dv, 1.0f, strip, outk + h, ld, s - jw0, lane);
 }
 
 template <typename K>
@@ -613,7 +629,9 @@ hipError_t set_lds(K kern, size_t bytes, bool* done) {
 template <int DH>
 hipError_t fwd_launch(const AttnDesc& d, const void* qkv, void* o, float* lse, hipStream_t st) {
   using C = Cfg<DH>;
-  constexpr size_t lds = (4 * C::kTileU4 + C::kPadU4) * sizeof(uint4);
+  constexpr size_t lds_out = (size_t)kWaves * out_strip_u4<DH>() * sizeof(uint4);   // the output strips re-use the tiles' LDS
+  constexpr size_t lds_tiles = (4 * C::kTileU4 + C::kPadU4) * sizeof(uint4);
+  constexpr size_t lds = lds_tiles > lds_out ? lds_tiles : lds_out;
   static bool done = false;
   hipError_t e = set_lds(attn_fwd_mfma_kernel<DH>, lds, &done);
   if (e != hipSuccess) return e;
@@ -627,8 +645,11 @@ template <int DH>
 hipError_t bwd_launch(const AttnDesc& d, const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
                       float* delta, hipStream_t st) {
   using C = Cfg<DH>;
-  constexpr size_t lds_dq = (4 * C::kTileU4 + C::kPadU4) * sizeof(uint4);
-  constexpr size_t lds_dkv = (2 * (2 * C::kTileU4 + 2 * kTile / 4) + C::kPadU4 + (C::kDkvVInLds ? kWaves * C::KS * 64 : 0)) * sizeof(uint4);
+  constexpr size_t lds_out = (size_t)kWaves * out_strip_u4<DH>() * sizeof(uint4);   // the output strips re-use the tiles' LDS
+  constexpr size_t lds_dq_tiles = (4 * C::kTileU4 + C::kPadU4) * sizeof(uint4);
+  constexpr size_t lds_dq = lds_dq_tiles > lds_out ? lds_dq_tiles : lds_out;
+  constexpr size_t lds_dkv_tiles = (2 * (2 * C::kTileU4 + 2 * kTile / 4) + C::kPadU4 + (C::kDkvVInLds ? kWaves * C::KS * 64 : 0)) * sizeof(uint4);
+  constexpr size_t lds_dkv = lds_dkv_tiles > lds_out ? lds_dkv_tiles : lds_out;
   static_assert(lds_dkv <= 160 * 1024, "LDS of a CU");
   static bool done_dq = false, done_dkv = false;
   hipError_t e = set_lds(attn_dq_mfma_kernel<DH>, lds_dq, &done_dq);
