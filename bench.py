@@ -41,34 +41,34 @@ TRAFFIC_BYTES_PER_LAUNCH = {
         # grouped weight-gradient GEMM: the 8 products of the stage's 2 layers over 4 microbatches' tokens each
         # (reduction length 8192): L2-miss read traffic 0.9..1.0e11 (the operand panels of products this size pass
         # through the 4 MB L2 of every XCD many times; the counter sees what misses L2, whether HBM or the
-        # memory-side cache serves it; two profiling runs of the same build read 8.75e10 and 9.93e10) + 6.44e9
+        # memory-side cache serves it; profiling runs of the same build read 8.75e10 .. 9.93e10) + 6.44e9
         # written.  Algorithmic minimum 1.72e10: operands once + fp32 accumulator read-modify-write.
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 1.0575e+11,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.9278e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.9219e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 9.3845e+10,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.9213e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.9221e+09,
         # forward projections and the data gradients (the latter on the transposed weight copy): averages
         # over the six shapes this instance serves
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 1.2944e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 1.2348e+09,
     },
     "C4": {
         # (activation recomputation: the forward GEMMs run twice per microbatch; 4 layers x 4 products over 4 passes per
         # weight-gradient launch, reduction length 16384)
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 7.7594e+10,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 7.4494e+10,
         "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.0825e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.0750e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 6.5736e+08,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.0757e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 6.4765e+08,
     },
     "C2": {
         # grouped weight-gradient GEMM (the 24 products of the stage's 6 layers over 4 microbatches' tokens each,
         # reduction length 16384): FETCH_SIZE x 1.997 (copy-kernel factor) + WRITE_SIZE x 1.000; algorithmic minimum
         # 3.825e9 (operands once + fp32 accumulator read-modify-write)
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 4.3773e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 4.3753e+09,
         # the other GEMM instances (averages over the shapes each serves)
         "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.2830e+08,
         "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.2617e+08,
         "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, false, 0>": 8.6542e+07,
-        "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, true, 0>": 8.0691e+07,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 7.3568e+07,
+        "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, true, 0>": 8.0733e+07,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 7.3567e+07,
     },
 }
 
