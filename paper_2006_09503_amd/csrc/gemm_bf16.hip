@@ -1194,6 +1194,8 @@ bool segments_ok(const GemmDesc& d) {
 
 void gemm_bf16_set_tile(int id) { g_tile_override = id; }
 
+int gemm_compute_units() { return compute_units(); }
+
 // Name of the kernel instance a (grouped) call will run, in the form profilers print template
 // arguments, so that event timings can be matched with a kernel trace.
 void gemm_bf16_kernel_name(const GemmDesc* d, int count, char* out, size_t cap) {

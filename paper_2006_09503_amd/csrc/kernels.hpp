@@ -56,6 +56,8 @@ hipError_t gemm(const GemmDesc& d, hipStream_t stream);
 // 1..4 independent GEMMs of the same form, epilogue and dtype; bf16 runs them in one launch.
 constexpr int kGemmMaxGroup = 24;   // GEMMs of one form and epilogue that may share a launch
 hipError_t gemm_grouped(const GemmDesc* d, int count, hipStream_t stream);
+// CUs of the current device (a launch of T tiles takes ceil(T / CUs) rounds of one tile per CU).
+int gemm_compute_units();
 // Name (with template arguments, as a kernel trace prints it) of the kernel such a call runs.
 void gemm_kernel_name(const GemmDesc* d, int count, char* out, size_t cap);
 

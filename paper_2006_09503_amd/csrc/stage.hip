@@ -414,14 +414,30 @@ hipError_t flush_wgrad(stage2bw* st) {
     product(A.o, h, st->dx1[l], (int64_t)T * h * E, h, st->G + o.wo);
     product(A.a, h, st->dqkv[l], (int64_t)T * 3 * h * E, 3 * h, st->G + o.wqkv);
   }
-  for (size_t i0 = 0; i0 < wg.size(); i0 += kGemmMaxGroup) {
-    const int cnt = (int)std::min<size_t>(kGemmMaxGroup, wg.size() - i0);
+  // One launch per run of products with at least kMinRounds rounds of 256x256 tiles on the chip's CUs (what is left
+  // at the end joins the last run).  Shared launches exist to spare small products their ramp, drain and partial
+  // last round; beyond a few rounds a longer launch is slower, not faster: the 32 tiles that run on an XCD at a time
+  // share operand panels in its L2 only while they stay within some twenty K steps of each other, they drift apart
+  // over the rounds, and nothing but the end of a launch brings them back in step (weight-gradient time per batch
+  // on one box, C5: 96 rounds in one launch 390 ms, launches of 16 rounds 358 ms; C4: 48 rounds 184 ms, 8 rounds
+  // 168 ms; thresholds of 4 and 16 rounds measure within 1 % of 8).
+  constexpr int64_t kMinRounds = 8;
+  const int64_t min_tiles = kMinRounds * gemm_compute_units();
+  auto tiles_of = [](const GemmDesc& d) { return (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256); };
+  for (size_t i0 = 0; i0 < wg.size();) {
+    size_t i1 = i0;
+    int64_t tiles = 0, rest = 0;
+    while (i1 < wg.size() && i1 - i0 < (size_t)kGemmMaxGroup && tiles < min_tiles) tiles += tiles_of(wg[i1++]);
+    for (size_t i = i1; i < wg.size(); ++i) rest += tiles_of(wg[i]);
+    if (rest < min_tiles / 2 && wg.size() - i0 <= (size_t)kGemmMaxGroup) i1 = wg.size();
+    const int cnt = (int)(i1 - i0);
     double flops = 0.0;
     for (int i = 0; i < cnt; ++i) flops += 2.0 * wg[i0 + i].M * (double)wg[i0 + i].N * wg[i0 + i].K;
     char wg_name[96] = "";
     if (st->timing) gemm_kernel_name(&wg[i0], cnt, wg_name, sizeof(wg_name));
     hipError_t e = timed(st, STAGE_K_GEMM_WGRAD, wg_name, flops, 0.0, [&] { return gemm_grouped(&wg[i0], cnt, st->cur); });
     if (e != hipSuccess) return e;
+    i0 = i1;
   }
   // the sets are free again once this launch has run
   if (!c.recompute) {
