@@ -82,9 +82,9 @@ typedef struct {
                         /* reduction range j*T (the accumulator of Section 3.1 is then read and       */
                         /* written once per j microbatches; a group never crosses a batch end, so the */
                         /* coalesced sum is the same up to the order of fp32 additions).  0: the      */
-                        /* library's choice (4); 1..8: at most this many.  Always 1 in fp32 mode and   */
-                        /* when b*s is not a multiple of 64.  Each unit above 1 keeps one more set of  */
-                        /* activations alive (with recompute: one more scratch set)                    */
+                        /* library's choice (4; 8 if b*s <= 2048); 1..8: at most this many.  Always 1  */
+                        /* in fp32 mode and when b*s is not a multiple of 64.  Each unit above 1 keeps */
+                        /* one more set of activations alive (with recompute: one more scratch set)    */
 } stage_config_t;
 
 /*

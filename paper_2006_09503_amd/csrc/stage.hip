@@ -663,10 +663,12 @@ int stage_create(const stage_config_t* cfg, const float* init_weights_host, void
   ALLOC(st->adam_m, P * 4, nullptr);
   if (cfg->optimizer == STAGE_OPT_ADAM) ALLOC(st->adam_v, P * 4, nullptr);
 
-  // Backward passes per grouped weight-gradient launch: the caller's choice, else 4; never more than m
-  // (a group stays inside its batch).  The segmented product exists in the bf16 ring kernels only, whose
+  // Backward passes per grouped weight-gradient launch: the caller's choice, else what brings the reduction
+  // range to 16384 tokens (4 passes of 4096 tokens, 8 of 2048 or fewer: measured, 8 instead of 4 passes of 2048
+  // are +3 % on the weight-gradient launches, 8 instead of 4 of 4096 nothing); never more than m (a group stays
+  // inside its batch).  The segmented product exists in the bf16 ring kernels only, whose
   // K tiles must divide a pass's tokens, and a set's number must fit the kernel's 4-bit fields.
-  int j = cfg->wgrad_group > 0 ? cfg->wgrad_group : 4;
+  int j = cfg->wgrad_group > 0 ? cfg->wgrad_group : (T <= 2048 ? 8 : 4);
   if (j > cfg->m) j = cfg->m;
   if (st->dtype != kBF16 || T % 64 != 0) j = 1;
   if (!cfg->recompute && j > 1 && cfg->max_inflight + j - 1 > 16) j = std::max(1, 17 - cfg->max_inflight);
