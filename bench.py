@@ -38,19 +38,19 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # set or kernel that was not profiled reports null.
 TRAFFIC_BYTES_PER_LAUNCH = {
     "C5": {
-        # weight-gradient GEMM launches: the 8 products of the stage's 2 layers over 4 microbatches' tokens each
-        # (reduction length 8192) go out in 6 launches of 16 rounds of tiles (FC2; FC1; out-projection + QKV, per
-        # layer); average per launch: L2-miss read traffic 8.67e9 (the operand panels of products this size pass
+        # weight-gradient GEMM launches: the 8 products of the stage's 2 layers over 8 microbatches' tokens each
+        # (reduction length 16384) go out in 6 launches of 16 rounds of tiles (FC2; FC1; out-projection + QKV, per
+        # layer); average per launch: L2-miss read traffic 1.65e10 (the operand panels of products this size pass
         # through the 4 MB L2 of every XCD once per block of 32 tiles; the counter sees what misses L2, whether HBM or
-        # the memory-side cache serves it) + 1.07e9 written.  Algorithmic minimum 2.86e9: operands once + fp32
-        # accumulator read-modify-write.  (All 8 products in one launch of 96 rounds: 8.75e10 .. 9.93e10 per group
-        # instead of 5.85e10, see the stage's flush of pending products.)
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 9.7462e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.9218e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.9260e+09,
+        # the memory-side cache serves it) + 1.07e9 written.  Algorithmic minimum 3.58e9: operands once + fp32
+        # accumulator read-modify-write.  (4 microbatches and all 8 products in one launch of 96 rounds: 8.75e10 ..
+        # 9.93e10 per 4 microbatches instead of 5.3e10, see the stage's flush of pending products.)
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 1.7609e+10,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.9214e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.9309e+09,
         # forward projections and the data gradients (the latter on the transposed weight copy): averages
         # over the six shapes this instance serves
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 1.2577e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 1.2628e+09,
     },
     "C4": {
         # (activation recomputation: the forward GEMMs run twice per microbatch; 4 layers x 4 products over 4 passes,
