@@ -87,7 +87,7 @@ hipError_t colsum_finalize(const float* partial, int parts, int n, float* out, b
 
 // Grouped forms: column sums of up to 4 matrices [rows, n_i] in one launch into
 // partial[parts][sum n_i] (segment i starts at column sum_{j<i} n_j), and the final reduction
-// of up to 8 (partial, out) pairs in one launch.
+// of up to kFinalizeMaxItems (partial, out) pairs in one launch (n and ld multiples of 4, pointers 16-byte aligned).
 struct ColsumItem { const void* y; int n; int ld; };
 hipError_t colsum_partial_grouped(const ColsumItem* items, int count, int rows, float* partial, int* parts_out,
                                   int* total_cols_out, int dtype, hipStream_t stream);

@@ -540,36 +540,42 @@ __global__ __launch_bounds__(kWg) void colsum_partial_grouped_kernel(ColsumGroup
   }
 }
 
-// out_s[n_s] (+)= sum over parts_s rows of partial_s, for up to kFinalizeMaxItems segments in one launch
+// out_s[n_s] (+)= sum over parts_s rows of partial_s, for up to kFinalizeMaxItems segments in one launch.
+// A workgroup owns 64 columns: 16 threads x 16 bytes cover 256 contiguous bytes of a row (whole cache lines; with
+// one float per thread a workgroup used half of every line it touched), 16 such groups walk the rows.
 __global__ __launch_bounds__(kWg) void colsum_finalize_grouped_kernel(FinalizeGroup g) {
-  __shared__ float red[16][17];
+  __shared__ float4 red[16][17];
   int sidx = 0;
   for (int q = 1; q < g.count; ++q)
     if ((int)blockIdx.x >= g.block0[q]) sidx = q;
   const float* partial = g.partial[sidx];
   const int parts = g.parts[sidx], n = g.n[sidx], ld = g.ld[sidx];
   const int c = threadIdx.x & 15, pl = threadIdx.x >> 4;
-  const int col = (blockIdx.x - g.block0[sidx]) * 16 + c;
-  float s = 0.f;
+  const int col = ((blockIdx.x - g.block0[sidx]) * 16 + c) * 4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   if (col < n) {
     int p = pl;
     for (; p + 7 * 16 < parts; p += 8 * 16) {
-      float v[8];
+      float4 v[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = partial[(int64_t)(p + i * 16) * ld + col];
+      for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const float4*>(partial + (int64_t)(p + i * 16) * ld + col);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) s += v[i];
+      for (int i = 0; i < 8; ++i) { s.x += v[i].x; s.y += v[i].y; s.z += v[i].z; s.w += v[i].w; }
     }
-    for (; p < parts; p += 16) s += partial[(int64_t)p * ld + col];
+    for (; p < parts; p += 16) {
+      const float4 v = *reinterpret_cast<const float4*>(partial + (int64_t)p * ld + col);
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
   }
   red[pl][c] = s;
   __syncthreads();
   if (pl == 0 && col < n) {
-    float t = 0.f;
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) t += red[i][c];
-    float* out = g.out[sidx];
-    out[col] = g.accumulate ? out[col] + t : t;
+    for (int i = 0; i < 16; ++i) { const float4 v = red[i][c]; t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w; }
+    float4* out = reinterpret_cast<float4*>(g.out[sidx] + col);
+    if (g.accumulate) { const float4 o = *out; t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w; }
+    *out = t;
   }
 }
 
@@ -755,9 +761,10 @@ hipError_t colsum_finalize_grouped(const FinalizeItem* items, int count, bool ac
   for (int i = 0; i < count; ++i) {
     const FinalizeItem& it = items[i];
     if (!it.partial || !it.out || it.parts <= 0 || it.n <= 0 || it.ld < it.n) return hipErrorInvalidValue;
+    if (it.n % 4 || it.ld % 4 || !aligned16(it.partial) || !aligned16(it.out)) return hipErrorInvalidValue;   // 16-byte accesses
     g.partial[i] = it.partial; g.parts[i] = it.parts; g.n[i] = it.n; g.ld[i] = it.ld; g.out[i] = it.out;
     g.block0[i] = blocks;
-    blocks += ceil_div(it.n, 16);
+    blocks += ceil_div(it.n, 64);
   }
   hipLaunchKernelGGL(colsum_finalize_grouped_kernel, dim3(blocks), dim3(kWg), 0, stream, g);
   return hipGetLastError();
