@@ -45,31 +45,31 @@ TRAFFIC_BYTES_PER_LAUNCH = {
         # the memory-side cache serves it) + 1.07e9 written.  Algorithmic minimum 3.58e9: operands once + fp32
         # accumulator read-modify-write.  (4 microbatches and all 8 products in one launch of 96 rounds: 8.75e10 ..
         # 9.93e10 per 4 microbatches instead of 5.3e10, see the stage's flush of pending products.)
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 1.7609e+10,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.9214e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.9309e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 1.7393e+10,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.9274e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.9391e+09,
         # forward projections and the data gradients (the latter on the transposed weight copy): averages
         # over the six shapes this instance serves
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 1.2628e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 1.2530e+09,
     },
     "C4": {
         # (activation recomputation: the forward GEMMs run twice per microbatch; 4 layers x 4 products over 4 passes,
         # reduction length 16384, in 6 weight-gradient launches of 8 rounds)
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 7.5042e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 7.5499e+09,
         "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.0825e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.0752e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 6.5524e+08,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.0777e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 6.5386e+08,
     },
     "C2": {
         # grouped weight-gradient GEMM (the 24 products of the stage's 6 layers over 4 microbatches' tokens each,
         # reduction length 16384): FETCH_SIZE x 1.997 (copy-kernel factor) + WRITE_SIZE x 1.000; algorithmic minimum
         # 3.825e9 (operands once + fp32 accumulator read-modify-write)
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 4.3753e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 4.3746e+09,
         # the other GEMM instances (averages over the shapes each serves)
         "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.2830e+08,
         "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.2617e+08,
         "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, false, 0>": 8.6542e+07,
-        "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, true, 0>": 8.0733e+07,
+        "gemm_bf16_ring_kernel<128, 128, 32, 64, 64, 4, false, true, 0>": 8.0722e+07,
         "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 7.3567e+07,
     },
 }
