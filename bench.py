@@ -45,20 +45,20 @@ TRAFFIC_BYTES_PER_LAUNCH = {
         # the memory-side cache serves it) + 1.07e9 written.  Algorithmic minimum 3.58e9: operands once + fp32
         # accumulator read-modify-write.  (4 microbatches and all 8 products in one launch of 96 rounds: 8.75e10 ..
         # 9.93e10 per 4 microbatches instead of 5.3e10, see the stage's flush of pending products.)
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 1.7393e+10,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.9274e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.9391e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 1.7651e+10,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.9206e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.9351e+09,
         # forward projections and the data gradients (the latter on the transposed weight copy): averages
         # over the six shapes this instance serves
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 1.2530e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 1.2583e+09,
     },
     "C4": {
         # (activation recomputation: the forward GEMMs run twice per microbatch; 4 layers x 4 products over 4 passes,
         # reduction length 16384, in 6 weight-gradient launches of 8 rounds)
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 7.5499e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.0825e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.0777e+09,
-        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 6.5386e+08,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, true, false, 3>": 7.5253e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 2>": 1.0826e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 1>": 1.0772e+09,
+        "gemm_bf16_ring_kernel<256, 256, 128, 64, 32, 4, false, false, 0>": 6.6144e+08,
     },
     "C2": {
         # grouped weight-gradient GEMM (the 24 products of the stage's 6 layers over 4 microbatches' tokens each,
@@ -286,10 +286,11 @@ def main():
                     "measurement: recomputation frees the memory for a larger b, Section 4.1 and the appendix)")
     ap.add_argument("--stages", type=int, default=1, help="d > 1: a d-stage 2BW pipeline of such stages in this process, one "
                     "HIP stream per stage, squared-error loss behind the last (an extra measurement, not the headline)")
-    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
+    ap.add_argument("--streams", type=int, default=0, choices=(0, 1, 2),
                     help="2: backward passes and updates on a stream of their own, so that the forward and backward "
                          "passes of different microbatches overlap (the per-kernel timing region always runs on one "
-                         "stream: each kernel then has the GPU to itself)")
+                         "stream: each kernel then has the GPU to itself); 0 (default): what the workload's shape "
+                         "recommends (two streams unless every projection gives each CU a 256x256 tile)")
     ap.add_argument("--wgrad-group", type=int, default=None, help="override how many microbatches' weight-gradient "
                     "products one launch covers (reduction length j*T; default: the library's choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -322,6 +323,8 @@ def main():
         cfg = cfg.with_(microbatch=args.microbatch)
     if args.wgrad_group is not None:
         cfg = cfg.with_(wgrad_group=args.wgrad_group)
+    if args.streams == 0:
+        args.streams = cfg.recommended_streams
     p, m = cfg.max_inflight, cfg.m
     K, W = args.steps, args.warmup
     assert K >= 1 and W >= 2, "two warm-up batches are needed before the version rule leaves version 0"
