@@ -24,8 +24,8 @@ class Mi355xProfile:
     n_gpus: int = 8
     gpus_per_server: int = 8
     microbatch_sizes: List[int] = field(default_factory=lambda: [8, 16, 32])
-    # one block, forward + backward, two streams: 22.39 / 43.4 / 76.08 ms per step of m = 8 microbatches x 6 blocks
-    block_time_s: List[float] = field(default_factory=lambda: [22.39e-3 / 48, 43.4e-3 / 48, 76.08e-3 / 48])
+    # one block, forward + backward, two streams: 21.2 / 42.5 / 72.9 ms per step of m = 8 microbatches x 6 blocks
+    block_time_s: List[float] = field(default_factory=lambda: [21.2e-3 / 48, 42.5e-3 / 48, 72.9e-3 / 48])
     weight_bytes: float = 0.0            # one bf16 version
     state_bytes: float = 0.0             # fp32 master, Adam m and v, gradient accumulator: 16 B / parameter
     act_bytes_per_sample: float = 0.0    # stash of the whole model per sample: 18.9 MB per block (0.9 GB per slot of 6 blocks x 8)
@@ -35,7 +35,7 @@ class Mi355xProfile:
     bw_low: float = 50e9                 # one 400 Gb/s NIC per GPU between servers
     memory_capacity: float = 288e9
     global_batch: int = 512
-    c_extra: float = 4.0 / 3.0           # measured here: 1.31 .. 1.36
+    c_extra: float = 4.0 / 3.0           # measured here: 1.28 .. 1.35
 
     def __post_init__(self):
         p = PARAMS_PER_BLOCK * self.n_blocks
