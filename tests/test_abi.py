@@ -49,6 +49,15 @@ def test_param_counts_of_the_workload_shapes():
         assert binding.stage_param_count(cfg) == n == synth.param_count(cfg)
 
 
+def test_stream_recommendation_follows_the_smallest_projection():
+    """Two streams while the smallest projection (T x h outputs) leaves CUs without a 256x256 tile, one from 256
+    tiles on: 16 x 4, 16 x 10, 16 x 16 and 8 x 32 tiles at the four large workload shapes."""
+    want = {"C2": 2, "C3": 2, "C4": 1, "C5": 1}
+    for name, n in want.items():
+        assert synth.PRESETS[name].recommended_streams == n
+    assert synth.PRESETS["C2"].with_(microbatch=32).recommended_streams == 1   # 64 x 4 tiles
+
+
 @pytest.mark.parametrize("bad", [dict(hidden=100), dict(n_heads=3), dict(m=1, max_inflight=2), dict(mask_mode=5),
                                  dict(precision=7), dict(n_layers=0), dict(ffn=12), dict(hidden=16, n_heads=4),
                                  dict(beta1=1.0), dict(recompute=2),
