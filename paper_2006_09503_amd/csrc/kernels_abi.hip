@@ -21,7 +21,7 @@ bool dtype_ok(int d) { return d == kF32 || d == kBF16; }
 constexpr int kStaticParts = 64;            // == colsum_max_parts()
 constexpr int kStaticMaxCols = 32768;
 constexpr int kStaticMaxDevices = 64;
-__device__ __align__(256) float scratch[kStaticParts * kStaticMaxCols];
+static __device__ __align__(256) float scratch[kStaticParts * kStaticMaxCols];
 float* scratch_ptr[kStaticMaxDevices] = {};  // per device: the address of that device's copy of `scratch`
 }  // namespace
 
