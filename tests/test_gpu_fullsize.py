@@ -87,3 +87,38 @@ def test_first_microbatch_at_full_width_against_stored_oracle_samples(workload):
     r = bench.prefix_check(workload, synth.PRESETS[workload], 0)
     print(workload, r, flush=True)
     assert r is not None and r["ok"], r
+
+
+def test_weight_gradient_of_eight_passes_at_full_width():
+    """The launch the largest workload spends a third of its time in: the FC2 weight gradient summed over eight
+    backward passes inside one product (32768 x 8192 outputs, reduction range 8 x 2048 tokens in eight buffers), on top
+    of an accumulator.  Checked on sampled outputs -- the four corners, the seams of the 256 x 256 tiles and random
+    positions -- against fp64 dot products of the same bf16 inputs.  Bar 1e-5 relative L2 over the samples: fp32
+    accumulation over 1024 MFMA steps of random-signed terms leaves about eps * sqrt(1024 / 2) = 1.4e-6."""
+    import torch
+    from paper_2006_09503_amd import binding as B
+    L = B.lib()
+    M, N, T, n_seg = 32768, 8192, 2048, 8
+    g = torch.Generator(device="cuda").manual_seed(7)
+    X = torch.randn((n_seg, T, M), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    DY = (torch.randn((n_seg, T, N), generator=g, device="cuda", dtype=torch.float32) * 0.1).to(torch.bfloat16)
+    G0 = torch.randn((M, N), generator=g, device="cuda", dtype=torch.float32)
+    G = G0.clone()
+    ia = np.array([5, 2, 7, 0, 1, 6, 3, 4], dtype=np.uint8)
+    ib = np.array([0, 1, 2, 3, 4, 5, 6, 7], dtype=np.uint8)
+    assert L.k2bw_gemm_wgrad_segmented(M, N, T, n_seg, X.data_ptr(), M, T * M * 2, ia.ctypes.data, DY.data_ptr(), N,
+                                       T * N * 2, ib.ctypes.data, G.data_ptr(), N, 1, None) == 0
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(11)
+    rows = np.concatenate([[0, M - 1, 255, 256, 16383, 16384], rng.integers(0, M, 58)])
+    cols = np.concatenate([[0, N - 1, 255, 256, 4095, 4096], rng.integers(0, N, 58)])
+    # (gathering the sampled columns is indexing; the sums are numpy fp64)
+    xs = X[:, :, torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)     # [seg, T, 64]
+    dys = DY[:, :, torch.from_numpy(cols).cuda()].float().cpu().numpy().astype(np.float64)   # [seg, T, 64]
+    want = sum(xs[a].T @ dys[b] for a, b in zip(ia, ib))                                      # [64, 64]
+    idx_r, idx_c = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
+    got = G[idx_r][:, idx_c].cpu().numpy().astype(np.float64)
+    want = want + G0[idx_r][:, idx_c].cpu().numpy().astype(np.float64)
+    err = np.linalg.norm(got - want) / np.linalg.norm(want)
+    print(f"eight-pass weight gradient at {M} x {N} x {n_seg * T}: rel L2 over {got.size} samples {err:.2e}", flush=True)
+    assert err < 1e-5
